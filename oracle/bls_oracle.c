@@ -1,0 +1,483 @@
+/*
+ * CPU oracle for the distributed embedding-lookup path.  TEST INFRASTRUCTURE ONLY.
+ *
+ * Plain, slow, single-threaded C that states what the path computes, written from
+ * the paper's description of the problem and sharing nothing with the HIP library.
+ * Only the tests, the smoke check and the benchmark's cpu_baseline leg may call it;
+ * the product never does.
+ *
+ * What the paper fixes (section / listing cited at each function):
+ *   - every rank owns a contiguous block of the global batch (Introduction: row-block
+ *     partition of the batch into mini-batches) and a share of the embedding tables
+ *     ("distributed by a given partitioning strategy");
+ *   - each rank works out which vectors it needs from which rank and fetches them
+ *     with an alltoallv (Introduction);
+ *   - the lookup itself is an EmbeddingBag over (offsets, indices) per table and the
+ *     alltoallv moves the pooled vectors, sized by the number of tables per rank
+ *     (Listing 1: apply_emb, then alltoall(ly, n_emb_per_rank));
+ *   - with bound k = 0 the exchange is semantically MPI_Alltoallv (A zero-bound
+ *     parameter), and for any k the results are unchanged (Abstract; Related Work:
+ *     vectors "always fully accurate");
+ *   - completion copies the receive region of the iteration's ring slot to the
+ *     caller's buffer (Alltoallv completion).
+ * Where the paper is silent the reading taken is stated beside the code and listed in
+ * the design notes: sum pooling without weights; a single fp32 accumulator starting
+ * at +0.0f with terms added in bag order; stable (input-order) placement inside every
+ * bucket; row-wise block shards of ceil(rows/P) rows; the first B mod P ranks get one
+ * extra sample.
+ *
+ * Notation: P ranks, T tables, B global batch, D vector length, bag g = t*B + b,
+ * lookup l in [offsets[g], offsets[g+1]); requester s(b); owner d(t, idx); F = 1 for
+ * table-wise partition and P for row-wise.
+ *
+ * Every function returns 0, or a negative code: -1 bad argument, -2 index or offset
+ * out of range, -3 out of memory.
+ */
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+#define ORC_OK 0
+#define ORC_EINVAL (-1)
+#define ORC_ERANGE (-2)
+#define ORC_ENOMEM (-3)
+
+/* ---- partition helpers -------------------------------------------------------- */
+
+/* Mini-batch of rank s: samples [first(s), first(s+1)).  The first B mod P ranks hold
+ * one sample more (reading; every benchmark workload divides evenly). */
+static int64_t batch_first(int64_t B, int P, int s)
+{
+    int64_t q = B / P, r = B % P;
+    return (int64_t)s * q + (s < r ? s : r);
+}
+
+static int requester_of(int64_t B, int P, int64_t b)
+{
+    int s;
+    for (s = 0; s < P; ++s)
+        if (b < batch_first(B, P, s + 1)) return s;
+    return P - 1;
+}
+
+/* Rows per shard for the row-wise block partition: ceil(rows / P); the last shards may
+ * be short or empty. */
+static int64_t rows_per_shard(int64_t rows, int P) { return (rows + P - 1) / P; }
+
+/* n_loc[d]: number of tables rank d serves; loc[t]: position of t among its owner's
+ * tables in increasing t.  Row-wise: every rank serves a shard of every table. */
+static void local_tables(int P, int T, int part_kind, const int32_t *owner, int *n_loc, int *loc)
+{
+    int t, d;
+    for (d = 0; d < P; ++d) n_loc[d] = 0;
+    for (t = 0; t < T; ++t) {
+        if (part_kind == 1) { loc[t] = t; }
+        else { loc[t] = n_loc[owner[t]]; n_loc[owner[t]] += 1; }
+    }
+    if (part_kind == 1) for (d = 0; d < P; ++d) n_loc[d] = T;
+}
+
+/* Segment index of (owner d, requester s, local table t_loc, local sample b_loc): the
+ * order in which owner-side lookups are stored, d-major, then s, then table, then
+ * sample.  Also the order of pooled vectors in the send regions. */
+static int64_t segment_index(int P, int64_t B, const int *n_loc, int d, int s, int t_loc, int64_t b_loc)
+{
+    int64_t base = 0;
+    int dd;
+    for (dd = 0; dd < d; ++dd) base += (int64_t)n_loc[dd] * B;
+    base += (int64_t)n_loc[d] * batch_first(B, P, s);
+    return base + (int64_t)t_loc * (batch_first(B, P, s + 1) - batch_first(B, P, s)) + b_loc;
+}
+
+static int check_partition(int P, int T, int part_kind, const int64_t *rows, const int32_t *owner)
+{
+    int t;
+    if (P < 1 || T < 1 || (part_kind != 0 && part_kind != 1)) return ORC_EINVAL;
+    for (t = 0; t < T; ++t) {
+        if (rows[t] < 1) return ORC_EINVAL;
+        if (part_kind == 0 && (owner[t] < 0 || owner[t] >= P)) return ORC_EINVAL;
+    }
+    return ORC_OK;
+}
+
+/* ---- index bucketing: counts, displacements, stable placement ------------------- */
+
+/*
+ * Introduction ("each process determines the vector IDs required from other
+ * processes, and retrieves them through an alltoallv"): for every lookup l, in
+ * increasing l, the requester s, the owner d and the row r inside the owner's shard.
+ * sendcounts[s][d] = number of lookups rank s asks of rank d; recvcounts is its
+ * transpose; displacements are running sums (the MPI_Alltoallv convention the
+ * paper's benchmark signature uses); lookups keep their input order inside a bucket.
+ *
+ * Outputs: sendcounts, sdispls [P*P] row-major [s][d]; recvcounts, rdispls [P*P]
+ * row-major [d][s]; ridx[nnz] local rows in owner-side order (d, then s, then l);
+ * segoff[F*T*B+1] start of every (d, s, t_loc, b_loc) segment in ridx; perm[nnz]
+ * (nullable) requester-side position of lookup l (s, then d, then l).
+ */
+int orc_plan(int P, int T, int64_t B, int part_kind, const int64_t *rows, const int32_t *owner,
+             const int64_t *indices, const int64_t *offsets,
+             int64_t *sendcounts, int64_t *sdispls, int64_t *recvcounts, int64_t *rdispls,
+             int64_t *ridx, int64_t *segoff, int64_t *perm)
+{
+    int rc = check_partition(P, T, part_kind, rows, owner);
+    int s, d, t;
+    int64_t b, l, g, nseg, i;
+    int F = part_kind == 1 ? P : 1;
+    int *n_loc, *loc;
+    int64_t *sbase, *rbase, *cursor, *seglen;
+    if (rc) return rc;
+    if (B < 1) return ORC_EINVAL;
+    nseg = (int64_t)F * T * B;
+    n_loc = (int *)malloc(sizeof(int) * P);
+    loc = (int *)malloc(sizeof(int) * T);
+    sbase = (int64_t *)malloc(sizeof(int64_t) * P);
+    rbase = (int64_t *)malloc(sizeof(int64_t) * P);
+    cursor = (int64_t *)malloc(sizeof(int64_t) * P * P);
+    seglen = (int64_t *)calloc((size_t)nseg, sizeof(int64_t));
+    if (!n_loc || !loc || !sbase || !rbase || !cursor || !seglen) { rc = ORC_ENOMEM; goto done; }
+    local_tables(P, T, part_kind, owner, n_loc, loc);
+
+    if (offsets[0] != 0) { rc = ORC_ERANGE; goto done; }
+    for (g = 0; g < (int64_t)T * B; ++g)
+        if (offsets[g + 1] < offsets[g]) { rc = ORC_ERANGE; goto done; }
+
+    /* pass 1: count */
+    for (i = 0; i < (int64_t)P * P; ++i) sendcounts[i] = 0;
+    for (t = 0; t < T; ++t) {
+        for (b = 0; b < B; ++b) {
+            g = (int64_t)t * B + b;
+            s = requester_of(B, P, b);
+            for (l = offsets[g]; l < offsets[g + 1]; ++l) {
+                int64_t idx = indices[l];
+                if (idx < 0 || idx >= rows[t]) { rc = ORC_ERANGE; goto done; }
+                d = part_kind == 1 ? (int)(idx / rows_per_shard(rows[t], P)) : owner[t];
+                sendcounts[s * P + d] += 1;
+                seglen[segment_index(P, B, n_loc, d, s, loc[t], b - batch_first(B, P, s))] += 1;
+            }
+        }
+    }
+    /* transpose and running sums */
+    for (s = 0; s < P; ++s)
+        for (d = 0; d < P; ++d) recvcounts[d * P + s] = sendcounts[s * P + d];
+    for (s = 0; s < P; ++s) {
+        int64_t run = 0;
+        for (d = 0; d < P; ++d) { sdispls[s * P + d] = run; run += sendcounts[s * P + d]; }
+    }
+    for (d = 0; d < P; ++d) {
+        int64_t run = 0;
+        for (s = 0; s < P; ++s) { rdispls[d * P + s] = run; run += recvcounts[d * P + s]; }
+    }
+    {   /* region bases: rank regions laid one after another */
+        int64_t run = 0;
+        for (s = 0; s < P; ++s) {
+            sbase[s] = run;
+            for (d = 0; d < P; ++d) run += sendcounts[s * P + d];
+        }
+        run = 0;
+        for (d = 0; d < P; ++d) {
+            rbase[d] = run;
+            for (s = 0; s < P; ++s) run += recvcounts[d * P + s];
+        }
+    }
+    segoff[0] = 0;
+    for (i = 0; i < nseg; ++i) segoff[i + 1] = segoff[i] + seglen[i];
+
+    /* pass 2: stable placement, one cursor per (s, d) bucket */
+    for (i = 0; i < (int64_t)P * P; ++i) cursor[i] = 0;
+    for (t = 0; t < T; ++t) {
+        for (b = 0; b < B; ++b) {
+            g = (int64_t)t * B + b;
+            s = requester_of(B, P, b);
+            for (l = offsets[g]; l < offsets[g + 1]; ++l) {
+                int64_t idx = indices[l], r, rank;
+                if (part_kind == 1) {
+                    int64_t rps = rows_per_shard(rows[t], P);
+                    d = (int)(idx / rps);
+                    r = idx - (int64_t)d * rps;
+                } else {
+                    d = owner[t];
+                    r = idx;
+                }
+                rank = cursor[s * P + d]++;
+                ridx[rbase[d] + rdispls[d * P + s] + rank] = r;
+                if (perm) perm[l] = sbase[s] + sdispls[s * P + d] + rank;
+            }
+        }
+    }
+done:
+    free(n_loc); free(loc); free(sbase); free(rbase); free(cursor); free(seglen);
+    return rc;
+}
+
+/* ---- EmbeddingBag --------------------------------------------------------------- */
+
+/* IEEE binary16 -> binary32, exact. */
+static float half_to_float(uint16_t h)
+{
+    uint32_t sign = (uint32_t)(h & 0x8000u) << 16;
+    uint32_t e = (h >> 10) & 0x1Fu, m = h & 0x3FFu, bits;
+    float f;
+    if (e == 0) {
+        if (m == 0) bits = sign;
+        else {                       /* subnormal: normalise */
+            int sh = 0;
+            while (!(m & 0x400u)) { m <<= 1; ++sh; }
+            m &= 0x3FFu;
+            bits = sign | ((uint32_t)(127 - 15 - sh + 1) << 23) | (m << 13);
+        }
+    } else if (e == 31) bits = sign | 0x7F800000u | (m << 13);
+    else bits = sign | ((e + 127 - 15) << 23) | (m << 13);
+    memcpy(&f, &bits, 4);
+    return f;
+}
+
+static float elem(const void *table, int dtype, int64_t i)
+{
+    return dtype == 1 ? half_to_float(((const uint16_t *)table)[i]) : ((const float *)table)[i];
+}
+
+/*
+ * Listing 1, apply_emb: the plain definition of the whole path's result.
+ *   Out[b][t][c] = sum over l in bag (t,b) of W_t[indices[l]][c]
+ * computed in double precision (out64, nullable) and with one fp32 accumulator that
+ * starts at +0.0f and adds the terms in increasing l (out32, nullable).  tables[t] is
+ * table t with global row numbering, dtype 0 = fp32, 1 = fp16 storage.
+ */
+int orc_embbag_plain(int T, int D, int64_t B, int dtype, const int64_t *rows, const void *const *tables,
+                     const int64_t *indices, const int64_t *offsets, double *out64, float *out32)
+{
+    int t, c;
+    int64_t b, l;
+    for (t = 0; t < T; ++t)
+        for (b = 0; b < B; ++b) {
+            int64_t g = (int64_t)t * B + b;
+            for (l = offsets[g]; l < offsets[g + 1]; ++l)
+                if (indices[l] < 0 || indices[l] >= rows[t]) return ORC_ERANGE;
+            for (c = 0; c < D; ++c) {
+                double a64 = 0.0;
+                float a32 = 0.0f;
+                for (l = offsets[g]; l < offsets[g + 1]; ++l) {
+                    float x = elem(tables[t], dtype, indices[l] * D + c);
+                    a64 += (double)x;
+                    a32 += x;
+                }
+                if (out64) out64[((int64_t)b * T + t) * D + c] = a64;
+                if (out32) out32[((int64_t)b * T + t) * D + c] = a32;
+            }
+        }
+    return ORC_OK;
+}
+
+/* Sum of the absolute values of a bag's terms, in double: the scale the fp32
+ * tolerance is relative to.  Same layout as orc_embbag_plain's outputs. */
+int orc_embbag_absmass(int T, int D, int64_t B, int dtype, const void *const *tables,
+                       const int64_t *indices, const int64_t *offsets, double *mass)
+{
+    int t, c;
+    int64_t b, l;
+    for (t = 0; t < T; ++t)
+        for (b = 0; b < B; ++b)
+            for (c = 0; c < D; ++c) {
+                int64_t g = (int64_t)t * B + b;
+                double a = 0.0;
+                for (l = offsets[g]; l < offsets[g + 1]; ++l) {
+                    double x = (double)elem(tables[t], dtype, indices[l] * D + c);
+                    a += x < 0 ? -x : x;
+                }
+                mass[((int64_t)b * T + t) * D + c] = a;
+            }
+    return ORC_OK;
+}
+
+/*
+ * Owner-side pooling (Listing 1, apply_emb on each rank's local tables / shards).
+ * For owner d, local table t_loc, sample b = first(s) + b_loc:
+ *   Y_d[t_loc][b][:] = sum over the segment's rows of W_{t,d}[ridx[.]][:]
+ * fp32 accumulator from +0.0f, terms in segment order.  Y is the concatenation of
+ * Y_0 .. Y_{P-1}, each [n_loc(d)][B][D].  Row-wise shard d of table t is rows
+ * [d*rps, min((d+1)*rps, rows_t)) of the global table.
+ */
+int orc_pool(int P, int T, int D, int64_t B, int part_kind, const int64_t *rows, const int32_t *owner,
+             int dtype, const void *const *tables, const int64_t *ridx, const int64_t *segoff, float *Y)
+{
+    int rc = check_partition(P, T, part_kind, rows, owner);
+    int *n_loc, *loc, d, s, t, c;
+    int64_t ybase = 0;
+    if (rc) return rc;
+    n_loc = (int *)malloc(sizeof(int) * P);
+    loc = (int *)malloc(sizeof(int) * T);
+    if (!n_loc || !loc) { free(n_loc); free(loc); return ORC_ENOMEM; }
+    local_tables(P, T, part_kind, owner, n_loc, loc);
+    for (d = 0; d < P; ++d) {
+        for (t = 0; t < T; ++t) {
+            int64_t shard_first, shard_rows;
+            if (part_kind == 0 && owner[t] != d) continue;
+            if (part_kind == 1) {
+                int64_t rps = rows_per_shard(rows[t], P);
+                shard_first = (int64_t)d * rps;
+                shard_rows = rows[t] - shard_first;
+                if (shard_rows > rps) shard_rows = rps;
+                if (shard_rows < 0) shard_rows = 0;
+            } else { shard_first = 0; shard_rows = rows[t]; }
+            for (s = 0; s < P; ++s) {
+                int64_t f = batch_first(B, P, s), n = batch_first(B, P, s + 1) - f, b_loc, j;
+                for (b_loc = 0; b_loc < n; ++b_loc) {
+                    int64_t sg = segment_index(P, B, n_loc, d, s, loc[t], b_loc);
+                    float *y = Y + ybase + ((int64_t)loc[t] * B + f + b_loc) * D;
+                    for (j = segoff[sg]; j < segoff[sg + 1]; ++j)
+                        if (ridx[j] < 0 || ridx[j] >= shard_rows) { rc = ORC_ERANGE; goto done; }
+                    for (c = 0; c < D; ++c) {
+                        float acc = 0.0f;
+                        for (j = segoff[sg]; j < segoff[sg + 1]; ++j)
+                            acc += elem(tables[t], dtype, (shard_first + ridx[j]) * D + c);
+                        y[c] = acc;
+                    }
+                }
+            }
+        }
+        ybase += (int64_t)n_loc[d] * B * D;
+    }
+done:
+    free(n_loc); free(loc);
+    return rc;
+}
+
+/* ---- pooled-vector exchange ----------------------------------------------------- */
+
+/*
+ * Listing 1, alltoall(ly, n_emb_per_rank): counts of the pooled exchange in fp32
+ * elements.  Owner d sends requester s its n_loc(d) local tables for s's mini-batch:
+ * pcount[d][s] = n_loc(d) * B_loc(s) * D.  Displacements are running sums; region
+ * bases lay the ranks' send (resp. receive) regions one after another.
+ * Outputs [P*P]: pcount, psdispl row-major [d][s]; prcount, prdispl row-major [s][d];
+ * [P]: psbase, prbase.
+ */
+int orc_pooled_counts(int P, int T, int D, int64_t B, int part_kind, const int32_t *owner,
+                      int64_t *pcount, int64_t *psdispl, int64_t *prcount, int64_t *prdispl,
+                      int64_t *psbase, int64_t *prbase)
+{
+    int *n_loc = (int *)malloc(sizeof(int) * P), *loc = (int *)malloc(sizeof(int) * T), d, s;
+    int64_t run;
+    if (!n_loc || !loc) { free(n_loc); free(loc); return ORC_ENOMEM; }
+    local_tables(P, T, part_kind, owner, n_loc, loc);
+    for (d = 0; d < P; ++d)
+        for (s = 0; s < P; ++s) {
+            int64_t n = batch_first(B, P, s + 1) - batch_first(B, P, s);
+            pcount[d * P + s] = (int64_t)n_loc[d] * n * D;
+            prcount[s * P + d] = pcount[d * P + s];
+        }
+    for (d = 0, run = 0; d < P; ++d) {
+        int64_t in = 0;
+        psbase[d] = run;
+        for (s = 0; s < P; ++s) { psdispl[d * P + s] = in; in += pcount[d * P + s]; }
+        run += in;
+    }
+    for (s = 0, run = 0; s < P; ++s) {
+        int64_t in = 0;
+        prbase[s] = run;
+        for (d = 0; d < P; ++d) { prdispl[s * P + d] = in; in += prcount[s * P + d]; }
+        run += in;
+    }
+    free(n_loc); free(loc);
+    return ORC_OK;
+}
+
+/* S(p), the send buffer of Fig. 5: owner d lays its pooled vectors out by destination,
+ * S_d[s][t_loc][b_loc][:] = Y_d[t_loc][first(s) + b_loc][:]. */
+int orc_pack(int P, int T, int D, int64_t B, int part_kind, const int32_t *owner, const float *Y, float *S)
+{
+    int *n_loc = (int *)malloc(sizeof(int) * P), *loc = (int *)malloc(sizeof(int) * T), d, s, tl;
+    int64_t ybase = 0;
+    if (!n_loc || !loc) { free(n_loc); free(loc); return ORC_ENOMEM; }
+    local_tables(P, T, part_kind, owner, n_loc, loc);
+    for (d = 0; d < P; ++d) {
+        for (s = 0; s < P; ++s) {
+            int64_t f = batch_first(B, P, s), n = batch_first(B, P, s + 1) - f, b_loc;
+            for (tl = 0; tl < n_loc[d]; ++tl)
+                for (b_loc = 0; b_loc < n; ++b_loc)
+                    memcpy(S + segment_index(P, B, n_loc, d, s, tl, b_loc) * D,
+                           Y + ybase + ((int64_t)tl * B + f + b_loc) * D, sizeof(float) * D);
+        }
+        ybase += (int64_t)n_loc[d] * B * D;
+    }
+    free(n_loc); free(loc);
+    return ORC_OK;
+}
+
+/*
+ * MPI_Alltoallv as the textbook defines it (A zero-bound parameter: with k = 0 the
+ * collective is semantically MPI_Alltoallv): for every source and destination rank,
+ *   recv[dst][rdispls[dst][src] ..] = send[src][sdispls[src][dst] ..], sendcounts[src][dst] items.
+ * Rank regions are concatenated: rank p's send region starts at sbase[p], its receive
+ * region at rbase[p].  Alltoallv initiation writes these blocks into R(dst, slot); on
+ * one device that write is this copy.
+ */
+int orc_alltoallv_f32(int P, const float *send, const int64_t *sbase, const int64_t *sendcounts,
+                      const int64_t *sdispls, float *recv, const int64_t *rbase,
+                      const int64_t *recvcounts, const int64_t *rdispls)
+{
+    int src, dst;
+    for (src = 0; src < P; ++src)
+        for (dst = 0; dst < P; ++dst) {
+            if (recvcounts[dst * P + src] != sendcounts[src * P + dst]) return ORC_EINVAL;
+            memcpy(recv + rbase[dst] + rdispls[dst * P + src],
+                   send + sbase[src] + sdispls[src * P + dst],
+                   sizeof(float) * (size_t)sendcounts[src * P + dst]);
+        }
+    return ORC_OK;
+}
+
+/*
+ * Alltoallv completion: copy the receive region out into the caller's tensor,
+ * Out[b][t][:] for b in the requester's mini-batch.  Table-wise: the one block that
+ * holds table t.  Row-wise: every owner sent a partial sum for (t, b); add them from
+ * +0.0f in increasing owner rank (reading: the paper never shards a table by rows).
+ * R is the concatenation of the requesters' receive regions, each [d][t_loc][b_loc][D].
+ */
+int orc_unpack(int P, int T, int D, int64_t B, int part_kind, const int32_t *owner, const float *R, float *Out)
+{
+    int *n_loc = (int *)malloc(sizeof(int) * P), *loc = (int *)malloc(sizeof(int) * T), d, s, t, c;
+    int64_t rbase = 0;
+    if (!n_loc || !loc) { free(n_loc); free(loc); return ORC_ENOMEM; }
+    local_tables(P, T, part_kind, owner, n_loc, loc);
+    for (s = 0; s < P; ++s) {
+        int64_t f = batch_first(B, P, s), n = batch_first(B, P, s + 1) - f, b_loc, total = 0;
+        for (b_loc = 0; b_loc < n; ++b_loc)
+            for (t = 0; t < T; ++t) {
+                float *o = Out + ((f + b_loc) * T + t) * D;
+                for (c = 0; c < D; ++c) o[c] = 0.0f;
+                {
+                    int64_t blk = 0;           /* start of owner d's block inside R_s */
+                    for (d = 0; d < P; ++d) {
+                        if (part_kind == 1 || owner[t] == d) {
+                            const float *r = R + rbase + blk + ((int64_t)loc[t] * n + b_loc) * D;
+                            if (part_kind == 1) for (c = 0; c < D; ++c) o[c] += r[c];
+                            else memcpy(o, r, sizeof(float) * D);
+                        }
+                        blk += (int64_t)n_loc[d] * n * D;
+                    }
+                }
+            }
+        for (d = 0; d < P; ++d) total += (int64_t)n_loc[d] * n * D;
+        rbase += total;
+    }
+    free(n_loc); free(loc);
+    return ORC_OK;
+}
+
+/* Ordered fp32 sum and fp64 sum of n rows of length D given directly (for checking
+ * single bags of workloads too large to hold on the host). */
+int orc_bag_sum(int D, int64_t n, const float *rows_nd, float *out32, double *out64)
+{
+    int c;
+    int64_t j;
+    for (c = 0; c < D; ++c) {
+        float a32 = 0.0f;
+        double a64 = 0.0;
+        for (j = 0; j < n; ++j) { a32 += rows_nd[j * D + c]; a64 += (double)rows_nd[j * D + c]; }
+        if (out32) out32[c] = a32;
+        if (out64) out64[c] = a64;
+    }
+    return ORC_OK;
+}
