@@ -1,0 +1,171 @@
+/*
+ * libbls - one GPU's share of the distributed sparse-embedding lookup of
+ * bounded-lag-synchronous (BLS) DLRM inference, for AMD MI355X (gfx950).
+ *
+ * P ranks are simulated inside one GPU's memory.  Rank s owns a contiguous block of
+ * the global batch (its mini-batch); rank d owns a share of the embedding tables
+ * (whole tables, or a block of rows of every table).  One iteration of the path is
+ *
+ *   bls_plan            which lookups go to which rank: alltoallv counts and
+ *                       displacements, and the lookups laid out in owner order
+ *   bls_embbag_pool     EmbeddingBag (sum) on every owner's local tables or shards
+ *   bls_pack            pooled vectors into per-destination send regions S(d)
+ *   bls_ring_advance    take the next of the k receive buffers, slot = iteration mod k
+ *   bls_alltoallv_local the alltoallv itself: S(d) blocks into R(s, slot)
+ *   bls_unpack          completion: copy R(s, slot) out as [B][T][D], free the slot
+ *
+ * Notation (used in every comment below): P ranks, T tables, B global batch, D vector
+ * length, K = max(k, 1) ring slots, F = 1 (table-wise partition) or P (row-wise),
+ * bag g = t*B + b, requester s(b) = rank whose mini-batch holds sample b, owner
+ * d(t, idx), n_loc(d) = number of tables rank d serves, loc(t) = position of t among
+ * its owner's tables in increasing t.  Mini-batch of rank s is samples
+ * [first(s), first(s+1)); when P does not divide B the first B mod P ranks hold one
+ * sample more.  Row-wise shards hold ceil(rows_t / P) rows (the last ones may be
+ * short or empty): d = idx / ceil(rows_t / P).
+ *
+ * Segment order.  Owner-side data (ridx, segoff, send regions) is ordered by
+ * (d, s, t_loc, b_loc), b_loc = b - first(s).  Receive regions are ordered by
+ * (s, d, t_loc, b_loc).
+ *
+ * Conventions.  Every function returns BLS_OK or a negative code and never throws or
+ * aborts.  Pointers named d_* are DEVICE memory owned by the caller and must stay
+ * valid until the work enqueued on `hip_stream` has finished; all other pointers are
+ * HOST memory.  `hip_stream` is a hipStream_t passed as void* (NULL = the null
+ * stream).  Calls enqueue work and return without waiting.  Data-dependent errors
+ * (an index outside its table, offsets that decrease) cannot be seen by the host at
+ * call time: kernels skip the offending item, raise a device-side flag, and
+ * bls_check reports it.  The library allocates a few KB of device memory per context
+ * for its descriptor tables and never anything proportional to the problem; scratch
+ * memory comes from the caller (d_ws).  A context is not thread safe.
+ */
+#ifndef BLS_H
+#define BLS_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct bls_ctx bls_ctx; /* opaque; host memory owned by the library */
+
+enum {
+    BLS_OK = 0,
+    BLS_EINVAL = -1,      /* bad argument, missing shard, NULL pointer                       */
+    BLS_ERANGE = -2,      /* an index outside [0, rows_t) or non-monotone offsets (device)   */
+    BLS_ENOSPC = -3,      /* a caller buffer (workspace, ring) is too small                  */
+    BLS_ERING_FULL = -4,  /* K iterations already in flight                                  */
+    BLS_ERING_EMPTY = -5, /* completion asked for with nothing in flight                     */
+    BLS_EORDER = -6,      /* completion out of FIFO order, or exchange into a wrong slot     */
+    BLS_EHIP = -7         /* a HIP runtime call failed; text in bls_last_error               */
+};
+
+enum { BLS_FP32 = 0, BLS_FP16 = 1 };          /* table storage; accumulation and output are fp32 */
+enum { BLS_TABLE_WISE = 0, BLS_ROW_WISE = 1 };
+
+typedef struct bls_config {
+    int32_t P, T, D, k;          /* 1 <= P <= 64; k >= 0 is the paper's bound, K = max(k,1) slots   */
+    int64_t B;                   /* global batch, B >= P                                             */
+    int32_t table_dtype;         /* BLS_FP32 | BLS_FP16                                              */
+    int32_t part_kind;           /* BLS_TABLE_WISE | BLS_ROW_WISE                                    */
+    const int64_t *rows;         /* host [T], rows per table (global), each >= 1                     */
+    const int32_t *table_owner;  /* host [T], owner rank of each table; read for table-wise only     */
+} bls_config;
+
+/* Lifecycle.  bls_create copies the configuration (rows / table_owner are not kept).
+ * Touches no GPU. */
+int bls_create(const bls_config *cfg, bls_ctx **out);
+int bls_destroy(bls_ctx *ctx);
+
+/* Hand the library one table shard: row-major [rows_in_shard][D] in the configured
+ * storage dtype, device memory, 16-byte aligned, borrowed until bls_destroy.
+ * Table-wise: rank must be table_owner[t] and rows_in_shard = rows[t].  Row-wise: one
+ * call per (t, rank), rows_in_shard = number of rows of table t that fall in the
+ * rank's block (may be 0, then d_rows may be NULL). */
+int bls_set_shard(bls_ctx *ctx, int32_t t, int32_t rank, const void *d_rows, int64_t rows_in_shard);
+
+/* Buffer sizes in bytes for a batch of at most max_nnz lookups: plan workspace, the
+ * pooled buffer Y, the send buffer S, and one ring slot (all three F*T*B*D fp32). */
+int bls_sizes(const bls_ctx *ctx, int64_t max_nnz, size_t *plan_ws_bytes, size_t *pooled_bytes,
+              size_t *send_bytes, size_t *slot_bytes);
+
+/* Counts and displacements of the pooled-vector alltoallv (the exchange of Listing 1,
+ * alltoall(ly, n_emb_per_rank)), in fp32 elements, closed-form from the configuration:
+ * pcount[d][s] = n_loc(d) * B_loc(s) * D.  Host outputs, [P*P] each, any may be NULL:
+ * pcount / psdispl row-major [d][s] (send side), prcount / prdispl row-major [s][d]. */
+int bls_pooled_counts(const bls_ctx *ctx, int64_t *pcount, int64_t *psdispl, int64_t *prcount, int64_t *prdispl);
+
+/*
+ * Index bucketing (Introduction: every process works out which vector IDs it needs
+ * from which process; the irregular per-peer counts are what make the exchange an
+ * alltoallv).  Inputs: d_indices[nnz] global row ids, d_offsets[T*B+1] with
+ * offsets[0] = 0 and offsets[T*B] = nnz, bag g = t*B + b.
+ * Outputs, all int64 device arrays:
+ *   d_sendcounts, d_sdispls [P*P] row-major [s][d]: lookups rank s asks of rank d and
+ *       their exclusive running sum over d;
+ *   d_recvcounts, d_rdispls [P*P] row-major [d][s]: the transpose and its running sum;
+ *   d_ridx[nnz]: row inside the owner's shard of every lookup, in owner order
+ *       (d, then s, then input order - placement inside a bucket is stable);
+ *   d_segoff[F*T*B+1]: start in d_ridx of every (d, s, t_loc, b_loc) segment, last
+ *       entry nnz;
+ *   d_perm[nnz] or NULL: requester-side position (s, then d, then input order) of
+ *       every lookup, i.e. where it sits in rank s's send region of the index exchange.
+ * d_ws / ws_bytes: scratch of at least bls_sizes' plan_ws_bytes, 8-byte aligned.
+ */
+int bls_plan(bls_ctx *ctx, const int64_t *d_indices, const int64_t *d_offsets, int64_t nnz,
+             int64_t *d_sendcounts, int64_t *d_sdispls, int64_t *d_recvcounts, int64_t *d_rdispls,
+             int64_t *d_ridx, int64_t *d_segoff, int64_t *d_perm, void *d_ws, size_t ws_bytes, void *hip_stream);
+
+/*
+ * EmbeddingBag, sum mode (Listing 1: apply_emb over offsets and indices; the paper's
+ * profile shows it dominating the run).  For owner d, local table t_loc and sample b:
+ *   Y_d[t_loc][b][:] = sum over the segment's rows of W_{t,d}[ridx[.]][:]
+ * fp32 accumulation from +0 in segment order (bit-exact against an ordered CPU sum).
+ * d_pooled is Y_0 .. Y_{P-1} back to back, Y_d = [n_loc(d)][B][D] fp32.  nnz is the
+ * extent of d_ridx; segments that reach past it are skipped and flagged.
+ */
+int bls_embbag_pool(bls_ctx *ctx, const int64_t *d_ridx, const int64_t *d_segoff, int64_t nnz,
+                    float *d_pooled, void *hip_stream);
+
+/* Send buffer S(p) of the alltoallv figure: S_d[s][t_loc][b_loc][:] =
+ * Y_d[t_loc][first(s)+b_loc][:], regions of d = 0..P-1 back to back (segment order). */
+int bls_pack(bls_ctx *ctx, const float *d_pooled, float *d_send, void *hip_stream);
+
+/* Ring of K receive buffers R(*, i) (BLS backend initialisation: k buffers created
+ * once and reused circularly).  d_slots is caller-owned, bytes >= K * slot_bytes,
+ * 16-byte aligned. */
+int bls_set_ring(bls_ctx *ctx, void *d_slots, size_t bytes);
+
+/* Start iteration j = number of earlier successful calls: slot = j mod K (Alltoallv
+ * initiation).  Fails with BLS_ERING_FULL when K iterations are in flight (section on
+ * the bound: a process that has issued k iterations must complete the oldest first).
+ * Makes `hip_stream` wait until the slot's previous contents have been copied out. */
+int bls_ring_advance(bls_ctx *ctx, int64_t *iter_out, int32_t *slot_out, void *hip_stream);
+
+/* The alltoallv on one device (Alltoallv initiation: each source writes its block into
+ * the destination's receive buffer R(dst, slot); with k = 0 this is MPI_Alltoallv):
+ * R_s(slot)[d][t_loc][b_loc][:] = S_d[s][t_loc][b_loc][:] for all P*P (d, s) blocks.
+ * `slot` must be the slot of the youngest iteration started and not yet exchanged. */
+int bls_alltoallv_local(bls_ctx *ctx, const float *d_send, int32_t slot, void *hip_stream);
+
+/* Alltoallv completion for iteration `iter`, which must be the oldest in flight
+ * (wait() completes the tail request and pops it): copy the receive regions of its
+ * slot to d_out[B][T][D] fp32 and free the slot.  Table-wise: a copy.  Row-wise: the P
+ * partial sums of every (b, t) are added from +0 in increasing owner rank. */
+int bls_unpack(bls_ctx *ctx, int64_t iter, float *d_out, void *hip_stream);
+
+/* Ring state for callers and tests: next iteration number, oldest in flight, K. */
+int bls_ring_state(const bls_ctx *ctx, int64_t *head, int64_t *tail, int32_t *K);
+
+/* Wait for `hip_stream`, then return BLS_ERANGE if any kernel since the last
+ * bls_check saw a bad index / offset / segment (and clear the flag), else BLS_OK. */
+int bls_check(bls_ctx *ctx, void *hip_stream);
+
+/* Text of the last error on this context (never NULL). */
+const char *bls_last_error(const bls_ctx *ctx);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* BLS_H */

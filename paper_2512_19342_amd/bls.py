@@ -1,0 +1,183 @@
+"""ctypes binding of libbls.so: argument marshalling only.
+
+Function names and argument order follow include/bls.h.  Device buffers are torch
+tensors (used for their memory and for the current stream, nothing else); the binding
+passes ``data_ptr()`` and sizes through.  If the library has not been built the import
+of a symbol raises - there is no CPU or PyTorch fallback for any step.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional, Sequence
+
+import torch
+
+BLS_OK, BLS_EINVAL, BLS_ERANGE, BLS_ENOSPC = 0, -1, -2, -3
+BLS_ERING_FULL, BLS_ERING_EMPTY, BLS_EORDER, BLS_EHIP = -4, -5, -6, -7
+BLS_FP32, BLS_FP16 = 0, 1
+BLS_TABLE_WISE, BLS_ROW_WISE = 0, 1
+
+EXPORTS = [
+    "bls_create", "bls_destroy", "bls_set_shard", "bls_sizes", "bls_pooled_counts", "bls_plan",
+    "bls_embbag_pool", "bls_pack", "bls_set_ring", "bls_ring_advance", "bls_alltoallv_local",
+    "bls_unpack", "bls_ring_state", "bls_check", "bls_last_error",
+]
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_lib = None
+
+
+class bls_config(C.Structure):
+    _fields_ = [("P", C.c_int32), ("T", C.c_int32), ("D", C.c_int32), ("k", C.c_int32),
+                ("B", C.c_int64), ("table_dtype", C.c_int32), ("part_kind", C.c_int32),
+                ("rows", C.POINTER(C.c_int64)), ("table_owner", C.POINTER(C.c_int32))]
+
+
+def lib_path() -> str:
+    return os.path.join(_HERE, "libbls.so")
+
+
+def lib() -> C.CDLL:
+    """The loaded library.  Raises if it has not been built (python -m paper_2512_19342_amd.build)."""
+    global _lib
+    if _lib is None:
+        path = lib_path()
+        if not os.path.exists(path):
+            raise RuntimeError(f"{path} is missing: build it with `python -m paper_2512_19342_amd.build` "
+                               "(there is no fallback path)")
+        L = C.CDLL(path)
+        vp, i64p = C.c_void_p, C.c_void_p
+        L.bls_create.argtypes = [C.POINTER(bls_config), C.POINTER(vp)]
+        L.bls_destroy.argtypes = [vp]
+        L.bls_set_shard.argtypes = [vp, C.c_int32, C.c_int32, vp, C.c_int64]
+        L.bls_sizes.argtypes = [vp, C.c_int64] + [C.POINTER(C.c_size_t)] * 4
+        L.bls_pooled_counts.argtypes = [vp] + [C.POINTER(C.c_int64)] * 4
+        L.bls_plan.argtypes = [vp, i64p, i64p, C.c_int64, i64p, i64p, i64p, i64p, i64p, i64p, i64p, vp, C.c_size_t, vp]
+        L.bls_embbag_pool.argtypes = [vp, i64p, i64p, C.c_int64, vp, vp]
+        L.bls_pack.argtypes = [vp, vp, vp, vp]
+        L.bls_set_ring.argtypes = [vp, vp, C.c_size_t]
+        L.bls_ring_advance.argtypes = [vp, C.POINTER(C.c_int64), C.POINTER(C.c_int32), vp]
+        L.bls_alltoallv_local.argtypes = [vp, vp, C.c_int32, vp]
+        L.bls_unpack.argtypes = [vp, C.c_int64, vp, vp]
+        L.bls_ring_state.argtypes = [vp, C.POINTER(C.c_int64), C.POINTER(C.c_int64), C.POINTER(C.c_int32)]
+        L.bls_check.argtypes = [vp, vp]
+        L.bls_last_error.argtypes = [vp]
+        L.bls_last_error.restype = C.c_char_p
+        for name in EXPORTS:
+            if name != "bls_last_error":
+                getattr(L, name).restype = C.c_int
+        _lib = L
+    return _lib
+
+
+class BlsError(RuntimeError):
+    def __init__(self, fn: str, code: int, text: str = ""):
+        super().__init__(f"{fn} -> {code}: {text}")
+        self.code = code
+
+
+def _ptr(t: Optional[torch.Tensor]) -> Optional[int]:
+    return None if t is None else t.data_ptr()
+
+
+def _stream(stream) -> Optional[int]:
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return stream.cuda_stream if hasattr(stream, "cuda_stream") else int(stream)
+
+
+class Context:
+    """One bls_ctx.  Methods carry the names of the C entry points."""
+
+    def __init__(self, P: int, T: int, D: int, k: int, B: int, rows: Sequence[int], table_owner: Sequence[int],
+                 table_dtype: int = BLS_FP32, part_kind: int = BLS_TABLE_WISE):
+        self._h = C.c_void_p()
+        rows_a = (C.c_int64 * T)(*[int(x) for x in rows])
+        own_a = (C.c_int32 * T)(*[int(x) for x in table_owner])
+        cfg = bls_config(P, T, D, k, B, table_dtype, part_kind, rows_a, own_a)
+        rc = lib().bls_create(C.byref(cfg), C.byref(self._h))
+        if rc != BLS_OK:
+            self._h = C.c_void_p()
+            raise BlsError("bls_create", rc, "invalid configuration")
+        self.P, self.T, self.D, self.k, self.B = P, T, D, k, B
+        self.K = max(k, 1)
+        self.F = P if part_kind == BLS_ROW_WISE else 1
+        self.part_kind, self.table_dtype = part_kind, table_dtype
+        self.n_vec = self.F * T * B
+        self._keep = []
+
+    # -- plumbing
+    def _call(self, name: str, *args) -> int:
+        rc = getattr(lib(), name)(self._h, *args)
+        if rc != BLS_OK:
+            raise BlsError(name, rc, self.bls_last_error())
+        return rc
+
+    def bls_last_error(self) -> str:
+        return lib().bls_last_error(self._h).decode()
+
+    def bls_destroy(self):
+        if self._h:
+            lib().bls_destroy(self._h)
+            self._h = C.c_void_p()
+
+    def __del__(self):
+        try:
+            self.bls_destroy()
+        except Exception:
+            pass
+
+    # -- set-up
+    def bls_set_shard(self, t: int, rank: int, rows_tensor: Optional[torch.Tensor], rows_in_shard: Optional[int] = None):
+        n = int(rows_tensor.shape[0]) if rows_in_shard is None else int(rows_in_shard)
+        if rows_tensor is not None:
+            assert rows_tensor.is_contiguous()
+            self._keep.append(rows_tensor)
+        self._call("bls_set_shard", t, rank, _ptr(rows_tensor), n)
+
+    def bls_sizes(self, max_nnz: int):
+        a = [C.c_size_t() for _ in range(4)]
+        self._call("bls_sizes", max_nnz, *[C.byref(x) for x in a])
+        return dict(zip(("plan_ws_bytes", "pooled_bytes", "send_bytes", "slot_bytes"), (x.value for x in a)))
+
+    def bls_pooled_counts(self):
+        pp = self.P * self.P
+        a = [(C.c_int64 * pp)() for _ in range(4)]
+        self._call("bls_pooled_counts", *a)
+        return dict(zip(("pcount", "psdispl", "prcount", "prdispl"), (list(x) for x in a)))
+
+    def bls_set_ring(self, slots: torch.Tensor):
+        self._keep.append(slots)
+        self._call("bls_set_ring", _ptr(slots), slots.numel() * slots.element_size())
+
+    # -- the path
+    def bls_plan(self, indices, offsets, nnz, sendcounts, sdispls, recvcounts, rdispls, ridx, segoff, perm, ws, stream=None):
+        self._call("bls_plan", _ptr(indices), _ptr(offsets), int(nnz), _ptr(sendcounts), _ptr(sdispls), _ptr(recvcounts),
+                   _ptr(rdispls), _ptr(ridx), _ptr(segoff), _ptr(perm), _ptr(ws), ws.numel() * ws.element_size(),
+                   _stream(stream))
+
+    def bls_embbag_pool(self, ridx, segoff, nnz, pooled, stream=None):
+        self._call("bls_embbag_pool", _ptr(ridx), _ptr(segoff), int(nnz), _ptr(pooled), _stream(stream))
+
+    def bls_pack(self, pooled, send, stream=None):
+        self._call("bls_pack", _ptr(pooled), _ptr(send), _stream(stream))
+
+    def bls_ring_advance(self, stream=None):
+        it, slot = C.c_int64(), C.c_int32()
+        self._call("bls_ring_advance", C.byref(it), C.byref(slot), _stream(stream))
+        return it.value, slot.value
+
+    def bls_alltoallv_local(self, send, slot, stream=None):
+        self._call("bls_alltoallv_local", _ptr(send), int(slot), _stream(stream))
+
+    def bls_unpack(self, it, out, stream=None):
+        self._call("bls_unpack", int(it), _ptr(out), _stream(stream))
+
+    def bls_ring_state(self):
+        h, t, k = C.c_int64(), C.c_int64(), C.c_int32()
+        self._call("bls_ring_state", C.byref(h), C.byref(t), C.byref(k))
+        return h.value, t.value, k.value
+
+    def bls_check(self, stream=None):
+        self._call("bls_check", _stream(stream))

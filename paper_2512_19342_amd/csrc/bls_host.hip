@@ -1,0 +1,353 @@
+// Host side of libbls: context, configuration checks, sizes, descriptor upload, the ring
+// of receive buffers and the C entry points.  Kernels live in bls_plan.hip, bls_pool.hip
+// and bls_permute.hip.
+#include <algorithm>
+#include <cstdio>
+#include <cstring>
+#include <new>
+
+#include "bls_internal.h"
+
+int bls_fail(bls_ctx *ctx, int code, const char *what)
+{
+    if (ctx) ctx->err = what;
+    return code;
+}
+
+int bls_fail_hip(bls_ctx *ctx, hipError_t e, const char *what)
+{
+    if (ctx) ctx->err = std::string(what) + ": " + hipGetErrorString(e);
+    return BLS_EHIP;
+}
+
+static int64_t first_of(int64_t B, int P, int s)
+{
+    const int64_t q = B / P, r = B % P;
+    return (int64_t)s * q + std::min<int64_t>(s, r);
+}
+
+extern "C" int bls_create(const bls_config *cfg, bls_ctx **out)
+{
+    if (!cfg || !out) return BLS_EINVAL;
+    *out = nullptr;
+    if (cfg->P < 1 || cfg->P > 64 || cfg->T < 1 || cfg->D < 1 || cfg->k < 0) return BLS_EINVAL;
+    if (cfg->B < cfg->P || cfg->B > 0x7fffffffLL) return BLS_EINVAL;
+    if (cfg->table_dtype != BLS_FP32 && cfg->table_dtype != BLS_FP16) return BLS_EINVAL;
+    if (cfg->part_kind != BLS_TABLE_WISE && cfg->part_kind != BLS_ROW_WISE) return BLS_EINVAL;
+    if (!cfg->rows || (cfg->part_kind == BLS_TABLE_WISE && !cfg->table_owner)) return BLS_EINVAL;
+    const int P = cfg->P, T = cfg->T;
+    const int F = cfg->part_kind == BLS_ROW_WISE ? P : 1;
+    if ((int64_t)F * T > 65535) return BLS_EINVAL;   // one grid row per (owner, local table)
+    for (int t = 0; t < T; ++t) {
+        if (cfg->rows[t] < 1) return BLS_EINVAL;
+        if (cfg->part_kind == BLS_TABLE_WISE && (cfg->table_owner[t] < 0 || cfg->table_owner[t] >= P)) return BLS_EINVAL;
+    }
+    bls_ctx *c = new (std::nothrow) bls_ctx();
+    if (!c) return BLS_EINVAL;
+    c->P = P; c->T = T; c->D = cfg->D; c->k = cfg->k; c->K = std::max(cfg->k, 1); c->F = F; c->Q = F * T;
+    c->dtype = cfg->table_dtype; c->part_kind = cfg->part_kind; c->B = cfg->B;
+    c->rows.assign(cfg->rows, cfg->rows + T);
+    c->owner.assign(T, 0);
+    if (cfg->part_kind == BLS_TABLE_WISE) c->owner.assign(cfg->table_owner, cfg->table_owner + T);
+    c->first.resize(P + 1);
+    for (int s = 0; s <= P; ++s) c->first[s] = first_of(c->B, P, s);
+    c->n_loc.assign(P, 0); c->nsum.assign(P + 1, 0); c->t_loc.assign(T, 0); c->t_q.assign(T, 0); c->rps.assign(T, 0);
+    for (int t = 0; t < T; ++t) {
+        if (c->part_kind == BLS_TABLE_WISE) { c->t_loc[t] = c->n_loc[c->owner[t]]++; c->rps[t] = c->rows[t]; }
+        else { c->t_loc[t] = t; c->rps[t] = (c->rows[t] + P - 1) / P; }
+    }
+    if (c->part_kind == BLS_ROW_WISE) c->n_loc.assign(P, T);
+    for (int d = 0; d < P; ++d) c->nsum[d + 1] = c->nsum[d] + c->n_loc[d];
+    c->q_t.assign(c->Q, 0); c->q_d.assign(c->Q, 0); c->q_rows.assign(c->Q, 0);
+    c->q_base.assign(c->Q, nullptr); c->q_set.assign(c->Q, 0);
+    for (int t = 0; t < T; ++t) {
+        if (c->part_kind == BLS_TABLE_WISE) {
+            const int q = c->nsum[c->owner[t]] + c->t_loc[t];
+            c->t_q[t] = q; c->q_t[q] = t; c->q_d[q] = c->owner[t]; c->q_rows[q] = c->rows[t];
+        } else {
+            c->t_q[t] = t;
+            for (int d = 0; d < P; ++d) {
+                const int q = d * T + t;
+                const int64_t lo = (int64_t)d * c->rps[t];
+                c->q_t[q] = t; c->q_d[q] = d;
+                c->q_rows[q] = std::max<int64_t>(0, std::min<int64_t>(c->rps[t], c->rows[t] - lo));
+                if (c->q_rows[q] == 0) c->q_set[q] = 1;   // an empty shard needs no storage
+            }
+        }
+    }
+    c->nseg = c->nvec = (int64_t)c->Q * c->B;
+    c->slot_bytes = (size_t)c->nvec * c->D * sizeof(float);
+    c->ring.resize(c->K);
+    *out = c;
+    return BLS_OK;
+}
+
+extern "C" int bls_destroy(bls_ctx *ctx)
+{
+    if (!ctx) return BLS_EINVAL;
+    if (ctx->device >= 0) {
+        int cur = -1;
+        if (hipGetDevice(&cur) == hipSuccess) {
+            if (cur != ctx->device) (void)hipSetDevice(ctx->device);
+            for (auto &r : ctx->ring) {
+                if (r.filled) (void)hipEventDestroy(r.filled);
+                if (r.released) (void)hipEventDestroy(r.released);
+            }
+            if (ctx->blob) { (void)hipDeviceSynchronize(); (void)hipFree(ctx->blob); }
+            if (cur != ctx->device) (void)hipSetDevice(cur);
+        }
+    }
+    delete ctx;
+    return BLS_OK;
+}
+
+extern "C" int bls_set_shard(bls_ctx *ctx, int32_t t, int32_t rank, const void *d_rows, int64_t rows_in_shard)
+{
+    if (!ctx) return BLS_EINVAL;
+    if (t < 0 || t >= ctx->T || rank < 0 || rank >= ctx->P) return bls_fail(ctx, BLS_EINVAL, "bls_set_shard: table or rank out of range");
+    int q;
+    if (ctx->part_kind == BLS_TABLE_WISE) {
+        if (rank != ctx->owner[t]) return bls_fail(ctx, BLS_EINVAL, "bls_set_shard: rank is not the table's owner");
+        q = ctx->t_q[t];
+    } else q = rank * ctx->T + t;
+    if (rows_in_shard != ctx->q_rows[q]) return bls_fail(ctx, BLS_EINVAL, "bls_set_shard: rows_in_shard does not match the partition");
+    if (rows_in_shard > 0 && !d_rows) return bls_fail(ctx, BLS_EINVAL, "bls_set_shard: NULL storage for a non-empty shard");
+    if (((uintptr_t)d_rows & 15u) != 0) return bls_fail(ctx, BLS_EINVAL, "bls_set_shard: storage must be 16-byte aligned");
+    if (rows_in_shard >= 0xffffffffLL) return bls_fail(ctx, BLS_EINVAL, "bls_set_shard: shard too large");
+    ctx->q_base[q] = d_rows;
+    ctx->q_set[q] = 1;
+    ctx->dirty = true;
+    return BLS_OK;
+}
+
+extern "C" int bls_sizes(const bls_ctx *ctx, int64_t max_nnz, size_t *plan_ws_bytes, size_t *pooled_bytes,
+                         size_t *send_bytes, size_t *slot_bytes)
+{
+    if (!ctx || max_nnz < 0) return BLS_EINVAL;
+    if (plan_ws_bytes) *plan_ws_bytes = bls_plan_ws_bytes(ctx);
+    if (pooled_bytes) *pooled_bytes = ctx->slot_bytes;
+    if (send_bytes) *send_bytes = ctx->slot_bytes;
+    if (slot_bytes) *slot_bytes = ctx->slot_bytes;
+    return BLS_OK;
+}
+
+extern "C" int bls_pooled_counts(const bls_ctx *ctx, int64_t *pcount, int64_t *psdispl, int64_t *prcount, int64_t *prdispl)
+{
+    if (!ctx) return BLS_EINVAL;
+    const int P = ctx->P;
+    for (int d = 0; d < P; ++d) {
+        int64_t run = 0;
+        for (int s = 0; s < P; ++s) {
+            const int64_t n = (int64_t)ctx->n_loc[d] * (ctx->first[s + 1] - ctx->first[s]) * ctx->D;
+            if (pcount) pcount[d * P + s] = n;
+            if (psdispl) psdispl[d * P + s] = run;
+            if (prcount) prcount[s * P + d] = n;
+            run += n;
+        }
+    }
+    if (prdispl)
+        for (int s = 0; s < P; ++s) {
+            int64_t run = 0;
+            for (int d = 0; d < P; ++d) {
+                prdispl[s * P + d] = run;
+                run += (int64_t)ctx->n_loc[d] * (ctx->first[s + 1] - ctx->first[s]) * ctx->D;
+            }
+        }
+    return BLS_OK;
+}
+
+// ---- descriptor upload --------------------------------------------------------------
+
+namespace {
+struct BlobWriter {
+    std::vector<char> host;
+    template <class V> size_t put(const std::vector<V> &v)
+    {
+        size_t at = (host.size() + 15) & ~size_t(15);
+        host.resize(at + v.size() * sizeof(V));
+        if (!v.empty()) memcpy(host.data() + at, v.data(), v.size() * sizeof(V));
+        return at;
+    }
+};
+}  // namespace
+
+int bls_commit(bls_ctx *ctx)
+{
+    for (int q = 0; q < ctx->Q; ++q)
+        if (!ctx->q_set[q]) return bls_fail(ctx, BLS_EINVAL, "a table shard has not been set (bls_set_shard)");
+    int dev = -1;
+    BLS_HIP(ctx, hipGetDevice(&dev));
+    if (ctx->device >= 0 && dev != ctx->device) return bls_fail(ctx, BLS_EINVAL, "context used on a different device than before");
+    if (!ctx->dirty && ctx->blob) return BLS_OK;
+
+    BlobWriter w;
+    std::vector<int32_t> errflag(4, 0);
+    const size_t o_err = w.put(errflag);
+    const size_t o_first = w.put(ctx->first), o_nloc = w.put(ctx->n_loc), o_nsum = w.put(ctx->nsum);
+    const size_t o_rows = w.put(ctx->rows), o_rps = w.put(ctx->rps), o_tq = w.put(ctx->t_q);
+    const size_t o_qt = w.put(ctx->q_t), o_qd = w.put(ctx->q_d), o_qbase = w.put(ctx->q_base), o_qrows = w.put(ctx->q_rows);
+    if (!ctx->blob) {
+        BLS_HIP(ctx, hipMalloc(&ctx->blob, w.host.size()));
+        ctx->blob_bytes = w.host.size();
+        ctx->device = dev;
+    } else {
+        BLS_HIP(ctx, hipDeviceSynchronize());   // earlier kernels may still read the old tables
+    }
+    BLS_HIP(ctx, hipMemcpy(ctx->blob, w.host.data(), w.host.size(), hipMemcpyHostToDevice));
+    char *b = (char *)ctx->blob;
+    DevDesc &d = ctx->desc;
+    d.P = ctx->P; d.T = ctx->T; d.D = ctx->D; d.F = ctx->F; d.Q = ctx->Q; d.part_kind = ctx->part_kind; d.dtype = ctx->dtype;
+    d.pad0 = 0; d.B = ctx->B; d.Bq = (uint32_t)(ctx->B / ctx->P); d.Br = (uint32_t)(ctx->B % ctx->P); d.nseg = ctx->nseg;
+    d.err = (int32_t *)(b + o_err);
+    d.first = (const int64_t *)(b + o_first); d.n_loc = (const int32_t *)(b + o_nloc); d.nsum = (const int32_t *)(b + o_nsum);
+    d.rows = (const int64_t *)(b + o_rows); d.rps = (const int64_t *)(b + o_rps); d.t_q = (const int32_t *)(b + o_tq);
+    d.q_t = (const int32_t *)(b + o_qt); d.q_d = (const int32_t *)(b + o_qd);
+    d.q_base = (const void *const *)(b + o_qbase); d.q_rows = (const int64_t *)(b + o_qrows);
+    ctx->dirty = false;
+    return BLS_OK;
+}
+
+// ---- entry points that launch kernels -------------------------------------------------
+
+extern "C" int bls_plan(bls_ctx *ctx, const int64_t *d_indices, const int64_t *d_offsets, int64_t nnz,
+                        int64_t *d_sendcounts, int64_t *d_sdispls, int64_t *d_recvcounts, int64_t *d_rdispls,
+                        int64_t *d_ridx, int64_t *d_segoff, int64_t *d_perm, void *d_ws, size_t ws_bytes, void *hip_stream)
+{
+    if (!ctx) return BLS_EINVAL;
+    if (nnz < 0 || !d_offsets || !d_sendcounts || !d_sdispls || !d_recvcounts || !d_rdispls || !d_segoff || !d_ws)
+        return bls_fail(ctx, BLS_EINVAL, "bls_plan: NULL argument or negative nnz");
+    if (nnz > 0 && (!d_indices || !d_ridx)) return bls_fail(ctx, BLS_EINVAL, "bls_plan: NULL indices or ridx with nnz > 0");
+    if (ws_bytes < bls_plan_ws_bytes(ctx)) return bls_fail(ctx, BLS_ENOSPC, "bls_plan: workspace too small");
+    if (((uintptr_t)d_ws & 7u) != 0) return bls_fail(ctx, BLS_EINVAL, "bls_plan: workspace must be 8-byte aligned");
+    int rc = bls_commit(ctx);
+    if (rc) return rc;
+    return bls_launch_plan(ctx, d_indices, d_offsets, nnz, d_sendcounts, d_sdispls, d_recvcounts, d_rdispls, d_ridx,
+                           d_segoff, d_perm, d_ws, ws_bytes, (hipStream_t)hip_stream);
+}
+
+extern "C" int bls_embbag_pool(bls_ctx *ctx, const int64_t *d_ridx, const int64_t *d_segoff, int64_t nnz,
+                               float *d_pooled, void *hip_stream)
+{
+    if (!ctx) return BLS_EINVAL;
+    if (nnz < 0 || !d_segoff || !d_pooled || (nnz > 0 && !d_ridx)) return bls_fail(ctx, BLS_EINVAL, "bls_embbag_pool: NULL argument");
+    if (((uintptr_t)d_pooled & 15u) != 0) return bls_fail(ctx, BLS_EINVAL, "bls_embbag_pool: output must be 16-byte aligned");
+    int rc = bls_commit(ctx);
+    if (rc) return rc;
+    return bls_launch_pool(ctx, d_ridx, d_segoff, nnz, d_pooled, (hipStream_t)hip_stream);
+}
+
+extern "C" int bls_pack(bls_ctx *ctx, const float *d_pooled, float *d_send, void *hip_stream)
+{
+    if (!ctx) return BLS_EINVAL;
+    if (!d_pooled || !d_send || d_pooled == d_send) return bls_fail(ctx, BLS_EINVAL, "bls_pack: NULL or aliased buffers");
+    if ((((uintptr_t)d_pooled | (uintptr_t)d_send) & 15u) != 0) return bls_fail(ctx, BLS_EINVAL, "bls_pack: buffers must be 16-byte aligned");
+    int rc = bls_commit(ctx);
+    if (rc) return rc;
+    return bls_launch_pack(ctx, d_pooled, d_send, (hipStream_t)hip_stream);
+}
+
+// ---- ring -------------------------------------------------------------------------------
+
+extern "C" int bls_set_ring(bls_ctx *ctx, void *d_slots, size_t bytes)
+{
+    if (!ctx) return BLS_EINVAL;
+    if (!d_slots || ((uintptr_t)d_slots & 15u) != 0) return bls_fail(ctx, BLS_EINVAL, "bls_set_ring: NULL or misaligned ring");
+    if (bytes < (size_t)ctx->K * ctx->slot_bytes) return bls_fail(ctx, BLS_ENOSPC, "bls_set_ring: ring smaller than K slots");
+    if (ctx->head != ctx->tail) return bls_fail(ctx, BLS_EORDER, "bls_set_ring: iterations in flight");
+    ctx->slots = (char *)d_slots;
+    return BLS_OK;
+}
+
+extern "C" int bls_ring_state(const bls_ctx *ctx, int64_t *head, int64_t *tail, int32_t *K)
+{
+    if (!ctx) return BLS_EINVAL;
+    if (head) *head = ctx->head;
+    if (tail) *tail = ctx->tail;
+    if (K) *K = ctx->K;
+    return BLS_OK;
+}
+
+extern "C" int bls_ring_advance(bls_ctx *ctx, int64_t *iter_out, int32_t *slot_out, void *hip_stream)
+{
+    if (!ctx || !iter_out || !slot_out) return BLS_EINVAL;
+    if (ctx->head - ctx->tail >= ctx->K) return bls_fail(ctx, BLS_ERING_FULL, "bls_ring_advance: K iterations in flight");
+    const int64_t j = ctx->head;
+    const int slot = (int)(j % ctx->K);
+    RingSlot &r = ctx->ring[slot];
+    if (r.has_released)   // the stream that refills the slot must see the earlier copy-out finished
+        BLS_HIP(ctx, hipStreamWaitEvent((hipStream_t)hip_stream, r.released, 0));
+    r.state = 1;
+    r.iter = j;
+    ctx->head = j + 1;
+    *iter_out = j;
+    *slot_out = slot;
+    return BLS_OK;
+}
+
+static int ensure_events(bls_ctx *ctx, RingSlot &r)
+{
+    if (!r.filled) BLS_HIP(ctx, hipEventCreateWithFlags(&r.filled, hipEventDisableTiming));
+    if (!r.released) BLS_HIP(ctx, hipEventCreateWithFlags(&r.released, hipEventDisableTiming));
+    return BLS_OK;
+}
+
+extern "C" int bls_alltoallv_local(bls_ctx *ctx, const float *d_send, int32_t slot, void *hip_stream)
+{
+    if (!ctx) return BLS_EINVAL;
+    if (!d_send || ((uintptr_t)d_send & 15u) != 0) return bls_fail(ctx, BLS_EINVAL, "bls_alltoallv_local: NULL or misaligned send buffer");
+    if (!ctx->slots) return bls_fail(ctx, BLS_EINVAL, "bls_alltoallv_local: no ring (bls_set_ring)");
+    if (slot < 0 || slot >= ctx->K) return bls_fail(ctx, BLS_EINVAL, "bls_alltoallv_local: slot out of range");
+    RingSlot &r = ctx->ring[slot];
+    if (r.state != 1 || r.iter != ctx->head - 1)
+        return bls_fail(ctx, BLS_EORDER, "bls_alltoallv_local: slot does not belong to the iteration just started");
+    int rc = bls_commit(ctx);
+    if (rc) return rc;
+    rc = ensure_events(ctx, r);
+    if (rc) return rc;
+    rc = bls_launch_exchange(ctx, d_send, (float *)(ctx->slots + (size_t)slot * ctx->slot_bytes), (hipStream_t)hip_stream);
+    if (rc) return rc;
+    BLS_HIP(ctx, hipEventRecord(r.filled, (hipStream_t)hip_stream));
+    r.state = 2;
+    return BLS_OK;
+}
+
+extern "C" int bls_unpack(bls_ctx *ctx, int64_t iter, float *d_out, void *hip_stream)
+{
+    if (!ctx) return BLS_EINVAL;
+    if (ctx->head == ctx->tail) return bls_fail(ctx, BLS_ERING_EMPTY, "bls_unpack: nothing in flight");
+    if (iter != ctx->tail) return bls_fail(ctx, BLS_EORDER, "bls_unpack: not the oldest iteration in flight");
+    if (!d_out || ((uintptr_t)d_out & 15u) != 0) return bls_fail(ctx, BLS_EINVAL, "bls_unpack: NULL or misaligned output");
+    const int slot = (int)(iter % ctx->K);
+    RingSlot &r = ctx->ring[slot];
+    if (r.state != 2) return bls_fail(ctx, BLS_EORDER, "bls_unpack: the iteration's exchange has not been issued");
+    int rc = bls_commit(ctx);
+    if (rc) return rc;
+    BLS_HIP(ctx, hipStreamWaitEvent((hipStream_t)hip_stream, r.filled, 0));
+    rc = bls_launch_unpack(ctx, (const float *)(ctx->slots + (size_t)slot * ctx->slot_bytes), d_out, (hipStream_t)hip_stream);
+    if (rc) return rc;
+    BLS_HIP(ctx, hipEventRecord(r.released, (hipStream_t)hip_stream));
+    r.has_released = true;
+    r.state = 0;
+    ctx->tail = iter + 1;
+    return BLS_OK;
+}
+
+extern "C" int bls_check(bls_ctx *ctx, void *hip_stream)
+{
+    if (!ctx) return BLS_EINVAL;
+    BLS_HIP(ctx, hipStreamSynchronize((hipStream_t)hip_stream));
+    if (!ctx->blob) return BLS_OK;
+    int32_t flag = 0;
+    BLS_HIP(ctx, hipMemcpy(&flag, ctx->desc.err, sizeof(flag), hipMemcpyDeviceToHost));
+    if (flag) {
+        int32_t zero = 0;
+        BLS_HIP(ctx, hipMemcpy(ctx->desc.err, &zero, sizeof(zero), hipMemcpyHostToDevice));
+        return bls_fail(ctx, BLS_ERANGE, "a kernel skipped an out-of-range index, offset or segment");
+    }
+    return BLS_OK;
+}
+
+extern "C" const char *bls_last_error(const bls_ctx *ctx)
+{
+    return ctx ? ctx->err.c_str() : "NULL context";
+}

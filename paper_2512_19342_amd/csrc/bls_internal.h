@@ -1,0 +1,126 @@
+// Internal declarations shared by the libbls translation units (host context,
+// device-side descriptor, launch helpers).  Not part of the public interface.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include <string>
+#include <vector>
+
+#include "bls.h"
+
+// Device-side view of the problem.  Passed to kernels by value; the arrays live in one
+// small device allocation owned by the context.
+//
+// q numbers the (owner, local table) pairs in owner-major order, q = nsum[d] + t_loc,
+// 0 <= q < Q = F*T.  Pooled vector (q, b) sits at vector index
+//   y(q,b)     = q*B + b                                        in the pooled buffer Y,
+//   sigma(q,b) = nsum[d]*B + n_loc[d]*first[s] + t_loc*n + b_loc in segment / send order,
+//   rho(q,b)   = Q*first[s] + q*n + b_loc                        in receive order,
+// with s the requester of b, n its mini-batch size and b_loc = b - first[s].
+struct DevDesc {
+    int32_t P, T, D, F, Q, part_kind, dtype, pad0;
+    int64_t B;
+    uint32_t Bq, Br;             // B / P and B % P
+    int64_t nseg;                // F*T*B
+    const int64_t *first;        // [P+1] first sample of every mini-batch
+    const int32_t *n_loc;        // [P]
+    const int32_t *nsum;         // [P+1] exclusive running sum of n_loc
+    const int64_t *rows;         // [T]
+    const int64_t *rps;          // [T] rows per shard (row-wise); rows (table-wise)
+    const int32_t *t_q;          // [T] q of table t at its owner (table-wise); t (row-wise, add d*T)
+    const int32_t *q_t;          // [Q]
+    const int32_t *q_d;          // [Q]
+    const void *const *q_base;   // [Q] shard storage
+    const int64_t *q_rows;       // [Q] rows in the shard
+    int32_t *err;                // error flag, set to 1 by kernels that skip a bad item
+};
+
+struct RingSlot {
+    int state = 0;               // 0 free, 1 acquired (exchange not yet enqueued), 2 filled
+    int64_t iter = -1;
+    hipEvent_t filled = nullptr;   // recorded after the exchange into the slot
+    hipEvent_t released = nullptr; // recorded after the slot was copied out
+    bool has_released = false;
+};
+
+struct bls_ctx {
+    // configuration (host copies)
+    int32_t P = 0, T = 0, D = 0, k = 0, K = 1, F = 1, Q = 0, dtype = 0, part_kind = 0;
+    int64_t B = 0;
+    std::vector<int64_t> rows, rps, first, q_rows;
+    std::vector<int32_t> owner, n_loc, nsum, t_loc, t_q, q_t, q_d;
+    std::vector<const void *> q_base;
+    std::vector<uint8_t> q_set;
+    int64_t nseg = 0, nvec = 0;   // nvec = nseg = F*T*B pooled vectors per iteration
+
+    // device side
+    int device = -1;
+    void *blob = nullptr;         // descriptor arrays + error flag
+    size_t blob_bytes = 0;
+    bool dirty = true;            // host tables changed since the last upload
+    DevDesc desc{};
+
+    // ring
+    char *slots = nullptr;
+    size_t slot_bytes = 0;
+    int64_t head = 0, tail = 0;   // next iteration to start, oldest in flight
+    std::vector<RingSlot> ring;
+
+    std::string err;
+};
+
+// ---- helpers shared by the translation units -------------------------------------
+int bls_fail(bls_ctx *ctx, int code, const char *what);
+int bls_fail_hip(bls_ctx *ctx, hipError_t e, const char *what);
+int bls_commit(bls_ctx *ctx);   // upload descriptor tables if needed; requires every shard
+
+#define BLS_HIP(ctx, call)                                         \
+    do {                                                           \
+        hipError_t e_ = (call);                                    \
+        if (e_ != hipSuccess) return bls_fail_hip(ctx, e_, #call); \
+    } while (0)
+
+// launches, defined next to their kernels
+int bls_launch_plan(bls_ctx *ctx, const int64_t *idx, const int64_t *off, int64_t nnz, int64_t *sendcounts,
+                    int64_t *sdispls, int64_t *recvcounts, int64_t *rdispls, int64_t *ridx, int64_t *segoff,
+                    int64_t *perm, void *ws, size_t ws_bytes, hipStream_t st);
+size_t bls_plan_ws_bytes(const bls_ctx *ctx);
+int bls_launch_pool(bls_ctx *ctx, const int64_t *ridx, const int64_t *segoff, int64_t nnz, float *Y, hipStream_t st);
+int bls_launch_pack(bls_ctx *ctx, const float *Y, float *S, hipStream_t st);
+int bls_launch_exchange(bls_ctx *ctx, const float *S, float *R, hipStream_t st);
+int bls_launch_unpack(bls_ctx *ctx, const float *R, float *out, hipStream_t st);
+
+// ---- device helpers ----------------------------------------------------------------
+#ifdef __HIPCC__
+// Requester s of sample b, its position b_loc inside the mini-batch and the
+// mini-batch size n.  The first Br ranks hold Bq+1 samples, the rest Bq.
+__device__ __forceinline__ void bls_split_sample(const DevDesc &dd, uint32_t b, int &s, uint32_t &b_loc, uint32_t &n)
+{
+    const uint32_t big = dd.Br * (dd.Bq + 1u);
+    if (b < big) {
+        s = (int)(b / (dd.Bq + 1u));
+        b_loc = b - (uint32_t)s * (dd.Bq + 1u);
+        n = dd.Bq + 1u;
+    } else {
+        const uint32_t r = b - big;
+        const uint32_t q = r / dd.Bq;
+        s = (int)(dd.Br + q);
+        b_loc = r - q * dd.Bq;
+        n = dd.Bq;
+    }
+}
+
+__device__ __forceinline__ int64_t bls_sigma(const DevDesc &dd, int q, int s, uint32_t b_loc, uint32_t n)
+{
+    const int d = dd.q_d[q];
+    const int64_t ns = dd.nsum[d];
+    return ns * dd.B + (int64_t)dd.n_loc[d] * dd.first[s] + (int64_t)(q - ns) * n + b_loc;
+}
+
+__device__ __forceinline__ int64_t bls_rho(const DevDesc &dd, int q, int s, uint32_t b_loc, uint32_t n)
+{
+    return (int64_t)dd.Q * dd.first[s] + (int64_t)q * n + b_loc;
+}
+#endif

@@ -1,0 +1,356 @@
+// bls_plan: index bucketing by owning rank.
+//
+// Every lookup belongs to exactly one segment (owner d, requester s, local table, local
+// sample), and segments are numbered in owner order, so
+//   1. count   - the length of every segment (table-wise: the bag length; row-wise: one
+//                wavefront per bag splits its lookups over the P owners with ballots),
+//   2. scan    - an exclusive scan of the segment lengths (LDS-staged, three phases) gives
+//                segoff, and the alltoallv counts and displacements are differences of
+//                segoff at the (d, s) block edges - no atomics, no separate histogram,
+//   3. scatter - every lookup is written to segoff[segment] + its rank among the
+//                segment's earlier lookups (lane prefix counts), which is the stable order.
+#include <algorithm>
+
+#include "bls_internal.h"
+
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int kItems = 16;                       // scan items per thread
+constexpr int kChunk = kThreads * kItems;        // scan items per block
+
+__device__ __forceinline__ void flag_error(const DevDesc &dd) { atomicOr(dd.err, 1); }
+
+__device__ __forceinline__ int64_t wave_inclusive_scan(int64_t v, int lane)
+{
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        const int64_t u = __shfl_up(v, o, 64);
+        if (lane >= o) v += u;
+    }
+    return v;
+}
+
+// ---- 1. count ------------------------------------------------------------------------
+
+// Table-wise: one thread per (q, b); the segment is the whole bag.
+__global__ __launch_bounds__(kThreads) void plan_count_tablewise(DevDesc dd, const int64_t *__restrict__ off,
+                                                                 int64_t nnz, int64_t *__restrict__ seglen)
+{
+    const int q = blockIdx.y;
+    const uint32_t b = blockIdx.x * kThreads + threadIdx.x;
+    if (b >= (uint32_t)dd.B) return;
+    const int64_t g = (int64_t)dd.q_t[q] * dd.B + b;
+    const int64_t lo = off[g], hi = off[g + 1];
+    int64_t len = hi - lo;
+    if (lo < 0 || hi > nnz || len < 0) { flag_error(dd); len = 0; }
+    int s; uint32_t b_loc, n;
+    bls_split_sample(dd, b, s, b_loc, n);
+    seglen[bls_sigma(dd, q, s, b_loc, n)] = len;
+}
+
+__device__ __forceinline__ int owner_of_row(int64_t ix, int64_t rps)
+{
+    return rps <= 0xffffffffLL && ix <= 0xffffffffLL ? (int)((uint32_t)ix / (uint32_t)rps) : (int)(ix / rps);
+}
+
+// Row-wise: one wavefront per bag (t, b).  Lane o < P accumulates the number of the
+// bag's lookups that fall in owner o's block of rows.
+__global__ __launch_bounds__(kThreads) void plan_count_rowwise(DevDesc dd, const int64_t *__restrict__ idx,
+                                                               const int64_t *__restrict__ off, int64_t nnz,
+                                                               int64_t *__restrict__ seglen)
+{
+    const int lane = threadIdx.x & 63;
+    const int t = blockIdx.y;
+    const uint32_t b = blockIdx.x * (kThreads / 64) + (threadIdx.x >> 6);
+    if (b >= (uint32_t)dd.B) return;                     // uniform per wavefront
+    const int64_t g = (int64_t)t * dd.B + b;
+    const int64_t lo = off[g], hi = off[g + 1];
+    int64_t len = hi - lo;
+    if (lo < 0 || hi > nnz || len < 0) { if (lane == 0) flag_error(dd); len = 0; }
+    const int64_t rows = dd.rows[t], rps = dd.rps[t];
+    int64_t cnt = 0;
+    for (int64_t c = 0; c < len; c += 64) {
+        const int64_t j = c + lane;
+        int d = -1;
+        if (j < len) {
+            const int64_t ix = idx[lo + j];
+            if (ix < 0 || ix >= rows) flag_error(dd);
+            else d = owner_of_row(ix, rps);
+        }
+        for (int o = 0; o < dd.P; ++o) {
+            const unsigned long long m = __ballot(d == o);
+            if (lane == o) cnt += __popcll(m);
+        }
+    }
+    if (lane < dd.P) {
+        int s; uint32_t b_loc, n;
+        bls_split_sample(dd, b, s, b_loc, n);
+        seglen[bls_sigma(dd, lane * dd.T + t, s, b_loc, n)] = cnt;
+    }
+}
+
+// ---- 2. scan ---------------------------------------------------------------------------
+// In-place inclusive scan of v[0..n) (v = segoff + 1, holding segment lengths), so that
+// segoff becomes the exclusive scan with segoff[nseg] = total.
+
+__global__ __launch_bounds__(kThreads) void scan_block_sums(const int64_t *__restrict__ v, int64_t n,
+                                                            int64_t *__restrict__ sums)
+{
+    __shared__ int64_t part[kThreads / 64];
+    const int64_t base = (int64_t)blockIdx.x * kChunk;
+    int64_t a = 0;
+#pragma unroll
+    for (int k = 0; k < kItems; ++k) {
+        const int64_t i = base + k * kThreads + threadIdx.x;
+        if (i < n) a += v[i];
+    }
+    const int lane = threadIdx.x & 63;
+    a = wave_inclusive_scan(a, lane);
+    if (lane == 63) part[threadIdx.x >> 6] = a;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        int64_t tot = 0;
+        for (int w = 0; w < kThreads / 64; ++w) tot += part[w];
+        sums[blockIdx.x] = tot;
+    }
+}
+
+// One block: exclusive scan of the block sums, in place.
+__global__ __launch_bounds__(kThreads) void scan_spine(int64_t *__restrict__ sums, int64_t nblk)
+{
+    __shared__ int64_t part[kThreads / 64];
+    __shared__ int64_t carry_s;
+    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+    if (threadIdx.x == 0) carry_s = 0;
+    __syncthreads();
+    for (int64_t base = 0; base < nblk; base += kThreads) {
+        const int64_t i = base + threadIdx.x;
+        const int64_t x = i < nblk ? sums[i] : 0;
+        int64_t inc = wave_inclusive_scan(x, lane);
+        if (lane == 63) part[wv] = inc;
+        __syncthreads();
+        int64_t before = carry_s;
+        for (int w = 0; w < wv; ++w) before += part[w];
+        if (i < nblk) sums[i] = before + inc - x;
+        __syncthreads();
+        if (threadIdx.x == kThreads - 1) carry_s = before + inc;
+        __syncthreads();
+    }
+}
+
+__global__ __launch_bounds__(kThreads) void scan_apply(int64_t *__restrict__ v, int64_t n,
+                                                       const int64_t *__restrict__ sums, int64_t *__restrict__ head)
+{
+    // items staged in LDS so that global accesses stay coalesced while every thread owns a
+    // contiguous run; one padding word per run keeps the per-thread walks off one bank
+    __shared__ int64_t tile[kChunk + kThreads];
+    __shared__ int64_t part[kThreads / 64];
+    const int64_t base = (int64_t)blockIdx.x * kChunk;
+    if (blockIdx.x == 0 && threadIdx.x == 0) *head = 0;   // segoff[0]
+#pragma unroll
+    for (int k = 0; k < kItems; ++k) {
+        const int e = k * kThreads + threadIdx.x;
+        const int64_t i = base + e;
+        tile[e + e / kItems] = i < n ? v[i] : 0;
+    }
+    __syncthreads();
+    const int mine = threadIdx.x * (kItems + 1);
+    int64_t run = 0;
+#pragma unroll
+    for (int k = 0; k < kItems; ++k) { run += tile[mine + k]; tile[mine + k] = run; }
+    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+    const int64_t inc = wave_inclusive_scan(run, lane);
+    if (lane == 63) part[wv] = inc;
+    __syncthreads();
+    int64_t before = sums[blockIdx.x] + inc - run;
+    for (int w = 0; w < wv; ++w) before += part[w];
+#pragma unroll
+    for (int k = 0; k < kItems; ++k) tile[mine + k] += before;
+    __syncthreads();
+#pragma unroll
+    for (int k = 0; k < kItems; ++k) {
+        const int e = k * kThreads + threadIdx.x;
+        const int64_t i = base + e;
+        if (i < n) v[i] = tile[e + e / kItems];
+    }
+}
+
+// One block: counts and displacements from segoff at the (d, s) block edges.
+// sabs[s][d] / rabs[d][s]: absolute start of bucket (s, d) in requester / owner order.
+__global__ __launch_bounds__(kThreads) void plan_finish(DevDesc dd, const int64_t *__restrict__ segoff,
+                                                        int64_t *__restrict__ sendcounts, int64_t *__restrict__ sdispls,
+                                                        int64_t *__restrict__ recvcounts, int64_t *__restrict__ rdispls,
+                                                        int64_t *__restrict__ sabs, int64_t *__restrict__ rabs)
+{
+    __shared__ int64_t rowtot[64];
+    const int P = dd.P;
+    for (int e = threadIdx.x; e < P * P; e += kThreads) {
+        const int d = e / P, s = e - d * P;
+        const int64_t edge0 = (int64_t)dd.nsum[d] * dd.B;
+        const int64_t lo = segoff[edge0 + (int64_t)dd.n_loc[d] * dd.first[s]];
+        const int64_t hi = segoff[edge0 + (int64_t)dd.n_loc[d] * dd.first[s + 1]];
+        recvcounts[d * P + s] = hi - lo;
+        rdispls[d * P + s] = lo - segoff[edge0];
+        rabs[d * P + s] = lo;
+        sendcounts[s * P + d] = hi - lo;
+    }
+    __syncthreads();
+    if (threadIdx.x < P) {
+        const int s = threadIdx.x;
+        int64_t run = 0;
+        for (int d = 0; d < P; ++d) { sdispls[s * P + d] = run; run += sendcounts[s * P + d]; }
+        rowtot[s] = run;
+    }
+    __syncthreads();
+    if (threadIdx.x < P) {
+        const int s = threadIdx.x;
+        int64_t sbase = 0;
+        for (int r = 0; r < s; ++r) sbase += rowtot[r];
+        for (int d = 0; d < P; ++d) sabs[s * P + d] = sbase + sdispls[s * P + d];
+    }
+}
+
+// ---- 3. scatter ------------------------------------------------------------------------
+
+// Table-wise: G lanes copy one bag to its place in owner order.
+template <int G>
+__global__ __launch_bounds__(kThreads) void plan_scatter_tablewise(DevDesc dd, const int64_t *__restrict__ idx,
+                                                                   const int64_t *__restrict__ off, int64_t nnz,
+                                                                   const int64_t *__restrict__ segoff,
+                                                                   int64_t *__restrict__ ridx, int64_t *__restrict__ perm,
+                                                                   const int64_t *__restrict__ sabs,
+                                                                   const int64_t *__restrict__ rabs)
+{
+    const int q = blockIdx.y;
+    const int li = threadIdx.x & (G - 1);
+    const uint32_t b = blockIdx.x * (kThreads / G) + threadIdx.x / G;
+    if (b >= (uint32_t)dd.B) return;
+    const int t = dd.q_t[q];
+    const int64_t g = (int64_t)t * dd.B + b;
+    const int64_t lo = off[g], hi = off[g + 1];
+    const int64_t len = hi - lo;
+    if (lo < 0 || hi > nnz || len < 0) return;           // flagged by the count kernel
+    int s; uint32_t b_loc, n;
+    bls_split_sample(dd, b, s, b_loc, n);
+    const int64_t dst = segoff[bls_sigma(dd, q, s, b_loc, n)];
+    if (dst < 0 || dst + len > nnz) { flag_error(dd); return; }
+    const int d = dd.q_d[q];
+    const int64_t rows = dd.rows[t];
+    const int64_t to_send = perm ? sabs[s * dd.P + d] - rabs[d * dd.P + s] : 0;
+    for (int64_t j = li; j < len; j += G) {
+        int64_t ix = idx[lo + j];
+        if (ix < 0 || ix >= rows) { flag_error(dd); ix = 0; }
+        ridx[dst + j] = ix;
+        if (perm) perm[lo + j] = dst + j + to_send;
+    }
+}
+
+// Row-wise: one wavefront per bag.  Lane o < P holds the start of owner o's segment and
+// how many of the bag's lookups it has already received; a lookup's place is that start
+// plus the number of earlier lanes with the same owner.
+__global__ __launch_bounds__(kThreads) void plan_scatter_rowwise(DevDesc dd, const int64_t *__restrict__ idx,
+                                                                 const int64_t *__restrict__ off, int64_t nnz,
+                                                                 const int64_t *__restrict__ segoff,
+                                                                 int64_t *__restrict__ ridx, int64_t *__restrict__ perm,
+                                                                 const int64_t *__restrict__ sabs,
+                                                                 const int64_t *__restrict__ rabs)
+{
+    const int lane = threadIdx.x & 63;
+    const int t = blockIdx.y;
+    const uint32_t b = blockIdx.x * (kThreads / 64) + (threadIdx.x >> 6);
+    if (b >= (uint32_t)dd.B) return;                     // uniform per wavefront
+    const int64_t g = (int64_t)t * dd.B + b;
+    const int64_t lo = off[g], hi = off[g + 1];
+    const int64_t len = hi - lo;
+    if (lo < 0 || hi > nnz || len < 0) return;           // flagged by the count kernel
+    const int64_t rows = dd.rows[t], rps = dd.rps[t];
+    int s; uint32_t b_loc, n;
+    bls_split_sample(dd, b, s, b_loc, n);
+    int64_t next = 0, to_send = 0;                        // lane o: next free place of owner o
+    if (lane < dd.P) {
+        next = segoff[bls_sigma(dd, lane * dd.T + t, s, b_loc, n)];
+        if (perm) to_send = sabs[s * dd.P + lane] - rabs[lane * dd.P + s];
+    }
+    const unsigned long long below = (1ull << lane) - 1ull;
+    for (int64_t c = 0; c < len; c += 64) {
+        const int64_t j = c + lane;
+        int d = -1;
+        int64_t r = 0;
+        if (j < len) {
+            const int64_t ix = idx[lo + j];
+            if (ix >= 0 && ix < rows) { d = owner_of_row(ix, rps); r = ix - (int64_t)d * rps; }
+        }
+        int rank = 0, add = 0;
+        for (int o = 0; o < dd.P; ++o) {
+            const unsigned long long m = __ballot(d == o);
+            if (d == o) rank = __popcll(m & below);
+            if (lane == o) add = __popcll(m);
+        }
+        const int src = d < 0 ? 0 : d;
+        const int64_t place = __shfl(next, src, 64) + rank;
+        const int64_t shift = __shfl(to_send, src, 64);
+        if (d >= 0) {
+            if (place >= 0 && place < nnz) {
+                ridx[place] = r;
+                if (perm) perm[lo + j] = place + shift;
+            } else flag_error(dd);
+        }
+        next += add;
+    }
+}
+
+int64_t scan_blocks(int64_t n) { return (n + kChunk - 1) / kChunk; }
+
+}  // namespace
+
+size_t bls_plan_ws_bytes(const bls_ctx *ctx)
+{
+    return (size_t)(scan_blocks(ctx->nseg) + 2 * ctx->P * ctx->P + 2) * sizeof(int64_t);
+}
+
+int bls_launch_plan(bls_ctx *ctx, const int64_t *idx, const int64_t *off, int64_t nnz, int64_t *sendcounts,
+                    int64_t *sdispls, int64_t *recvcounts, int64_t *rdispls, int64_t *ridx, int64_t *segoff,
+                    int64_t *perm, void *ws, size_t ws_bytes, hipStream_t st)
+{
+    (void)ws_bytes;
+    const DevDesc &dd = ctx->desc;
+    const int64_t nseg = ctx->nseg, nblk = scan_blocks(nseg);
+    int64_t *sums = (int64_t *)ws;
+    int64_t *sabs = sums + nblk, *rabs = sabs + ctx->P * ctx->P;
+    const uint32_t B = (uint32_t)ctx->B;
+    const bool rowwise = ctx->part_kind == BLS_ROW_WISE;
+
+    if (rowwise) {
+        dim3 grid((B + kThreads / 64 - 1) / (kThreads / 64), ctx->T);
+        plan_count_rowwise<<<grid, kThreads, 0, st>>>(dd, idx, off, nnz, segoff + 1);
+    } else {
+        dim3 grid((B + kThreads - 1) / kThreads, ctx->Q);
+        plan_count_tablewise<<<grid, kThreads, 0, st>>>(dd, off, nnz, segoff + 1);
+    }
+    scan_block_sums<<<dim3((unsigned)nblk), kThreads, 0, st>>>(segoff + 1, nseg, sums);
+    scan_spine<<<1, kThreads, 0, st>>>(sums, nblk);
+    scan_apply<<<dim3((unsigned)nblk), kThreads, 0, st>>>(segoff + 1, nseg, sums, segoff);
+    plan_finish<<<1, kThreads, 0, st>>>(dd, segoff, sendcounts, sdispls, recvcounts, rdispls, sabs, rabs);
+    if (nnz > 0) {
+        if (rowwise) {
+            dim3 grid((B + kThreads / 64 - 1) / (kThreads / 64), ctx->T);
+            plan_scatter_rowwise<<<grid, kThreads, 0, st>>>(dd, idx, off, nnz, segoff, ridx, perm, sabs, rabs);
+        } else {
+            // lanes per bag from the mean bag length
+            const int64_t mean = nnz / std::max<int64_t>(1, (int64_t)ctx->T * ctx->B);
+            if (mean >= 24) {
+                dim3 grid((B + kThreads / 32 - 1) / (kThreads / 32), ctx->Q);
+                plan_scatter_tablewise<32><<<grid, kThreads, 0, st>>>(dd, idx, off, nnz, segoff, ridx, perm, sabs, rabs);
+            } else if (mean >= 6) {
+                dim3 grid((B + kThreads / 8 - 1) / (kThreads / 8), ctx->Q);
+                plan_scatter_tablewise<8><<<grid, kThreads, 0, st>>>(dd, idx, off, nnz, segoff, ridx, perm, sabs, rabs);
+            } else {
+                dim3 grid((B + kThreads - 1) / kThreads, ctx->Q);
+                plan_scatter_tablewise<1><<<grid, kThreads, 0, st>>>(dd, idx, off, nnz, segoff, ridx, perm, sabs, rabs);
+            }
+        }
+    }
+    BLS_HIP(ctx, hipGetLastError());
+    return BLS_OK;
+}

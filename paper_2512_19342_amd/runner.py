@@ -1,0 +1,82 @@
+"""Buffer plumbing around one libbls context: allocates the device buffers the C entry
+points need (torch is used for memory and streams only) and issues the calls of one
+iteration in path order.  No arithmetic happens here."""
+from __future__ import annotations
+
+from typing import List, Optional
+
+import torch
+
+from . import bls
+
+
+class Pipeline:
+    """Device buffers + one Context for a fixed problem shape.
+
+    ``w`` is any object with P, T, D, k, B, rows, table_owner, table_dtype ("fp32"/"fp16")
+    and part_kind; ``tables`` are the T full tables (global row numbering) on the GPU.
+    Row-wise shards are views into those tables.
+    """
+
+    def __init__(self, w, tables: List[torch.Tensor], max_nnz: int, want_perm: bool = False):
+        dev = tables[0].device
+        assert dev.type == "cuda", "the hot path runs on the GPU only"
+        self.w, self.dev, self.max_nnz = w, dev, int(max_nnz)
+        dt = bls.BLS_FP16 if w.table_dtype == "fp16" else bls.BLS_FP32
+        self.ctx = bls.Context(w.P, w.T, w.D, w.k, w.B, w.rows, w.table_owner, dt, w.part_kind)
+        c = self.ctx
+        for t, tab in enumerate(tables):
+            assert tab.is_contiguous() and tab.shape == (w.rows[t], w.D)
+            if w.part_kind == bls.BLS_TABLE_WISE:
+                c.bls_set_shard(t, w.table_owner[t], tab)
+            else:
+                rps = -(-w.rows[t] // w.P)
+                for d in range(w.P):
+                    lo, hi = min(d * rps, w.rows[t]), min((d + 1) * rps, w.rows[t])
+                    if hi == lo:
+                        continue                        # empty shard: nothing to hand over
+                    shard = tab[lo:hi]
+                    if shard.data_ptr() % 16:
+                        shard = shard.clone()
+                    c.bls_set_shard(t, d, shard)
+        sz = c.bls_sizes(self.max_nnz)
+        pp = w.P * w.P
+        i64 = dict(dtype=torch.int64, device=dev)
+        self.sendcounts, self.sdispls = torch.zeros(pp, **i64), torch.zeros(pp, **i64)
+        self.recvcounts, self.rdispls = torch.zeros(pp, **i64), torch.zeros(pp, **i64)
+        self.ridx = torch.zeros(max(self.max_nnz, 1), **i64)
+        self.segoff = torch.zeros(c.n_vec + 1, **i64)
+        self.perm = torch.zeros(max(self.max_nnz, 1), **i64) if want_perm else None
+        self.ws = torch.zeros((sz["plan_ws_bytes"] + 7) // 8, **i64)
+        nfl = c.n_vec * w.D
+        self.pooled = torch.zeros(nfl, dtype=torch.float32, device=dev)
+        self.send = torch.zeros(nfl, dtype=torch.float32, device=dev)
+        self.slots = torch.zeros(c.K * nfl, dtype=torch.float32, device=dev)
+        c.bls_set_ring(self.slots)
+        self.n_floats = nfl
+
+    def new_out(self) -> torch.Tensor:
+        return torch.empty((self.w.B, self.w.T, self.w.D), dtype=torch.float32, device=self.dev)
+
+    # one iteration, split where the ring allows other iterations in between
+    def issue(self, indices: torch.Tensor, offsets: torch.Tensor, nnz: int, stream=None):
+        """plan, pool, pack, take a ring slot, exchange.  Returns (iteration, slot)."""
+        c = self.ctx
+        assert nnz <= self.max_nnz
+        c.bls_plan(indices, offsets, nnz, self.sendcounts, self.sdispls, self.recvcounts, self.rdispls,
+                   self.ridx, self.segoff, self.perm, self.ws, stream)
+        c.bls_embbag_pool(self.ridx, self.segoff, nnz, self.pooled, stream)
+        c.bls_pack(self.pooled, self.send, stream)
+        it, slot = c.bls_ring_advance(stream)
+        c.bls_alltoallv_local(self.send, slot, stream)
+        return it, slot
+
+    def complete(self, it: int, out: torch.Tensor, stream=None):
+        self.ctx.bls_unpack(it, out, stream)
+
+    def step(self, indices, offsets, nnz, out, stream=None):
+        it, _ = self.issue(indices, offsets, nnz, stream)
+        self.complete(it, out, stream)
+
+    def slot_view(self, slot: int) -> torch.Tensor:
+        return self.slots[slot * self.n_floats:(slot + 1) * self.n_floats]

@@ -1,0 +1,236 @@
+"""Parity of the HIP path against the CPU oracle, element by element, through the C ABI.
+
+Integer outputs (counts, displacements, ridx, segoff, perm) and every fp32 buffer (pooled,
+send, receive slot, output) must equal the oracle's bit for bit: both sides add a segment's
+rows in segment order from +0 and, for row-wise partitions, the P partial vectors in
+increasing owner rank.  Against the plain float64 definition the bound is
+|x - exact| <= tol * sum|terms| with tol = 1e-6 for fp32 tables and 1e-3 for fp16 storage.
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import synth
+
+pytestmark = pytest.mark.gpu
+
+TOL = {"fp32": 1e-6, "fp16": 1e-3}
+
+
+def case_of(w):
+    return oracle.Case(w.P, w.T, w.D, w.B, w.part_kind, w.rows, w.table_owner, 1 if w.table_dtype == "fp16" else 0)
+
+
+def bits(a):
+    a = np.ascontiguousarray(a)
+    return a.view(np.uint32) if a.dtype == np.float32 else a
+
+
+def run_gpu(w, tabs_cpu, batches, want_perm=True):
+    from paper_2512_19342_amd.runner import Pipeline
+    dev = torch.device("cuda:0")
+    tabs = [t.to(dev) for t in tabs_cpu]
+    max_nnz = max(int(off[-1]) for _, off in batches)
+    pipe = Pipeline(w, tabs, max_nnz, want_perm=want_perm)
+    res = []
+    for ix, off in batches:
+        nnz = int(off[-1])
+        out = pipe.new_out()
+        it, slot = pipe.issue(ix.to(dev), off.to(dev), nnz)
+        r = dict(sendcounts=pipe.sendcounts.cpu().numpy(), sdispls=pipe.sdispls.cpu().numpy(),
+                 recvcounts=pipe.recvcounts.cpu().numpy(), rdispls=pipe.rdispls.cpu().numpy(),
+                 ridx=pipe.ridx[:nnz].cpu().numpy(), segoff=pipe.segoff.cpu().numpy(),
+                 perm=pipe.perm[:nnz].cpu().numpy() if want_perm else None,
+                 Y=pipe.pooled.cpu().numpy(), S=pipe.send.cpu().numpy(), R=pipe.slot_view(slot).cpu().numpy())
+        pipe.complete(it, out)
+        pipe.ctx.bls_check()
+        r["Out"] = out.cpu().numpy()
+        res.append(r)
+    return res, pipe
+
+
+def check_against_oracle(w, tabs_cpu, batches, got):
+    c = case_of(w)
+    tabs_np = [t.numpy() for t in tabs_cpu]
+    for (ix, off), g in zip(batches, got):
+        ref = oracle.pipeline(c, tabs_np, ix.numpy(), off.numpy())
+        for k in ("sendcounts", "sdispls", "recvcounts", "rdispls", "ridx", "segoff", "perm"):
+            assert np.array_equal(g[k], ref[k]), k
+        for k in ("Y", "S", "R", "Out"):
+            assert np.array_equal(bits(g[k]), bits(ref[k])), k
+        o64, _ = oracle.embbag_plain(c, tabs_np, ix.numpy(), off.numpy(), want32=False)
+        mass = oracle.embbag_absmass(c, tabs_np, ix.numpy(), off.numpy())
+        assert np.all(np.abs(g["Out"].astype(np.float64) - o64) <= TOL[w.table_dtype] * mass)
+
+
+WORKLOADS = [(1, "full"), (2, "full"), (3, "small"), (4, "small"), (5, "small")]
+
+
+@pytest.mark.parametrize("cfg,size", WORKLOADS)
+def test_benchmark_workloads_match_oracle(cfg, size):
+    w = synth.workload(cfg, size)
+    tabs = [synth.make_table(w, t) for t in range(w.T)]
+    batches = [synth.make_batch(w, it) for it in range(2)]
+    got, _ = run_gpu(w, tabs, batches)
+    check_against_oracle(w, tabs, batches, got)
+
+
+def test_order_sensitive_values_rowwise_and_tablewise():
+    """Gaussian values make every reassociation visible in the last bit."""
+    for cfg in (3, 4):
+        w = synth.workload(cfg, "small")
+        w.values = "gauss"
+        tabs = [synth.make_table(w, t) for t in range(w.T)]
+        batches = [synth.make_batch(w, 7)]
+        got, _ = run_gpu(w, tabs, batches)
+        check_against_oracle(w, tabs, batches, got)
+
+
+EDGE = [
+    dict(P=1, T=2, D=4, B=3, part_kind=0, rows=[5, 6], bag=("fixed", 2)),
+    dict(P=2, T=3, D=4, B=4, part_kind=0, rows=[7, 5, 9], bag=("uniform", 0, 3)),            # empty bags
+    dict(P=3, T=4, D=8, B=7, part_kind=0, rows=[11, 3, 8, 20], bag=("uniform", 0, 4)),       # P does not divide B
+    dict(P=3, T=2, D=8, B=5, part_kind=1, rows=[10, 4], bag=("uniform", 0, 6)),              # ragged last shard
+    dict(P=4, T=3, D=4, B=8, part_kind=1, rows=[3, 17, 1], bag=("uniform", 1, 5)),           # empty shards
+    dict(P=3, T=5, D=7, B=50, part_kind=0, rows=[100, 30, 77, 5, 64], bag=("uniform", 0, 9)),   # odd D: scalar paths
+    dict(P=4, T=3, D=5, B=33, part_kind=1, rows=[101, 64, 9], bag=("uniform", 0, 70)),       # odd D, bags > 64
+    dict(P=2, T=3, D=24, B=70, part_kind=0, rows=[300, 200, 100], bag=("uniform", 0, 150)),  # 6 of 8 lanes, long bags
+    dict(P=2, T=2, D=320, B=40, part_kind=1, rows=[500, 333], bag=("uniform", 0, 20)),       # rows > 1 KB
+    dict(P=8, T=2, D=128, B=300, part_kind=1, rows=[4097, 1000], bag=("uniform", 0, 200)),   # long bags over 8 owners
+    dict(P=64, T=2, D=8, B=130, part_kind=1, rows=[5000, 129], bag=("uniform", 0, 90)),      # maximum P
+    dict(P=5, T=7, D=64, B=5000, part_kind=0, rows=[1000] * 7, bag=("uniform", 0, 3)),       # several scan blocks
+]
+
+
+@pytest.mark.parametrize("spec", EDGE)
+@pytest.mark.parametrize("dtype", ["fp32", "fp16"])
+def test_edge_shapes(spec, dtype):
+    w = synth.custom("edge", k=1, values="gauss", table_dtype=dtype, seed=23,
+                     index_dist=("zipf", 1.1), **spec)
+    tabs = [synth.make_table(w, t) for t in range(w.T)]
+    batches = [synth.make_batch(w, it) for it in range(2)]
+    got, _ = run_gpu(w, tabs, batches)
+    check_against_oracle(w, tabs, batches, got)
+
+
+def test_all_bags_empty():
+    w = synth.custom("empty", P=2, T=3, D=8, k=1, B=6, rows=[4, 5, 6], part_kind=1, bag=("fixed", 0))
+    tabs = [synth.make_table(w, t) for t in range(w.T)]
+    batches = [synth.make_batch(w, 0)]
+    assert int(batches[0][1][-1]) == 0
+    got, _ = run_gpu(w, tabs, batches)
+    check_against_oracle(w, tabs, batches, got)
+    assert not got[0]["Out"].any() and not np.signbit(got[0]["Out"]).any()
+
+
+@pytest.mark.parametrize("k", [0, 1, 2, 4])
+@pytest.mark.parametrize("cfg", [3, 4])
+def test_ring_deferred_completion(k, cfg):
+    """Completion deferred as long as the ring allows, on a second stream; every iteration
+    must still come out right (a slot overwritten too early would show) and in FIFO order."""
+    import paper_2512_19342_amd as B
+    from paper_2512_19342_amd.runner import Pipeline
+    w = synth.workload(cfg, "small")
+    w.k = k
+    dev = torch.device("cuda:0")
+    tabs_cpu = [synth.make_table(w, t) for t in range(w.T)]
+    tabs = [t.to(dev) for t in tabs_cpu]
+    N = 7
+    batches = [synth.make_batch(w, it) for it in range(N)]
+    pipe = Pipeline(w, tabs, max(int(o[-1]) for _, o in batches))
+    c = case_of(w)
+    tabs_np = [t.numpy() for t in tabs_cpu]
+    model = oracle.RingModel(k)
+    side = torch.cuda.Stream()
+    outs, pending = {}, []
+    for it, (ix, off) in enumerate(batches):
+        if len(model.in_flight) == model.K:
+            with pytest.raises(B.BlsError) as e:
+                pipe.ctx.bls_ring_advance()
+            assert e.value.code == B.BLS_ERING_FULL
+            if model.K > 1:
+                with pytest.raises(B.BlsError) as e:
+                    pipe.complete(pending[1], pipe.new_out())
+                assert e.value.code == B.BLS_EORDER
+            j = pending.pop(0)
+            model.retire(j)
+            outs[j] = pipe.new_out()
+            pipe.complete(j, outs[j], side)
+        j, slot = pipe.issue(ix.to(dev), off.to(dev), int(off[-1]))
+        assert (j, slot) == model.acquire()
+        pending.append(j)
+    for j, _ in model.drain():
+        assert pending.pop(0) == j
+        outs[j] = pipe.new_out()
+        pipe.complete(j, outs[j], side)
+    with pytest.raises(B.BlsError) as e:
+        pipe.complete(N, pipe.new_out())
+    assert e.value.code == B.BLS_ERING_EMPTY
+    torch.cuda.synchronize()
+    pipe.ctx.bls_check()
+    for it, (ix, off) in enumerate(batches):
+        ref = oracle.pipeline(c, tabs_np, ix.numpy(), off.numpy())["Out"]
+        assert np.array_equal(bits(outs[it].cpu().numpy()), bits(ref)), (k, it)
+
+
+def test_bad_inputs_are_flagged_not_faulted():
+    import paper_2512_19342_amd as B
+    from paper_2512_19342_amd.runner import Pipeline
+    for cfg in (3, 4):
+        w = synth.workload(cfg, "small")
+        dev = torch.device("cuda:0")
+        tabs = [synth.make_table(w, t).to(dev) for t in range(w.T)]
+        ix, off = synth.make_batch(w, 0)
+        nnz = int(off[-1])
+        pipe = Pipeline(w, tabs, nnz)
+        for how in ("index_high", "index_negative", "offsets_decrease", "offsets_past_end"):
+            bix, boff = ix.clone(), off.clone()
+            if how == "index_high":
+                bix[nnz // 2] = w.rows[0] + 10 ** 12
+            elif how == "index_negative":
+                bix[5] = -3
+            elif how == "offsets_decrease":
+                boff[10] = boff[12] + 5
+            else:
+                boff[-1] = nnz + 1000
+            pipe.step(bix.to(dev), boff.to(dev), nnz, pipe.new_out())
+            with pytest.raises(B.BlsError) as e:
+                pipe.ctx.bls_check()
+            assert e.value.code == B.BLS_ERANGE, how
+        # and the context still works afterwards
+        out = pipe.new_out()
+        pipe.step(ix.to(dev), off.to(dev), nnz, out)
+        pipe.ctx.bls_check()
+        c = case_of(w)
+        ref = oracle.pipeline(c, [t.cpu().numpy() for t in tabs], ix.numpy(), off.numpy())["Out"]
+        assert np.array_equal(bits(out.cpu().numpy()), bits(ref))
+
+
+def test_host_side_argument_errors():
+    import paper_2512_19342_amd as B
+    with pytest.raises(B.BlsError):
+        B.Context(0, 1, 4, 1, 4, [5], [0])
+    with pytest.raises(B.BlsError):
+        B.Context(2, 1, 4, 1, 1, [5], [0])               # B < P
+    with pytest.raises(B.BlsError):
+        B.Context(2, 1, 4, 1, 4, [5], [2])               # owner out of range
+    c = B.Context(2, 2, 4, 1, 4, [5, 6], [0, 1])
+    t0 = torch.zeros(5, 4, device="cuda")
+    with pytest.raises(B.BlsError):
+        c.bls_set_shard(0, 1, t0)                         # wrong owner
+    with pytest.raises(B.BlsError):
+        c.bls_set_shard(1, 1, t0)                         # wrong row count
+    c.bls_set_shard(0, 0, t0)
+    z = torch.zeros(64, dtype=torch.int64, device="cuda")
+    y = torch.zeros(64, device="cuda")
+    with pytest.raises(B.BlsError) as e:                  # shard of table 1 never set
+        c.bls_embbag_pool(z, z, 0, y)
+    assert e.value.code == B.BLS_EINVAL
+    c.bls_set_shard(1, 1, torch.zeros(6, 4, device="cuda"))
+    with pytest.raises(B.BlsError) as e:
+        c.bls_set_ring(torch.zeros(3, device="cuda"))
+    assert e.value.code == B.BLS_ENOSPC
+    with pytest.raises(B.BlsError) as e:
+        c.bls_alltoallv_local(y, 0)                       # no ring yet
+    assert e.value.code == B.BLS_EINVAL
