@@ -1,0 +1,198 @@
+#!/usr/bin/env python3
+"""Benchmark of the embedding-lookup hot path on one MI355X.
+
+One step = one pass of the whole path (plan, EmbeddingBag pool, pack, ring slot, local
+alltoallv, unpack) over one synthetic batch that is already resident in HBM.  Prints one
+JSON line: lookups/s for the whole path, the HBM roofline of the dominant kernel (the
+pool) from HIP events recorded inside the timed region, and the CPU oracle timed on a
+bounded sample of the same workload on this machine's host cores.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import re
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_HBM_GBPS = 8000.0          # MI355X published HBM3E peak
+
+WORKLOAD_TEXT = {
+    1: "cfg1: 8 tables x 10000 rows x dim 16 fp32, batch 128, pooling 1, uniform, P=2 table-wise round-robin, k=1",
+    2: "cfg2: 26 tables rows log-uniform [1e3,1e5], dim 64 fp32, batch 2048, pooling 1, uniform, P=4 table-wise balanced, k=1",
+    3: "cfg3: 26 tables x 1e6 rows x dim 128 fp32, batch 8192, bags U[1,40], Zipf 1.05, P=8 row-wise, k=2",
+    4: "cfg4: 64 tables rows power-law [1e3,4e7] (40.5 GB fp32, dim 128), batch 16384, bags U[1,64], Zipf 1.2, "
+       "8 largest tables on rank 0 of P=8 table-wise, k=4",
+    5: "cfg5: 8 tables x 2e7 rows x dim 128 fp16 storage / fp32 accumulate, batch 65536, pooling 32, Zipf 1.05, "
+       "P=8 row-wise, k=4",
+}
+
+
+def stage_bytes(w, nnz: int) -> dict:
+    """Algorithmic bytes per launch of every stage (what the stage must read and write)."""
+    nvec = w.F * w.T * w.B
+    pv = nvec * w.D * 4
+    out = w.T * w.B * w.D * 4
+    seg = 8 * nvec
+    return {
+        "plan": 8 * nnz + 8 * (w.T * w.B + 1) + 8 * nnz + seg,
+        "pool": 8 * nnz + seg + nnz * w.D * w.elem_bytes + pv,
+        "pack": 2 * pv,
+        "exchange": 2 * pv,
+        "unpack": pv + out,
+    }
+
+
+def recorded_traffic(cfg: int):
+    """HBM bytes per pool launch from the committed rocprofv3 counter summary, if present."""
+    path = os.path.join(ROOT, "profiles", f"pool_rows_cfg{cfg}_pmc.txt")
+    try:
+        m = re.search(r"^traffic_bytes_per_launch:\s*([0-9.eE+]+)", open(path).read(), re.M)
+        return float(m.group(1)) if m else None
+    except OSError:
+        return None
+
+
+def cpu_baseline(w, tabs_gpu, batches, budget_s: float) -> dict:
+    """The oracle, as it stands and single-threaded, over whole batches of the same workload
+    (all tables at full size, copied to the host) until about `budget_s` seconds are spent."""
+    import oracle
+    tabs = [t.cpu().numpy() for t in tabs_gpu]
+    case = oracle.Case(w.P, w.T, w.D, w.B, w.part_kind, w.rows, w.table_owner, 1 if w.table_dtype == "fp16" else 0)
+    host = [(ix.cpu().numpy(), off.cpu().numpy()) for ix, off in batches]
+    spent, nnz, n = 0.0, 0, 0
+    while spent < budget_s and n < 64:
+        ix, off = host[n % len(host)]
+        t0 = time.perf_counter()
+        oracle.pipeline(case, tabs, ix, off)
+        spent += time.perf_counter() - t0
+        nnz += int(off[-1])
+        n += 1
+    return {"value": nnz / spent, "unit": "lookups/s", "cores": 1, "kind": "oracle", "seconds": round(spent, 3),
+            "sample": f"{n} whole batches ({nnz} lookups) through the oracle's plan, pool, pack, alltoallv and "
+                      f"unpack, all {w.T} tables at full size on the host"}
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", type=int, default=4, help="benchmark workload 1..5 (default 4, the target)")
+    ap.add_argument("--size", default="full", choices=["full", "small"])
+    ap.add_argument("--batches", type=int, default=4, help="distinct pre-generated batches, rotated")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-seconds", type=float, default=12.0, help="CPU time to spend on the oracle baseline")
+    ap.add_argument("--index-dist", default=None, choices=[None, "uniform"],
+                    help="cache-defeating control: uniform indices instead of the workload's law")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs the path on one GPU (P simulated ranks live in its memory); "
+              "--gpus above 1 is not supported", file=sys.stderr)
+        return 2
+
+    import torch
+
+    import synth
+    from paper_2512_19342_amd.runner import Pipeline
+
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        return 2
+    dev = torch.device("cuda:0")
+    w = synth.workload(args.config, args.size)
+    if args.index_dist == "uniform":
+        w.index_dist = ("uniform",)
+    def note(msg: str):
+        print(f"[bench] {msg}", file=sys.stderr, flush=True)
+
+    t_setup = time.perf_counter()
+    tabs = [synth.make_table(w, t, dev) for t in range(w.T)]
+    torch.cuda.synchronize()
+    note(f"{w.T} tables ({w.table_bytes() / 1e9:.1f} GB) generated on the device")
+    batches = [synth.make_batch(w, it, dev) for it in range(args.batches)]
+    torch.cuda.synchronize()
+    note(f"{args.batches} batches generated")
+    w._cdf_cache.clear()
+    nnzs = [int(off[-1].item()) for _, off in batches]
+    pipe = Pipeline(w, tabs, max(nnzs))
+    out = pipe.new_out()
+    torch.cuda.synchronize()
+    t_setup = time.perf_counter() - t_setup
+    c = pipe.ctx
+    names = ["plan", "pool", "pack", "exchange", "unpack"]
+
+    def one_step(i: int, ev=None):
+        ix, off = batches[i % len(batches)]
+        nnz = nnzs[i % len(batches)]
+        if ev: ev[0].record()
+        c.bls_plan(ix, off, nnz, pipe.sendcounts, pipe.sdispls, pipe.recvcounts, pipe.rdispls,
+                   pipe.ridx, pipe.segoff, None, pipe.ws)
+        if ev: ev[1].record()
+        c.bls_embbag_pool(pipe.ridx, pipe.segoff, nnz, pipe.pooled)
+        if ev: ev[2].record()
+        c.bls_pack(pipe.pooled, pipe.send)
+        if ev: ev[3].record()
+        it, slot = c.bls_ring_advance()
+        c.bls_alltoallv_local(pipe.send, slot)
+        if ev: ev[4].record()
+        c.bls_unpack(it, out)
+        if ev: ev[5].record()
+        return nnz
+
+    for i in range(args.warmup):
+        one_step(i)
+    c.bls_check()
+    note("warm-up done")
+    events = [[torch.cuda.Event(enable_timing=True) for _ in range(6)] for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    lookups = 0
+    for i in range(args.steps):
+        lookups += one_step(args.warmup + i, events[i])
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    c.bls_check()
+    note(f"{args.steps} timed steps: {dt / args.steps * 1e3:.3f} ms per step")
+
+    stage_ms = {n: sum(e[k].elapsed_time(e[k + 1]) for e in events) / args.steps for k, n in enumerate(names)}
+    mean_nnz = lookups / args.steps
+    sb = stage_bytes(w, int(mean_nnz))
+    pool_s = stage_ms["pool"] * 1e-3
+    achieved = sb["pool"] / pool_s / 1e9
+    a_staged = sum(sb.values())
+    pool_pack_gbps = (sb["pool"] + sb["pack"]) / ((stage_ms["pool"] + stage_ms["pack"]) * 1e-3) / 1e9
+
+    res = {
+        "metric": "embedding lookups/sec + achieved HBM GB/s (bucket+pool+pack), 1 MI355X",
+        "value": lookups / dt, "unit": "lookups/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": dt / args.steps * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32" if w.table_dtype == "fp32" else "f16 storage, f32 accumulate", "data": "synthetic",
+        "config": {"workload": WORKLOAD_TEXT[args.config] + ("" if args.size == "full" else " [reduced twin]")
+                   + (" [uniform-index control]" if args.index_dist else ""),
+                   "P": w.P, "T": w.T, "D": w.D, "B": w.B, "k": w.k, "lookups_per_step": mean_nnz,
+                   "table_bytes": w.table_bytes(), "distinct_batches": len(batches)},
+        "roofline": {"bound": "hbm", "kernel": "pool_rows (bls_embbag_pool)", "achieved": achieved,
+                     "peak": PEAK_HBM_GBPS, "unit": "GB/s", "frac": achieved / PEAK_HBM_GBPS,
+                     "traffic": recorded_traffic(args.config) if not args.index_dist and args.size == "full" else None,
+                     "algorithmic_bytes_per_launch": sb["pool"], "avg_launch_ms": stage_ms["pool"]},
+        "hbm_gbps": {"whole_path_staged": a_staged / (dt / args.steps) / 1e9, "pool_plus_pack": pool_pack_gbps,
+                     "pool_plus_pack_frac_of_peak": pool_pack_gbps / PEAK_HBM_GBPS},
+        "stage_ms": stage_ms,
+        "stage_gbps": {n: sb[n] / (stage_ms[n] * 1e-3) / 1e9 for n in names},
+        "setup_s": round(t_setup, 2),
+    }
+    if not args.no_cpu_baseline:
+        note("timing the CPU oracle on the host")
+        res["cpu_baseline"] = cpu_baseline(w, tabs, batches, args.cpu_seconds)
+    print(json.dumps(res))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

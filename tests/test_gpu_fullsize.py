@@ -1,0 +1,88 @@
+"""Parity at the full benchmark sizes, in the launch configuration bench.py times.
+
+Tables (13-41 GB) are generated on the device; the oracle cannot hold them, so
+  - the integer outputs of bls_plan are compared in full with the oracle's plan, and
+  - pooled vectors are checked on sampled bags: the oracle sums the bag's rows, recomputed
+    on the host from the table generator, and the result must sit, bit for bit, at the
+    closed-form address of that bag in the pooled buffer, the send buffer, the receive slot
+    and the output (addresses computed here from the layout definitions, not by the library).
+Table values of these workloads lie on an exact grid, so every summation order gives the
+same bits and the row-wise partial sums can be checked the same way.
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import synth
+
+pytestmark = pytest.mark.gpu
+
+
+def layout(w):
+    P, T, B = w.P, w.T, w.B
+    first = [s * (B // P) + min(s, B % P) for s in range(P + 1)]
+    if w.part_kind == 0:
+        n_loc = [sum(1 for t in range(T) if w.table_owner[t] == d) for d in range(P)]
+        loc = [sum(1 for u in range(t) if w.table_owner[u] == w.table_owner[t]) for t in range(T)]
+    else:
+        n_loc, loc = [T] * P, list(range(T))
+    nsum = np.concatenate([[0], np.cumsum(n_loc)])
+    return first, n_loc, loc, nsum
+
+
+@pytest.mark.parametrize("cfg", [3, 4, 5])
+def test_full_size(cfg):
+    from paper_2512_19342_amd.runner import Pipeline
+    w = synth.workload(cfg, "full")
+    dev = torch.device("cuda:0")
+    print(f"full-size parity {w.name}: generating {w.table_bytes() / 1e9:.1f} GB of tables", flush=True)
+    tabs = [synth.make_table(w, t, dev) for t in range(w.T)]
+    ix, off = synth.make_batch(w, 3, dev)
+    w._cdf_cache.clear()
+    nnz = int(off[-1].item())
+    pipe = Pipeline(w, tabs, nnz, want_perm=True)
+    out = pipe.new_out()
+    it, slot = pipe.issue(ix, off, nnz)
+    Y, S, R = pipe.pooled, pipe.send, pipe.slot_view(slot)
+    pipe.complete(it, out)
+    pipe.ctx.bls_check()
+    print(f"  {nnz} lookups through the path; comparing the plan in full", flush=True)
+
+    ix_h, off_h = ix.cpu().numpy(), off.cpu().numpy()
+    case = oracle.Case(w.P, w.T, w.D, w.B, w.part_kind, w.rows, w.table_owner, 1 if w.table_dtype == "fp16" else 0)
+    ref = oracle.plan(case, ix_h, off_h)
+    assert ref["sendcounts"].sum() == nnz
+    for name, got in (("sendcounts", pipe.sendcounts), ("sdispls", pipe.sdispls), ("recvcounts", pipe.recvcounts),
+                      ("rdispls", pipe.rdispls), ("segoff", pipe.segoff), ("ridx", pipe.ridx[:nnz]), ("perm", pipe.perm[:nnz])):
+        assert np.array_equal(got.cpu().numpy(), ref[name]), name
+    del ref
+
+    P, T, B, D = w.P, w.T, w.B, w.D
+    first, n_loc, loc, nsum = layout(w)
+    rng = np.random.default_rng(cfg)
+    n_samples = 1200
+    ts, bs = rng.integers(0, T, n_samples), rng.integers(0, B, n_samples)
+    ts[:4], bs[:4] = [0, 0, T - 1, T - 1], [0, B - 1, 0, B - 1]
+    Yv, Sv, Rv = (x.view(-1, D) for x in (Y, S, R))
+    for t, b in zip(ts.tolist(), bs.tolist()):
+        g = t * B + b
+        idx = ix_h[off_h[g]:off_h[g + 1]]
+        s = next(r for r in range(P) if b < first[r + 1])
+        b_loc, n = b - first[s], first[s + 1] - first[s]
+        rows = synth.table_rows(w, t, torch.from_numpy(idx)).numpy()
+        whole32, _ = oracle.bag_sum(rows)
+        assert np.array_equal(out[b, t].cpu().numpy().view(np.uint32), whole32.view(np.uint32)), (t, b)
+        owners = [w.table_owner[t]] if w.part_kind == 0 else range(P)
+        for d in owners:
+            if w.part_kind == 0:
+                part32 = whole32
+            else:
+                rps = -(-w.rows[t] // P)
+                part32, _ = oracle.bag_sum(rows[idx // rps == d].reshape(-1, D))
+            q = int(nsum[d]) + loc[t]
+            sigma = int(nsum[d]) * B + n_loc[d] * first[s] + loc[t] * n + b_loc
+            rho = w.F * T * first[s] + q * n + b_loc
+            for name, buf, at in (("Y", Yv, q * B + b), ("S", Sv, sigma), ("R", Rv, rho)):
+                assert np.array_equal(buf[at].cpu().numpy().view(np.uint32), part32.view(np.uint32)), (name, t, b, d)
+    print(f"  {n_samples} sampled bags match in Y, S, R and Out", flush=True)
