@@ -90,6 +90,7 @@ def main() -> int:
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="CPU time to spend on the oracle baseline")
     ap.add_argument("--index-dist", default=None, choices=[None, "uniform"],
                     help="cache-defeating control: uniform indices instead of the workload's law")
+    ap.add_argument("--bag-fixed", type=int, default=0, help="experiment: every bag has this many lookups")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs the path on one GPU (P simulated ranks live in its memory); "
@@ -108,6 +109,8 @@ def main() -> int:
     w = synth.workload(args.config, args.size)
     if args.index_dist == "uniform":
         w.index_dist = ("uniform",)
+    if args.bag_fixed:
+        w.bag = ("fixed", args.bag_fixed)
     def note(msg: str):
         print(f"[bench] {msg}", file=sys.stderr, flush=True)
 
@@ -174,7 +177,8 @@ def main() -> int:
         "ms_per_step": dt / args.steps * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32" if w.table_dtype == "fp32" else "f16 storage, f32 accumulate", "data": "synthetic",
         "config": {"workload": WORKLOAD_TEXT[args.config] + ("" if args.size == "full" else " [reduced twin]")
-                   + (" [uniform-index control]" if args.index_dist else ""),
+                   + (" [uniform-index control]" if args.index_dist else "")
+                   + (f" [every bag {args.bag_fixed} lookups]" if args.bag_fixed else ""),
                    "P": w.P, "T": w.T, "D": w.D, "B": w.B, "k": w.k, "lookups_per_step": mean_nnz,
                    "table_bytes": w.table_bytes(), "distinct_batches": len(batches)},
         "roofline": {"bound": "hbm", "kernel": "pool_rows (bls_embbag_pool)", "achieved": achieved,

@@ -24,7 +24,7 @@ FLAGS = [
 def build(verbose: bool = False) -> str:
     """Compile every HIP source into one shared library; always recompiles."""
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    cmd = [hipcc] + FLAGS + SOURCES + ["-o", LIB]
+    cmd = [hipcc] + FLAGS + os.environ.get("BLS_EXTRA_FLAGS", "").split() + SOURCES + ["-o", LIB]
     if verbose:
         print(" ".join(cmd), file=sys.stderr)
     subprocess.check_call(cmd)

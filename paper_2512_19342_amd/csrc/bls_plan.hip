@@ -213,36 +213,46 @@ __global__ __launch_bounds__(kThreads) void plan_finish(DevDesc dd, const int64_
 
 // ---- 3. scatter ------------------------------------------------------------------------
 
-// Table-wise: G lanes copy one bag to its place in owner order.
-template <int G>
-__global__ __launch_bounds__(kThreads) void plan_scatter_tablewise(DevDesc dd, const int64_t *__restrict__ idx,
-                                                                   const int64_t *__restrict__ off, int64_t nnz,
-                                                                   const int64_t *__restrict__ segoff,
-                                                                   int64_t *__restrict__ ridx, int64_t *__restrict__ perm,
-                                                                   const int64_t *__restrict__ sabs,
-                                                                   const int64_t *__restrict__ rabs)
+// Table-wise: all bags of one table in one rank's mini-batch - a run (q, s) - are contiguous
+// both in input order and in owner order, so the scatter is Q*P block copies of index
+// lists.  grid: x strides over a run, y strides over the runs.
+__global__ __launch_bounds__(kThreads) void plan_scatter_runs(DevDesc dd, const int64_t *__restrict__ idx,
+                                                              const int64_t *__restrict__ off, int64_t nnz,
+                                                              const int64_t *__restrict__ segoff,
+                                                              int64_t *__restrict__ ridx, int64_t *__restrict__ perm,
+                                                              const int64_t *__restrict__ sabs,
+                                                              const int64_t *__restrict__ rabs)
 {
-    const int q = blockIdx.y;
-    const int li = threadIdx.x & (G - 1);
-    const uint32_t b = blockIdx.x * (kThreads / G) + threadIdx.x / G;
-    if (b >= (uint32_t)dd.B) return;
-    const int t = dd.q_t[q];
-    const int64_t g = (int64_t)t * dd.B + b;
-    const int64_t lo = off[g], hi = off[g + 1];
-    const int64_t len = hi - lo;
-    if (lo < 0 || hi > nnz || len < 0) return;           // flagged by the count kernel
-    int s; uint32_t b_loc, n;
-    bls_split_sample(dd, b, s, b_loc, n);
-    const int64_t dst = segoff[bls_sigma(dd, q, s, b_loc, n)];
-    if (dst < 0 || dst + len > nnz) { flag_error(dd); return; }
-    const int d = dd.q_d[q];
-    const int64_t rows = dd.rows[t];
-    const int64_t to_send = perm ? sabs[s * dd.P + d] - rabs[d * dd.P + s] : 0;
-    for (int64_t j = li; j < len; j += G) {
-        int64_t ix = idx[lo + j];
-        if (ix < 0 || ix >= rows) { flag_error(dd); ix = 0; }
-        ridx[dst + j] = ix;
-        if (perm) perm[lo + j] = dst + j + to_send;
+    constexpr int kPer = 4;
+    for (int run = blockIdx.y; run < dd.Q * dd.P; run += gridDim.y) {
+        const int q = run / dd.P, s = run - q * dd.P;
+        const int t = dd.q_t[q], d = dd.q_d[q];
+        const int64_t lo = off[(int64_t)t * dd.B + dd.first[s]], hi = off[(int64_t)t * dd.B + dd.first[s + 1]];
+        const int64_t len = hi - lo;
+        if (lo < 0 || hi > nnz || len <= 0) continue;        // bad offsets are flagged by the count kernel
+        const int64_t n = dd.first[s + 1] - dd.first[s];
+        const int64_t dst = segoff[(int64_t)dd.nsum[d] * dd.B + (int64_t)dd.n_loc[d] * dd.first[s] + (int64_t)(q - dd.nsum[d]) * n];
+        if (dst < 0 || dst + len > nnz) { if (threadIdx.x == 0 && blockIdx.x == 0) flag_error(dd); continue; }
+        const int64_t rows = dd.rows[t];
+        const int64_t to_send = perm ? sabs[s * dd.P + d] - rabs[d * dd.P + s] : 0;
+        const int64_t stride = (int64_t)gridDim.x * kThreads * kPer;
+        for (int64_t i0 = (int64_t)blockIdx.x * kThreads * kPer + threadIdx.x; i0 < len; i0 += stride) {
+            int64_t v[kPer];
+#pragma unroll
+            for (int k = 0; k < kPer; ++k) {
+                const int64_t i = i0 + k * kThreads;
+                v[k] = i < len ? idx[lo + i] : 0;
+            }
+#pragma unroll
+            for (int k = 0; k < kPer; ++k) {
+                const int64_t i = i0 + k * kThreads;
+                if (i < len) {
+                    if (v[k] < 0 || v[k] >= rows) { flag_error(dd); v[k] = 0; }
+                    ridx[dst + i] = v[k];
+                    if (perm) perm[lo + i] = dst + i + to_send;
+                }
+            }
+        }
     }
 }
 
@@ -337,18 +347,11 @@ int bls_launch_plan(bls_ctx *ctx, const int64_t *idx, const int64_t *off, int64_
             dim3 grid((B + kThreads / 64 - 1) / (kThreads / 64), ctx->T);
             plan_scatter_rowwise<<<grid, kThreads, 0, st>>>(dd, idx, off, nnz, segoff, ridx, perm, sabs, rabs);
         } else {
-            // lanes per bag from the mean bag length
-            const int64_t mean = nnz / std::max<int64_t>(1, (int64_t)ctx->T * ctx->B);
-            if (mean >= 24) {
-                dim3 grid((B + kThreads / 32 - 1) / (kThreads / 32), ctx->Q);
-                plan_scatter_tablewise<32><<<grid, kThreads, 0, st>>>(dd, idx, off, nnz, segoff, ridx, perm, sabs, rabs);
-            } else if (mean >= 6) {
-                dim3 grid((B + kThreads / 8 - 1) / (kThreads / 8), ctx->Q);
-                plan_scatter_tablewise<8><<<grid, kThreads, 0, st>>>(dd, idx, off, nnz, segoff, ridx, perm, sabs, rabs);
-            } else {
-                dim3 grid((B + kThreads - 1) / kThreads, ctx->Q);
-                plan_scatter_tablewise<1><<<grid, kThreads, 0, st>>>(dd, idx, off, nnz, segoff, ridx, perm, sabs, rabs);
-            }
+            const int64_t runs = (int64_t)ctx->Q * ctx->P;
+            const int64_t per_run = nnz / runs + 1;
+            const unsigned gx = (unsigned)std::min<int64_t>(256, std::max<int64_t>(1, (per_run + 2047) / 2048));
+            dim3 grid(gx, (unsigned)std::min<int64_t>(runs, 65535));
+            plan_scatter_runs<<<grid, kThreads, 0, st>>>(dd, idx, off, nnz, segoff, ridx, perm, sabs, rabs);
         }
     }
     BLS_HIP(ctx, hipGetLastError());

@@ -1,73 +1,130 @@
 // bls_embbag_pool: EmbeddingBag sum over HBM-resident table shards.
 //
 // A group of G lanes owns one segment (one bag's lookups at one owner); lane i of the
-// group holds columns [i*V, (i+1)*V) of the pooled vector in registers, V = 16 bytes of
-// table storage (4 fp32 or 8 fp16 values), so a row is fetched with one 128-bit load per
-// lane and consecutive lanes read consecutive addresses.  G = row bytes / 16 rounded up to
-// a power of two: a 512-byte row takes half a wavefront and a wavefront works on two bags
-// at once, a 256-byte row takes a quarter.  The group first loads up to G of its row
-// numbers with one coalesced load, then walks them U at a time: U independent row loads
-// are issued before the first add so that many rows are in flight per lane, and the adds
-// follow in segment order, which keeps the fp32 result identical to a sequential sum.
+// group keeps the columns stored in bytes [i*VB, (i+1)*VB) of a row in registers, so a row
+// is fetched with one load per lane and consecutive lanes read consecutive addresses.
+// G*VB covers the row: a 512-byte row is read by a whole wavefront with 8 bytes per lane
+// or by half a wavefront with 16.  The group first loads up to G of its row numbers with
+// one coalesced load, then walks them U at a time: U independent row loads are issued
+// before the first add so that many rows are in flight per lane, and the adds follow in
+// segment order, which keeps the fp32 result identical to a sequential sum.
+//
+// Bags are short (tens of rows), so a group does not stop at one: it streams the rows of
+// several consecutive segments - they are contiguous in ridx - and stores and clears its
+// accumulator whenever the stream crosses a segment boundary.  That amortises the
+// dependent loads at the start (segment offsets, then row numbers, then rows), lets the
+// next block of row numbers be fetched while the current one is consumed, and evens out
+// the lengths of the streams that share a wavefront.
+#include <algorithm>
+#include <cstdlib>
+
 #include "bls_internal.h"
 
 namespace {
 
 constexpr int kThreads = 256;
 constexpr uint32_t kBadRow = 0xffffffffu;
+constexpr uint64_t kNoRow = ~0ull;
 
 __device__ __forceinline__ void flag_error(const DevDesc &dd) { atomicOr(dd.err, 1); }
-
-template <int DT> struct Acc;
-
-template <> struct Acc<BLS_FP32> {
-    static constexpr int V = 4;
-    float4 a;
-    __device__ __forceinline__ void zero() { a = make_float4(0.f, 0.f, 0.f, 0.f); }
-    __device__ __forceinline__ void add(const uint4 &x)
-    {
-        a.x += __uint_as_float(x.x); a.y += __uint_as_float(x.y);
-        a.z += __uint_as_float(x.z); a.w += __uint_as_float(x.w);
-    }
-    __device__ __forceinline__ void store(float *p) const { *reinterpret_cast<float4 *>(p) = a; }
-};
 
 // IEEE binary16 -> binary32 (exact; one v_cvt_f32_f16 each)
 __device__ __forceinline__ float half_bits(unsigned short h) { return (float)__builtin_bit_cast(_Float16, h); }
 __device__ __forceinline__ float half_lo(uint32_t w) { return half_bits((unsigned short)(w & 0xffffu)); }
 __device__ __forceinline__ float half_hi(uint32_t w) { return half_bits((unsigned short)(w >> 16)); }
 
-template <> struct Acc<BLS_FP16> {
-    static constexpr int V = 8;
-    float4 a, b;
-    __device__ __forceinline__ void zero() { a = make_float4(0.f, 0.f, 0.f, 0.f); b = a; }
-    __device__ __forceinline__ void add(const uint4 &x)
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+
+// Per-lane accumulator: VB bytes of table storage per lane and row, NV values in them.
+template <int DT, int VB> struct Acc {
+    static constexpr int NW = VB / 4;                              // 32-bit words loaded per row
+    static constexpr int NV = DT == BLS_FP16 ? VB / 2 : VB / 4;   // fp32 values accumulated
+    struct Raw { uint32_t w[NW]; };
+    float a[NV];
+
+    __device__ __forceinline__ void zero()
     {
-        a.x += half_lo(x.x); a.y += half_hi(x.x); a.z += half_lo(x.y); a.w += half_hi(x.y);
-        b.x += half_lo(x.z); b.y += half_hi(x.z); b.z += half_lo(x.w); b.w += half_hi(x.w);
+#pragma unroll
+        for (int i = 0; i < NV; ++i) a[i] = 0.f;
+    }
+    static __device__ __forceinline__ Raw none()
+    {
+        Raw r;
+#pragma unroll
+        for (int i = 0; i < NW; ++i) r.w[i] = 0u;
+        return r;
+    }
+    // tables live in global memory: say so, or the loads are emitted as flat accesses
+    static __device__ __forceinline__ Raw load(const char *p)
+    {
+        Raw r;
+        if constexpr (NW == 4) {
+            const u32x4 v = *(const __attribute__((address_space(1))) u32x4 *)p;
+            r.w[0] = v.x; r.w[1] = v.y; r.w[2] = v.z; r.w[3] = v.w;
+        } else if constexpr (NW == 2) {
+            const u32x2 v = *(const __attribute__((address_space(1))) u32x2 *)p;
+            r.w[0] = v.x; r.w[1] = v.y;
+        } else {
+            r.w[0] = *(const __attribute__((address_space(1))) uint32_t *)p;
+        }
+        return r;
+    }
+    __device__ __forceinline__ void add(const Raw &r)
+    {
+#pragma unroll
+        for (int i = 0; i < NW; ++i) {
+            if constexpr (DT == BLS_FP16) { a[2 * i] += half_lo(r.w[i]); a[2 * i + 1] += half_hi(r.w[i]); }
+            else a[i] += __uint_as_float(r.w[i]);
+        }
     }
     __device__ __forceinline__ void store(float *p) const
     {
-        reinterpret_cast<float4 *>(p)[0] = a;
-        reinterpret_cast<float4 *>(p)[1] = b;
+        if constexpr (NV % 4 == 0) {
+#pragma unroll
+            for (int i = 0; i < NV / 4; ++i)
+                reinterpret_cast<float4 *>(p)[i] = make_float4(a[4 * i], a[4 * i + 1], a[4 * i + 2], a[4 * i + 3]);
+        } else if constexpr (NV == 2) {
+            *reinterpret_cast<float2 *>(p) = make_float2(a[0], a[1]);
+        } else {
+            p[0] = a[0];
+        }
     }
 };
 
+// 64-bit value of lane (gbase + k), k uniform.  A whole-wavefront group reads it into scalar
+// registers; narrower groups use the lane permute network (two ds_bpermute, no vector ALU
+// work beyond the address), which pipelines when several are issued back to back.
+template <int G>
+__device__ __forceinline__ uint64_t group_broadcast64(uint64_t v, int gbase4, int k)
+{
+    if constexpr (G == 64) {
+        const uint32_t lo = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)v, k);
+        const uint32_t hi = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)(v >> 32), k);
+        return ((uint64_t)hi << 32) | lo;
+    } else {
+        const uint32_t lo = (uint32_t)__builtin_amdgcn_ds_bpermute(gbase4 + 4 * k, (int)(uint32_t)v);
+        const uint32_t hi = (uint32_t)__builtin_amdgcn_ds_bpermute(gbase4 + 4 * k, (int)(uint32_t)(v >> 32));
+        return ((uint64_t)hi << 32) | lo;
+    }
+}
+
+// One segment per group of G lanes (used for G < 4, rows of 16 or 32 bytes).
 // grid: x over groups of samples, y = q (owner, local table).
-template <int G, int DT, int U>
+template <int G, int DT, int VB, int U>
 __global__ __launch_bounds__(kThreads) void pool_rows(DevDesc dd, const int64_t *__restrict__ ridx,
                                                       const int64_t *__restrict__ segoff, int64_t nnz,
                                                       float *__restrict__ Y)
 {
-    using A = Acc<DT>;
+    using A = Acc<DT, VB>;
     const int q = blockIdx.y;
     const int li = threadIdx.x & (G - 1);
     const int gbase = (threadIdx.x & 63) & ~(G - 1);
     const uint32_t b = blockIdx.x * (kThreads / G) + threadIdx.x / G;
     const bool live = b < (uint32_t)dd.B;
     const uint32_t row_bytes = (uint32_t)dd.D * (DT == BLS_FP16 ? 2u : 4u);
-    const bool col_ok = (uint32_t)li * 16u < row_bytes;      // lanes past the row's end idle
-    const char *__restrict__ base = (const char *)dd.q_base[q];
+    const bool col_ok = (uint32_t)li * VB < row_bytes;       // lanes past the row's end idle
+    const char *__restrict__ base = (const char *)dd.q_base[q] + (uint32_t)li * VB;
     const int64_t shard_rows = dd.q_rows[q];
 
     int64_t beg = 0, len = 0;
@@ -93,19 +150,129 @@ __global__ __launch_bounds__(kThreads) void pool_rows(DevDesc dd, const int64_t 
             else mine = (uint32_t)r;
         }
         for (int j = 0; __any(j < rem); j += U) {
-            uint4 v[U];
+            uint32_t r[U];
+            typename A::Raw v[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) r[u] = (uint32_t)__shfl((int)mine, gbase + ((j + u) & (G - 1)), 64);
 #pragma unroll
             for (int u = 0; u < U; ++u) {
-                const uint32_t r = (uint32_t)__shfl((int)mine, gbase + ((j + u) & (G - 1)), 64);
-                v[u] = make_uint4(0u, 0u, 0u, 0u);
-                if (j + u < rem && r != kBadRow && col_ok)
-                    v[u] = *reinterpret_cast<const uint4 *>(base + (uint64_t)r * row_bytes + (uint32_t)li * 16u);
+                v[u] = A::none();
+                if (j + u < rem && r[u] != kBadRow && col_ok) v[u] = A::load(base + (uint64_t)r[u] * row_bytes);
             }
 #pragma unroll
             for (int u = 0; u < U; ++u) acc.add(v[u]);      // adding +0 for skipped rows changes nothing
         }
     }
-    if (live && col_ok) acc.store(Y + ((int64_t)q * dd.B + b) * dd.D + li * A::V);
+    if (live && col_ok) acc.store(Y + ((int64_t)q * dd.B + b) * dd.D + li * A::NV);
+}
+
+// G >= 4 lanes stream up to nb_max (< G) consecutive segments of one (q, s) block.
+// grid: x over groups (s-major, then chunks of nb_max samples), y = q.
+template <int G, int DT, int VB, int U>
+__global__ __launch_bounds__(kThreads) void pool_stream(DevDesc dd, const int64_t *__restrict__ ridx,
+                                                        const int64_t *__restrict__ segoff, int64_t nnz,
+                                                        float *__restrict__ Y, int nb_max, uint32_t chunks_per_s)
+{
+    using A = Acc<DT, VB>;
+    const int q = blockIdx.y;
+    const int lane = threadIdx.x & 63;
+    const int li = lane & (G - 1);
+    const int gbase = lane & ~(G - 1);
+    const uint32_t gx = blockIdx.x * (kThreads / G) + threadIdx.x / G;
+    const uint32_t s = gx / chunks_per_s;
+    const uint32_t chunk = gx - s * chunks_per_s;
+    const uint32_t row_bytes = (uint32_t)dd.D * (DT == BLS_FP16 ? 2u : 4u);
+    const bool col_ok = (uint32_t)li * VB < row_bytes;       // lanes past the row's end idle:
+    // idle lanes re-read the row's first bytes (in bounds, same cache line) and never store
+    const char *__restrict__ base = (const char *)dd.q_base[q] + (col_ok ? (uint32_t)li * VB : 0u);
+    const int64_t shard_rows = dd.q_rows[q];
+
+    // this group's segments: samples [b0, b0 + nb) of mini-batch s
+    int nb = 0;
+    int64_t sg0 = 0, b0 = 0;
+    if (s < (uint32_t)dd.P) {
+        const int64_t f = dd.first[s], n = dd.first[s + 1] - f;
+        const int64_t bl0 = (int64_t)chunk * nb_max;
+        if (bl0 < n) {
+            nb = n - bl0 < nb_max ? (int)(n - bl0) : nb_max;
+            const int d = dd.q_d[q];
+            sg0 = (int64_t)dd.nsum[d] * dd.B + (int64_t)dd.n_loc[d] * f + (int64_t)(q - dd.nsum[d]) * n + bl0;
+            b0 = f + bl0;
+        }
+    }
+    // lane i of the group holds the start of segment i (i <= nb); all must be in order
+    int64_t seg = 0;
+    if (nb > 0 && li <= nb) seg = segoff[sg0 + li];
+    const int64_t seg_next = __shfl_down(seg, 1, G);
+    const int64_t beg = __shfl(seg, gbase, 64);
+    const int64_t end = __shfl(seg, gbase + nb, 64);
+    const bool bad = nb > 0 && ((li < nb && seg_next < seg) || beg < 0 || end > nnz || end - beg > 0x7fffffffLL);
+    const unsigned long long gmask = G == 64 ? ~0ull : ((1ull << (G & 63)) - 1ull) << gbase;
+    if (__ballot(bad) & gmask) { if (bad) flag_error(dd); nb = 0; }
+    const int rel = (int)(seg - beg);                        // segment starts relative to the stream
+    const int total = nb > 0 ? (int)(end - beg) : 0;
+
+    int cur = 0, pos = 0;                                    // segment being summed, rows consumed
+    int cur_end = nb > 0 ? (int)__shfl(rel, gbase + 1, 64) : -1;
+    A acc;
+    acc.zero();
+
+    // store finished segments (also empty ones); every lane of the wavefront takes part in the
+    // lane exchange, the updates are per group
+    auto flush = [&]() {
+        for (;;) {
+            const bool need = cur < nb && cur_end == pos;
+            if (!__any(need)) break;
+            const int nxt = __shfl(rel, gbase + (cur + 2 < G ? cur + 2 : G - 1), 64);
+            if (need) {
+                if (col_ok) acc.store(Y + ((int64_t)q * dd.B + b0 + cur) * dd.D + li * A::NV);
+                acc.zero();
+                ++cur;
+                cur_end = cur < nb ? nxt : -1;
+            }
+        }
+    };
+    flush();
+
+    // this lane's row of block c0 as a byte offset into the shard (kNoRow: none or out of range)
+    auto fetch = [&](int c0) -> uint64_t {
+        uint64_t m = kNoRow;
+        if (c0 + li < total) {
+            const int64_t r = ridx[beg + c0 + li];
+            if (r < 0 || r >= shard_rows) flag_error(dd);
+            else m = (uint64_t)r * row_bytes;
+        }
+        return m;
+    };
+    uint64_t mine = fetch(0);
+    typename A::Raw v[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) v[u] = A::none();
+    for (int c0 = 0; __any(c0 < total); c0 += G) {
+        const uint64_t ahead = fetch(c0 + G);                // next block of row numbers, in flight
+        const int left = total - c0;
+        const int rem = left < 0 ? 0 : (left > G ? G : left);
+        for (int j = 0; __any(j < rem); j += U) {
+            uint64_t off[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) off[u] = group_broadcast64<G>(mine, gbase * 4, j + u);
+            // lanes without a row keep stale registers and skip the add: nothing to clear
+#pragma unroll
+            for (int u = 0; u < U; ++u)
+                if ((uint32_t)(off[u] >> 32) != 0xffffffffu) v[u] = A::load(base + off[u]);
+            // every load of the batch has landed before the first add: said once, here, so that
+            // no wait is placed between the conditional loads of the next batch
+            __builtin_amdgcn_s_waitcnt(0x0f70);              // vmcnt(0)
+            const int at = c0 + j;                           // stream position of the batch (uniform)
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                if ((uint32_t)(off[u] >> 32) != 0xffffffffu) acc.add(v[u]);
+                pos = at + u + 1 < total ? at + u + 1 : total;
+                flush();
+            }
+        }
+        mine = ahead;
+    }
 }
 
 // Any D (odd lengths, rows longer than 1 KB): one wavefront per segment, lanes stride the
@@ -139,42 +306,92 @@ __global__ __launch_bounds__(kThreads) void pool_rows_generic(DevDesc dd, const 
     }
 }
 
-template <int G, int DT>
-void launch_rows(const bls_ctx *ctx, const int64_t *ridx, const int64_t *segoff, int64_t nnz, float *Y, hipStream_t st)
+int env_int(const char *name, int dflt)
 {
-    constexpr int U = DT == BLS_FP16 ? 4 : 8;
-    const uint32_t per_block = kThreads / G;
-    dim3 grid((unsigned)((ctx->B + per_block - 1) / per_block), ctx->Q);
-    pool_rows<G, DT, (U < G ? U : G)><<<grid, kThreads, 0, st>>>(ctx->desc, ridx, segoff, nnz, Y);
+    const char *v = getenv(name);
+    return v && *v ? atoi(v) : dflt;
 }
 
-template <int DT>
-bool dispatch_rows(const bls_ctx *ctx, int lanes, const int64_t *ridx, const int64_t *segoff, int64_t nnz, float *Y,
-                   hipStream_t st)
+template <int G, int DT, int VB, int U>
+void launch_rows(const bls_ctx *ctx, const int64_t *ridx, const int64_t *segoff, int64_t nnz, float *Y, hipStream_t st)
+{
+    constexpr int UU = U < G ? U : G;
+    const uint32_t per_block = kThreads / G;
+    if constexpr (G >= 4) {
+        // segments per group: aim at a stream of about a hundred rows
+        const int64_t mean = nnz / std::max<int64_t>(1, ctx->nseg) + 1;
+        int nb = 1;
+        while (nb * 2 < G && nb * 2 <= 16 && nb * mean < 96) nb *= 2;
+        nb = env_int("BLS_POOL_NB", nb);
+        nb = std::max(1, std::min(nb, G - 1));
+        const int64_t n_max = ctx->B / ctx->P + (ctx->B % ctx->P ? 1 : 0);
+        const uint32_t chunks = (uint32_t)((n_max + nb - 1) / nb);
+        const int64_t groups = (int64_t)chunks * ctx->P;
+        dim3 grid((unsigned)((groups + per_block - 1) / per_block), ctx->Q);
+        pool_stream<G, DT, VB, UU><<<grid, kThreads, 0, st>>>(ctx->desc, ridx, segoff, nnz, Y, nb, chunks);
+    } else {
+        dim3 grid((unsigned)((ctx->B + per_block - 1) / per_block), ctx->Q);
+        pool_rows<G, DT, VB, UU><<<grid, kThreads, 0, st>>>(ctx->desc, ridx, segoff, nnz, Y);
+    }
+}
+
+template <int DT, int VB, int U>
+bool dispatch_lanes(const bls_ctx *ctx, int lanes, const int64_t *ridx, const int64_t *segoff, int64_t nnz, float *Y,
+                    hipStream_t st)
 {
     switch (lanes) {
-    case 1: launch_rows<1, DT>(ctx, ridx, segoff, nnz, Y, st); return true;
-    case 2: launch_rows<2, DT>(ctx, ridx, segoff, nnz, Y, st); return true;
-    case 4: launch_rows<4, DT>(ctx, ridx, segoff, nnz, Y, st); return true;
-    case 8: launch_rows<8, DT>(ctx, ridx, segoff, nnz, Y, st); return true;
-    case 16: launch_rows<16, DT>(ctx, ridx, segoff, nnz, Y, st); return true;
-    case 32: launch_rows<32, DT>(ctx, ridx, segoff, nnz, Y, st); return true;
-    case 64: launch_rows<64, DT>(ctx, ridx, segoff, nnz, Y, st); return true;
+    case 1: if constexpr (VB == 16) { launch_rows<1, DT, VB, U>(ctx, ridx, segoff, nnz, Y, st); return true; } break;
+    case 2: if constexpr (VB == 16) { launch_rows<2, DT, VB, U>(ctx, ridx, segoff, nnz, Y, st); return true; } break;
+    case 4: if constexpr (VB == 16) { launch_rows<4, DT, VB, U>(ctx, ridx, segoff, nnz, Y, st); return true; } break;
+    case 8: if constexpr (VB == 16) { launch_rows<8, DT, VB, U>(ctx, ridx, segoff, nnz, Y, st); return true; } break;
+    case 16: if constexpr (VB >= 8) { launch_rows<16, DT, VB, U>(ctx, ridx, segoff, nnz, Y, st); return true; } break;
+    case 32: launch_rows<32, DT, VB, U>(ctx, ridx, segoff, nnz, Y, st); return true;
+    case 64: launch_rows<64, DT, VB, U>(ctx, ridx, segoff, nnz, Y, st); return true;
     }
     return false;
 }
+
+template <int DT, int VB>
+bool dispatch_unroll(const bls_ctx *ctx, int lanes, int unroll, const int64_t *ridx, const int64_t *segoff, int64_t nnz,
+                     float *Y, hipStream_t st)
+{
+    switch (unroll) {
+    case 4: return dispatch_lanes<DT, VB, 4>(ctx, lanes, ridx, segoff, nnz, Y, st);
+    case 16: return dispatch_lanes<DT, VB, 16>(ctx, lanes, ridx, segoff, nnz, Y, st);
+    default: return dispatch_lanes<DT, VB, 8>(ctx, lanes, ridx, segoff, nnz, Y, st);
+    }
+}
+
+template <int DT>
+bool dispatch_rows(const bls_ctx *ctx, int vb, int lanes, int unroll, const int64_t *ridx, const int64_t *segoff,
+                   int64_t nnz, float *Y, hipStream_t st)
+{
+    switch (vb) {
+    case 16: return dispatch_unroll<DT, 16>(ctx, lanes, unroll, ridx, segoff, nnz, Y, st);
+    case 8: return dispatch_unroll<DT, 8>(ctx, lanes, unroll, ridx, segoff, nnz, Y, st);
+    case 4: return dispatch_unroll<DT, 4>(ctx, lanes, unroll, ridx, segoff, nnz, Y, st);
+    }
+    return false;
+}
+
 
 }  // namespace
 
 int bls_launch_pool(bls_ctx *ctx, const int64_t *ridx, const int64_t *segoff, int64_t nnz, float *Y, hipStream_t st)
 {
     const int64_t row_bytes = (int64_t)ctx->D * (ctx->dtype == BLS_FP16 ? 2 : 4);
+    // bytes per lane and row, rows in flight per lane: BLS_POOL_VB / BLS_POOL_U override the defaults
+    int vb = env_int("BLS_POOL_VB", 16);
+    const int unroll = env_int("BLS_POOL_U", 8);
+    if (vb != 16 && vb != 8 && vb != 4) vb = 16;
+    while (vb > 4 && row_bytes % vb != 0) vb >>= 1;          // lanes must split the row evenly
+    while (vb < 16 && row_bytes > 64 * (int64_t)vb) vb <<= 1; // and 64 of them must cover it
     bool done = false;
-    if (row_bytes % 16 == 0 && row_bytes <= 1024) {
+    if (row_bytes % vb == 0 && row_bytes <= 64 * (int64_t)vb) {
         int lanes = 1;
-        while (lanes * 16 < row_bytes) lanes <<= 1;
-        done = ctx->dtype == BLS_FP16 ? dispatch_rows<BLS_FP16>(ctx, lanes, ridx, segoff, nnz, Y, st)
-                                      : dispatch_rows<BLS_FP32>(ctx, lanes, ridx, segoff, nnz, Y, st);
+        while ((int64_t)lanes * vb < row_bytes) lanes <<= 1;
+        done = ctx->dtype == BLS_FP16 ? dispatch_rows<BLS_FP16>(ctx, vb, lanes, unroll, ridx, segoff, nnz, Y, st)
+                                      : dispatch_rows<BLS_FP32>(ctx, vb, lanes, unroll, ridx, segoff, nnz, Y, st);
     }
     if (!done) {
         dim3 grid((unsigned)((ctx->B + kThreads / 64 - 1) / (kThreads / 64)), ctx->Q);

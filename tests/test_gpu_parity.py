@@ -234,3 +234,28 @@ def test_host_side_argument_errors():
     with pytest.raises(B.BlsError) as e:
         c.bls_alltoallv_local(y, 0)                       # no ring yet
     assert e.value.code == B.BLS_EINVAL
+
+
+@pytest.mark.parametrize("vb,unroll,nb", [(16, 8, 1), (16, 4, 3), (16, 16, 16), (8, 8, 0), (8, 4, 7), (4, 8, 0), (4, 16, 2)])
+def test_pool_launch_variants(vb, unroll, nb, monkeypatch):
+    """The tuning overrides pick other lane widths, unroll depths and segments per group;
+    every variant must give the same bits."""
+    monkeypatch.setenv("BLS_POOL_VB", str(vb))
+    monkeypatch.setenv("BLS_POOL_U", str(unroll))
+    if nb:
+        monkeypatch.setenv("BLS_POOL_NB", str(nb))
+    works = [synth.workload(c, "small") for c in (3, 4, 5)]
+    for w in works[:2]:
+        w.values = "gauss"
+    works.append(synth.custom("long", P=3, T=4, D=64, k=1, B=100, rows=[500, 40, 7, 1000], part_kind=0,
+                              bag=("uniform", 0, 150), values="gauss", index_dist=("zipf", 1.1)))
+    works.append(synth.custom("sparse", P=4, T=3, D=32, k=1, B=203, rows=[50, 3000, 9], part_kind=1,
+                              bag=("uniform", 0, 2), values="gauss", table_dtype="fp16"))
+    for w in works:
+        tabs = [synth.make_table(w, t) for t in range(w.T)]
+        batches = [synth.make_batch(w, 5)]
+        got, _ = run_gpu(w, tabs, batches, want_perm=False)
+        c = case_of(w)
+        ref = oracle.pipeline(c, [t.numpy() for t in tabs], batches[0][0].numpy(), batches[0][1].numpy())
+        for k in ("Y", "Out"):
+            assert np.array_equal(bits(got[0][k]), bits(ref[k])), (w.name, k)
