@@ -50,7 +50,7 @@ def stage_bytes(w, nnz: int) -> dict:
 
 def recorded_traffic(cfg: int):
     """HBM bytes per pool launch from the committed rocprofv3 counter summary, if present."""
-    path = os.path.join(ROOT, "profiles", f"pool_rows_cfg{cfg}_pmc.txt")
+    path = os.path.join(ROOT, "profiles", f"pool_stream_cfg{cfg}_pmc.txt")
     try:
         m = re.search(r"^traffic_bytes_per_launch:\s*([0-9.eE+]+)", open(path).read(), re.M)
         return float(m.group(1)) if m else None
@@ -181,7 +181,7 @@ def main() -> int:
                    + (f" [every bag {args.bag_fixed} lookups]" if args.bag_fixed else ""),
                    "P": w.P, "T": w.T, "D": w.D, "B": w.B, "k": w.k, "lookups_per_step": mean_nnz,
                    "table_bytes": w.table_bytes(), "distinct_batches": len(batches)},
-        "roofline": {"bound": "hbm", "kernel": "pool_rows (bls_embbag_pool)", "achieved": achieved,
+        "roofline": {"bound": "hbm", "kernel": "pool_stream (bls_embbag_pool)", "achieved": achieved,
                      "peak": PEAK_HBM_GBPS, "unit": "GB/s", "frac": achieved / PEAK_HBM_GBPS,
                      "traffic": recorded_traffic(args.config) if not args.index_dist and args.size == "full" else None,
                      "algorithmic_bytes_per_launch": sb["pool"], "avg_launch_ms": stage_ms["pool"]},
