@@ -1,0 +1,74 @@
+"""Do the pins bite?  Each case plants one plausible mistake in a copy of the oracle's C source
+(a transposed index, a dropped offset, an inclusive scan, a reversed loop, a wrong sign or bias),
+builds it on the CPU and checks that at least one pin test fails against it."""
+import ctypes
+import os
+import subprocess
+
+import pytest
+
+import oracle
+import tests.test_oracle_pins as pins
+
+SRC = os.path.join(os.path.dirname(oracle.__file__), "bls_oracle.c")
+
+MUTATIONS = {
+    "counts transposed": ("sendcounts[s * P + d] += 1;", "sendcounts[d * P + s] += 1;"),
+    "send displacements inclusive": ("{ sdispls[s * P + d] = run; run += sendcounts[s * P + d]; }",
+                                     "{ run += sendcounts[s * P + d]; sdispls[s * P + d] = run; }"),
+    "recv displacements not accumulated": ("{ rdispls[d * P + s] = run; run += recvcounts[d * P + s]; }",
+                                           "{ rdispls[d * P + s] = run; run += 0; }"),
+    "placement not stable": ("for (l = offsets[g]; l < offsets[g + 1]; ++l) {\n                int64_t idx = indices[l], r, rank;",
+                             "for (l = offsets[g + 1] - 1; l >= offsets[g]; --l) {\n                int64_t idx = indices[l], r, rank;"),
+    "local row not rebased": ("r = idx - (int64_t)d * rps;", "r = idx;"),
+    "plain sum wrong sign": ("a32 += x;", "a32 -= x;"),
+    "plain sum drops first term": ("for (l = offsets[g]; l < offsets[g + 1]; ++l) {\n                    float x",
+                                   "for (l = offsets[g] + 1; l < offsets[g + 1]; ++l) {\n                    float x"),
+    "pool ignores shard base": ("acc += elem(tables[t], dtype, (shard_first + ridx[j]) * D + c);",
+                                "acc += elem(tables[t], dtype, (ridx[j]) * D + c);"),
+    "pool column transposed": ("y[c] = acc;", "y[D - 1 - c] = acc;"),
+    "pack drops mini-batch offset": ("Y + ybase + ((int64_t)tl * B + f + b_loc) * D, sizeof(float) * D);",
+                                     "Y + ybase + ((int64_t)tl * B + b_loc) * D, sizeof(float) * D);"),
+    "exchange block sizes from the other side": ("prcount[s * P + d] = pcount[d * P + s];", "prcount[s * P + d] = pcount[s * P + d];"),
+    "unpack keeps only the last partial": ("for (c = 0; c < D; ++c) o[c] += r[c];", "for (c = 0; c < D; ++c) o[c] = r[c];"),
+    "unpack reads local table index t": ("R + rbase + blk + ((int64_t)loc[t] * n + b_loc) * D;",
+                                         "R + rbase + blk + ((int64_t)(part_kind ? loc[t] : 0) * n + b_loc) * D;"),
+    "half exponent bias": ("bits = sign | ((e + 127 - 15) << 23) | (m << 13);", "bits = sign | ((e + 127 - 16) << 23) | (m << 13);"),
+    "half subnormals flushed": ("if (m == 0) bits = sign;\n        else {", "if (m >= 0) bits = sign;\n        else {"),
+}
+
+PINS = [
+    lambda: pins.test_plan_matches_brute_force(pins.TINY[1], 3),
+    lambda: pins.test_plan_matches_brute_force(pins.TINY[2], 3),
+    lambda: pins.test_pipeline_out_matches_brute_force_and_plain(pins.TINY[1]),
+    lambda: pins.test_pipeline_out_matches_brute_force_and_plain(pins.TINY[2]),
+    lambda: pins.test_pooling_one_is_a_row_copy_and_integer_tables(),
+    lambda: pins.test_pack_exchange_unpack_addresses(pins.TINY[1]),
+    lambda: pins.test_pack_exchange_unpack_addresses(pins.TINY[2]),
+    lambda: pins.test_against_torch_embedding_bag(5, "small"),
+    lambda: pins.test_half_conversion_all_bit_patterns(),
+]
+
+
+@pytest.mark.parametrize("name", list(MUTATIONS))
+def test_planted_mistake_is_caught(name, tmp_path, monkeypatch):
+    old, new = MUTATIONS[name]
+    src = open(SRC).read()
+    assert src.count(old) >= 1, f"pattern for '{name}' no longer in the oracle source"
+    mutated = tmp_path / "mut.c"
+    mutated.write_text(src.replace(old, new, 1))
+    lib = tmp_path / "libmut.so"
+    subprocess.check_call(["gcc", "-O1", "-ffp-contract=off", "-std=c99", "-shared", "-fPIC", "-o", str(lib), str(mutated)])
+    monkeypatch.setattr(oracle, "_lib", ctypes.CDLL(str(lib)))
+    caught = 0
+    for pin in PINS:
+        try:
+            pin()
+        except (AssertionError, oracle.OracleError):
+            caught += 1
+    assert caught >= 1, f"no pin noticed: {name}"
+
+
+def test_pins_pass_on_the_real_oracle():
+    for pin in PINS:
+        pin()
