@@ -163,6 +163,40 @@ def main() -> int:
     c.bls_check()
     note(f"{args.steps} timed steps: {dt / args.steps * 1e3:.3f} ms per step")
 
+    # achievable ceiling for the permute stages: a plain device copy of one pooled buffer
+    cp = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+    pipe.send.copy_(pipe.pooled)
+    cp[0].record()
+    for _ in range(10):
+        pipe.send.copy_(pipe.pooled)
+    cp[1].record()
+    torch.cuda.synchronize()
+    copy_gbps = 2 * pipe.pooled.numel() * 4 / (cp[0].elapsed_time(cp[1]) / 10 * 1e-3) / 1e9
+
+    # the same work with the owner side fused (bls_embbag_pool_put: no pooled or send buffer);
+    # reported beside the staged path, never as `value`
+    def fused_step(i: int):
+        ix, off = batches[i % len(batches)]
+        nnz = nnzs[i % len(batches)]
+        c.bls_plan(ix, off, nnz, pipe.sendcounts, pipe.sdispls, pipe.recvcounts, pipe.rdispls,
+                   pipe.ridx, pipe.segoff, None, pipe.ws)
+        it, slot = c.bls_ring_advance()
+        c.bls_embbag_pool_put(pipe.ridx, pipe.segoff, nnz, slot)
+        c.bls_unpack(it, out)
+        return nnz
+
+    for i in range(args.warmup):
+        fused_step(i)
+    torch.cuda.synchronize()
+    tf = time.perf_counter()
+    fused_lookups = 0
+    for i in range(args.steps):
+        fused_lookups += fused_step(args.warmup + i)
+    torch.cuda.synchronize()
+    dtf = time.perf_counter() - tf
+    c.bls_check()
+    note(f"{args.steps} fused steps: {dtf / args.steps * 1e3:.3f} ms per step")
+
     stage_ms = {n: sum(e[k].elapsed_time(e[k + 1]) for e in events) / args.steps for k, n in enumerate(names)}
     mean_nnz = lookups / args.steps
     sb = stage_bytes(w, int(mean_nnz))
@@ -189,6 +223,11 @@ def main() -> int:
                      "pool_plus_pack_frac_of_peak": pool_pack_gbps / PEAK_HBM_GBPS},
         "stage_ms": stage_ms,
         "stage_gbps": {n: sb[n] / (stage_ms[n] * 1e-3) / 1e9 for n in names},
+        "fused_owner_side": {"entry_point": "bls_plan + bls_embbag_pool_put + bls_unpack", "ms_per_step": dtf / args.steps * 1e3,
+                             "lookups_per_s": fused_lookups / dtf},
+        "bucket_pool_pack": {"ms": stage_ms["plan"] + stage_ms["pool"] + stage_ms["pack"],
+                             "lookups_per_s": mean_nnz / ((stage_ms["plan"] + stage_ms["pool"] + stage_ms["pack"]) * 1e-3)},
+        "plain_copy_gbps": copy_gbps,
         "setup_s": round(t_setup, 2),
     }
     if not args.no_cpu_baseline:

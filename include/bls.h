@@ -13,6 +13,7 @@
  *   bls_ring_advance    take the next of the k receive buffers, slot = iteration mod k
  *   bls_alltoallv_local the alltoallv itself: S(d) blocks into R(s, slot)
  *   bls_unpack          completion: copy R(s, slot) out as [B][T][D], free the slot
+ * (bls_embbag_pool_put fuses pool, pack and the alltoallv: pooled vectors go straight into the slot.)
  *
  * Notation (used in every comment below): P ranks, T tables, B global batch, D vector
  * length, K = max(k, 1) ring slots, F = 1 (table-wise partition) or P (row-wise),
@@ -148,6 +149,15 @@ int bls_ring_advance(bls_ctx *ctx, int64_t *iter_out, int32_t *slot_out, void *h
  * R_s(slot)[d][t_loc][b_loc][:] = S_d[s][t_loc][b_loc][:] for all P*P (d, s) blocks.
  * `slot` must be the slot of the youngest iteration started and not yet exchanged. */
 int bls_alltoallv_local(bls_ctx *ctx, const float *d_send, int32_t slot, void *hip_stream);
+
+/* The owner side in one pass: EmbeddingBag sum whose results are put straight into the
+ * receive regions of ring slot `slot` (Alltoallv initiation is a sequence of one-sided puts
+ * into R(dst, slot); here the source of each put is the pooling kernel's accumulator rather
+ * than a send buffer, so neither Y nor S is written).  Leaves R(*, slot) exactly as
+ * bls_embbag_pool + bls_pack + bls_alltoallv_local would, bit for bit.  `slot` as for
+ * bls_alltoallv_local; arguments as for bls_embbag_pool. */
+int bls_embbag_pool_put(bls_ctx *ctx, const int64_t *d_ridx, const int64_t *d_segoff, int64_t nnz,
+                        int32_t slot, void *hip_stream);
 
 /* Alltoallv completion for iteration `iter`, which must be the oldest in flight
  * (wait() completes the tail request and pops it): copy the receive regions of its

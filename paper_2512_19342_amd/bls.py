@@ -20,7 +20,7 @@ BLS_TABLE_WISE, BLS_ROW_WISE = 0, 1
 
 EXPORTS = [
     "bls_create", "bls_destroy", "bls_set_shard", "bls_sizes", "bls_pooled_counts", "bls_plan",
-    "bls_embbag_pool", "bls_pack", "bls_set_ring", "bls_ring_advance", "bls_alltoallv_local",
+    "bls_embbag_pool", "bls_embbag_pool_put", "bls_pack", "bls_set_ring", "bls_ring_advance", "bls_alltoallv_local",
     "bls_unpack", "bls_ring_state", "bls_check", "bls_last_error",
 ]
 
@@ -55,6 +55,7 @@ def lib() -> C.CDLL:
         L.bls_pooled_counts.argtypes = [vp] + [C.POINTER(C.c_int64)] * 4
         L.bls_plan.argtypes = [vp, i64p, i64p, C.c_int64, i64p, i64p, i64p, i64p, i64p, i64p, i64p, vp, C.c_size_t, vp]
         L.bls_embbag_pool.argtypes = [vp, i64p, i64p, C.c_int64, vp, vp]
+        L.bls_embbag_pool_put.argtypes = [vp, i64p, i64p, C.c_int64, C.c_int32, vp]
         L.bls_pack.argtypes = [vp, vp, vp, vp]
         L.bls_set_ring.argtypes = [vp, vp, C.c_size_t]
         L.bls_ring_advance.argtypes = [vp, C.POINTER(C.c_int64), C.POINTER(C.c_int32), vp]
@@ -159,6 +160,9 @@ class Context:
 
     def bls_embbag_pool(self, ridx, segoff, nnz, pooled, stream=None):
         self._call("bls_embbag_pool", _ptr(ridx), _ptr(segoff), int(nnz), _ptr(pooled), _stream(stream))
+
+    def bls_embbag_pool_put(self, ridx, segoff, nnz, slot, stream=None):
+        self._call("bls_embbag_pool_put", _ptr(ridx), _ptr(segoff), int(nnz), int(slot), _stream(stream))
 
     def bls_pack(self, pooled, send, stream=None):
         self._call("bls_pack", _ptr(pooled), _ptr(send), _stream(stream))

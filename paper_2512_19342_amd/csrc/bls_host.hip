@@ -233,7 +233,7 @@ extern "C" int bls_embbag_pool(bls_ctx *ctx, const int64_t *d_ridx, const int64_
     if (((uintptr_t)d_pooled & 15u) != 0) return bls_fail(ctx, BLS_EINVAL, "bls_embbag_pool: output must be 16-byte aligned");
     int rc = bls_commit(ctx);
     if (rc) return rc;
-    return bls_launch_pool(ctx, d_ridx, d_segoff, nnz, d_pooled, (hipStream_t)hip_stream);
+    return bls_launch_pool(ctx, d_ridx, d_segoff, nnz, d_pooled, 0, (hipStream_t)hip_stream);
 }
 
 extern "C" int bls_pack(bls_ctx *ctx, const float *d_pooled, float *d_send, void *hip_stream)
@@ -284,6 +284,7 @@ extern "C" int bls_ring_advance(bls_ctx *ctx, int64_t *iter_out, int32_t *slot_o
     return BLS_OK;
 }
 
+
 static int ensure_events(bls_ctx *ctx, RingSlot &r)
 {
     if (!r.filled) BLS_HIP(ctx, hipEventCreateWithFlags(&r.filled, hipEventDisableTiming));
@@ -291,23 +292,51 @@ static int ensure_events(bls_ctx *ctx, RingSlot &r)
     return BLS_OK;
 }
 
-extern "C" int bls_alltoallv_local(bls_ctx *ctx, const float *d_send, int32_t slot, void *hip_stream)
+// The slot must be the one handed out by the latest bls_ring_advance and still be empty.
+static int slot_to_fill(bls_ctx *ctx, int32_t slot, const char *who, RingSlot **out)
 {
-    if (!ctx) return BLS_EINVAL;
-    if (!d_send || ((uintptr_t)d_send & 15u) != 0) return bls_fail(ctx, BLS_EINVAL, "bls_alltoallv_local: NULL or misaligned send buffer");
-    if (!ctx->slots) return bls_fail(ctx, BLS_EINVAL, "bls_alltoallv_local: no ring (bls_set_ring)");
-    if (slot < 0 || slot >= ctx->K) return bls_fail(ctx, BLS_EINVAL, "bls_alltoallv_local: slot out of range");
+    if (!ctx->slots) return bls_fail(ctx, BLS_EINVAL, "no ring (bls_set_ring)");
+    if (slot < 0 || slot >= ctx->K) return bls_fail(ctx, BLS_EINVAL, "slot out of range");
     RingSlot &r = ctx->ring[slot];
-    if (r.state != 1 || r.iter != ctx->head - 1)
-        return bls_fail(ctx, BLS_EORDER, "bls_alltoallv_local: slot does not belong to the iteration just started");
+    if (r.state != 1 || r.iter != ctx->head - 1) {
+        ctx->err = std::string(who) + ": slot does not belong to the iteration just started";
+        return BLS_EORDER;
+    }
     int rc = bls_commit(ctx);
     if (rc) return rc;
     rc = ensure_events(ctx, r);
     if (rc) return rc;
+    *out = &r;
+    return BLS_OK;
+}
+
+extern "C" int bls_alltoallv_local(bls_ctx *ctx, const float *d_send, int32_t slot, void *hip_stream)
+{
+    if (!ctx) return BLS_EINVAL;
+    if (!d_send || ((uintptr_t)d_send & 15u) != 0) return bls_fail(ctx, BLS_EINVAL, "bls_alltoallv_local: NULL or misaligned send buffer");
+    RingSlot *r = nullptr;
+    int rc = slot_to_fill(ctx, slot, "bls_alltoallv_local", &r);
+    if (rc) return rc;
     rc = bls_launch_exchange(ctx, d_send, (float *)(ctx->slots + (size_t)slot * ctx->slot_bytes), (hipStream_t)hip_stream);
     if (rc) return rc;
-    BLS_HIP(ctx, hipEventRecord(r.filled, (hipStream_t)hip_stream));
-    r.state = 2;
+    BLS_HIP(ctx, hipEventRecord(r->filled, (hipStream_t)hip_stream));
+    r->state = 2;
+    return BLS_OK;
+}
+
+extern "C" int bls_embbag_pool_put(bls_ctx *ctx, const int64_t *d_ridx, const int64_t *d_segoff, int64_t nnz,
+                                   int32_t slot, void *hip_stream)
+{
+    if (!ctx) return BLS_EINVAL;
+    if (nnz < 0 || !d_segoff || (nnz > 0 && !d_ridx)) return bls_fail(ctx, BLS_EINVAL, "bls_embbag_pool_put: NULL argument");
+    RingSlot *r = nullptr;
+    int rc = slot_to_fill(ctx, slot, "bls_embbag_pool_put", &r);
+    if (rc) return rc;
+    rc = bls_launch_pool(ctx, d_ridx, d_segoff, nnz, (float *)(ctx->slots + (size_t)slot * ctx->slot_bytes), 1,
+                         (hipStream_t)hip_stream);
+    if (rc) return rc;
+    BLS_HIP(ctx, hipEventRecord(r->filled, (hipStream_t)hip_stream));
+    r->state = 2;
     return BLS_OK;
 }
 

@@ -87,7 +87,9 @@ int bls_launch_plan(bls_ctx *ctx, const int64_t *idx, const int64_t *off, int64_
                     int64_t *sdispls, int64_t *recvcounts, int64_t *rdispls, int64_t *ridx, int64_t *segoff,
                     int64_t *perm, void *ws, size_t ws_bytes, hipStream_t st);
 size_t bls_plan_ws_bytes(const bls_ctx *ctx);
-int bls_launch_pool(bls_ctx *ctx, const int64_t *ridx, const int64_t *segoff, int64_t nnz, float *Y, hipStream_t st);
+// to_slot = 0: Y in pooled order (y); 1: Y is a ring slot, vectors go to receive order (rho)
+int bls_launch_pool(bls_ctx *ctx, const int64_t *ridx, const int64_t *segoff, int64_t nnz, float *Y, int to_slot,
+                    hipStream_t st);
 int bls_launch_pack(bls_ctx *ctx, const float *Y, float *S, hipStream_t st);
 int bls_launch_exchange(bls_ctx *ctx, const float *S, float *R, hipStream_t st);
 int bls_launch_unpack(bls_ctx *ctx, const float *R, float *out, hipStream_t st);

@@ -114,7 +114,7 @@ __device__ __forceinline__ uint64_t group_broadcast64(uint64_t v, int gbase4, in
 template <int G, int DT, int VB, int U>
 __global__ __launch_bounds__(kThreads) void pool_rows(DevDesc dd, const int64_t *__restrict__ ridx,
                                                       const int64_t *__restrict__ segoff, int64_t nnz,
-                                                      float *__restrict__ Y)
+                                                      float *__restrict__ Y, int to_slot)
 {
     using A = Acc<DT, VB>;
     const int q = blockIdx.y;
@@ -127,11 +127,12 @@ __global__ __launch_bounds__(kThreads) void pool_rows(DevDesc dd, const int64_t 
     const char *__restrict__ base = (const char *)dd.q_base[q] + (uint32_t)li * VB;
     const int64_t shard_rows = dd.q_rows[q];
 
-    int64_t beg = 0, len = 0;
+    int64_t beg = 0, len = 0, out = 0;
     if (live) {
         int s; uint32_t b_loc, n;
         bls_split_sample(dd, b, s, b_loc, n);
         const int64_t sg = bls_sigma(dd, q, s, b_loc, n);
+        out = to_slot ? bls_rho(dd, q, s, b_loc, n) : (int64_t)q * dd.B + b;
         beg = segoff[sg];
         const int64_t end = segoff[sg + 1];
         len = end - beg;
@@ -163,7 +164,7 @@ __global__ __launch_bounds__(kThreads) void pool_rows(DevDesc dd, const int64_t 
             for (int u = 0; u < U; ++u) acc.add(v[u]);      // adding +0 for skipped rows changes nothing
         }
     }
-    if (live && col_ok) acc.store(Y + ((int64_t)q * dd.B + b) * dd.D + li * A::NV);
+    if (live && col_ok) acc.store(Y + out * dd.D + li * A::NV);
 }
 
 // G >= 4 lanes stream up to nb_max (< G) consecutive segments of one (q, s) block.
@@ -171,7 +172,7 @@ __global__ __launch_bounds__(kThreads) void pool_rows(DevDesc dd, const int64_t 
 template <int G, int DT, int VB, int U>
 __global__ __launch_bounds__(kThreads) void pool_stream(DevDesc dd, const int64_t *__restrict__ ridx,
                                                         const int64_t *__restrict__ segoff, int64_t nnz,
-                                                        float *__restrict__ Y, int nb_max, uint32_t chunks_per_s)
+                                                        float *__restrict__ Y, int to_slot, int nb_max, uint32_t chunks_per_s)
 {
     using A = Acc<DT, VB>;
     const int q = blockIdx.y;
@@ -189,7 +190,7 @@ __global__ __launch_bounds__(kThreads) void pool_stream(DevDesc dd, const int64_
 
     // this group's segments: samples [b0, b0 + nb) of mini-batch s
     int nb = 0;
-    int64_t sg0 = 0, b0 = 0;
+    int64_t sg0 = 0, out0 = 0;                                // first segment, its vector in the output
     if (s < (uint32_t)dd.P) {
         const int64_t f = dd.first[s], n = dd.first[s + 1] - f;
         const int64_t bl0 = (int64_t)chunk * nb_max;
@@ -197,7 +198,7 @@ __global__ __launch_bounds__(kThreads) void pool_stream(DevDesc dd, const int64_
             nb = n - bl0 < nb_max ? (int)(n - bl0) : nb_max;
             const int d = dd.q_d[q];
             sg0 = (int64_t)dd.nsum[d] * dd.B + (int64_t)dd.n_loc[d] * f + (int64_t)(q - dd.nsum[d]) * n + bl0;
-            b0 = f + bl0;
+            out0 = to_slot ? (int64_t)dd.Q * f + (int64_t)q * n + bl0 : (int64_t)q * dd.B + f + bl0;
         }
     }
     // lane i of the group holds the start of segment i (i <= nb); all must be in order
@@ -225,7 +226,7 @@ __global__ __launch_bounds__(kThreads) void pool_stream(DevDesc dd, const int64_
             if (!__any(need)) break;
             const int nxt = __shfl(rel, gbase + (cur + 2 < G ? cur + 2 : G - 1), 64);
             if (need) {
-                if (col_ok) acc.store(Y + ((int64_t)q * dd.B + b0 + cur) * dd.D + li * A::NV);
+                if (col_ok) acc.store(Y + (out0 + cur) * dd.D + li * A::NV);
                 acc.zero();
                 ++cur;
                 cur_end = cur < nb ? nxt : -1;
@@ -280,7 +281,7 @@ __global__ __launch_bounds__(kThreads) void pool_stream(DevDesc dd, const int64_
 template <int DT>
 __global__ __launch_bounds__(kThreads) void pool_rows_generic(DevDesc dd, const int64_t *__restrict__ ridx,
                                                               const int64_t *__restrict__ segoff, int64_t nnz,
-                                                              float *__restrict__ Y)
+                                                              float *__restrict__ Y, int to_slot)
 {
     const int q = blockIdx.y;
     const int lane = threadIdx.x & 63;
@@ -293,7 +294,7 @@ __global__ __launch_bounds__(kThreads) void pool_rows_generic(DevDesc dd, const 
     if (beg < 0 || end < beg || end > nnz) { if (lane == 0) flag_error(dd); end = beg = 0; }
     const int64_t shard_rows = dd.q_rows[q];
     const void *base = dd.q_base[q];
-    float *y = Y + ((int64_t)q * dd.B + b) * dd.D;
+    float *y = Y + (to_slot ? bls_rho(dd, q, s, b_loc, n) : (int64_t)q * dd.B + b) * dd.D;
     for (int c = lane; c < dd.D; c += 64) {
         float acc = 0.f;
         for (int64_t j = beg; j < end; ++j) {
@@ -313,7 +314,7 @@ int env_int(const char *name, int dflt)
 }
 
 template <int G, int DT, int VB, int U>
-void launch_rows(const bls_ctx *ctx, const int64_t *ridx, const int64_t *segoff, int64_t nnz, float *Y, hipStream_t st)
+void launch_rows(const bls_ctx *ctx, const int64_t *ridx, const int64_t *segoff, int64_t nnz, float *Y, int to_slot, hipStream_t st)
 {
     constexpr int UU = U < G ? U : G;
     const uint32_t per_block = kThreads / G;
@@ -328,48 +329,48 @@ void launch_rows(const bls_ctx *ctx, const int64_t *ridx, const int64_t *segoff,
         const uint32_t chunks = (uint32_t)((n_max + nb - 1) / nb);
         const int64_t groups = (int64_t)chunks * ctx->P;
         dim3 grid((unsigned)((groups + per_block - 1) / per_block), ctx->Q);
-        pool_stream<G, DT, VB, UU><<<grid, kThreads, 0, st>>>(ctx->desc, ridx, segoff, nnz, Y, nb, chunks);
+        pool_stream<G, DT, VB, UU><<<grid, kThreads, 0, st>>>(ctx->desc, ridx, segoff, nnz, Y, to_slot, nb, chunks);
     } else {
         dim3 grid((unsigned)((ctx->B + per_block - 1) / per_block), ctx->Q);
-        pool_rows<G, DT, VB, UU><<<grid, kThreads, 0, st>>>(ctx->desc, ridx, segoff, nnz, Y);
+        pool_rows<G, DT, VB, UU><<<grid, kThreads, 0, st>>>(ctx->desc, ridx, segoff, nnz, Y, to_slot);
     }
 }
 
 template <int DT, int VB, int U>
 bool dispatch_lanes(const bls_ctx *ctx, int lanes, const int64_t *ridx, const int64_t *segoff, int64_t nnz, float *Y,
-                    hipStream_t st)
+                    int to_slot, hipStream_t st)
 {
     switch (lanes) {
-    case 1: if constexpr (VB == 16) { launch_rows<1, DT, VB, U>(ctx, ridx, segoff, nnz, Y, st); return true; } break;
-    case 2: if constexpr (VB == 16) { launch_rows<2, DT, VB, U>(ctx, ridx, segoff, nnz, Y, st); return true; } break;
-    case 4: if constexpr (VB == 16) { launch_rows<4, DT, VB, U>(ctx, ridx, segoff, nnz, Y, st); return true; } break;
-    case 8: if constexpr (VB == 16) { launch_rows<8, DT, VB, U>(ctx, ridx, segoff, nnz, Y, st); return true; } break;
-    case 16: if constexpr (VB >= 8) { launch_rows<16, DT, VB, U>(ctx, ridx, segoff, nnz, Y, st); return true; } break;
-    case 32: launch_rows<32, DT, VB, U>(ctx, ridx, segoff, nnz, Y, st); return true;
-    case 64: launch_rows<64, DT, VB, U>(ctx, ridx, segoff, nnz, Y, st); return true;
+    case 1: if constexpr (VB == 16) { launch_rows<1, DT, VB, U>(ctx, ridx, segoff, nnz, Y, to_slot, st); return true; } break;
+    case 2: if constexpr (VB == 16) { launch_rows<2, DT, VB, U>(ctx, ridx, segoff, nnz, Y, to_slot, st); return true; } break;
+    case 4: if constexpr (VB == 16) { launch_rows<4, DT, VB, U>(ctx, ridx, segoff, nnz, Y, to_slot, st); return true; } break;
+    case 8: if constexpr (VB == 16) { launch_rows<8, DT, VB, U>(ctx, ridx, segoff, nnz, Y, to_slot, st); return true; } break;
+    case 16: if constexpr (VB >= 8) { launch_rows<16, DT, VB, U>(ctx, ridx, segoff, nnz, Y, to_slot, st); return true; } break;
+    case 32: launch_rows<32, DT, VB, U>(ctx, ridx, segoff, nnz, Y, to_slot, st); return true;
+    case 64: launch_rows<64, DT, VB, U>(ctx, ridx, segoff, nnz, Y, to_slot, st); return true;
     }
     return false;
 }
 
 template <int DT, int VB>
 bool dispatch_unroll(const bls_ctx *ctx, int lanes, int unroll, const int64_t *ridx, const int64_t *segoff, int64_t nnz,
-                     float *Y, hipStream_t st)
+                     float *Y, int to_slot, hipStream_t st)
 {
     switch (unroll) {
-    case 4: return dispatch_lanes<DT, VB, 4>(ctx, lanes, ridx, segoff, nnz, Y, st);
-    case 16: return dispatch_lanes<DT, VB, 16>(ctx, lanes, ridx, segoff, nnz, Y, st);
-    default: return dispatch_lanes<DT, VB, 8>(ctx, lanes, ridx, segoff, nnz, Y, st);
+    case 4: return dispatch_lanes<DT, VB, 4>(ctx, lanes, ridx, segoff, nnz, Y, to_slot, st);
+    case 16: return dispatch_lanes<DT, VB, 16>(ctx, lanes, ridx, segoff, nnz, Y, to_slot, st);
+    default: return dispatch_lanes<DT, VB, 8>(ctx, lanes, ridx, segoff, nnz, Y, to_slot, st);
     }
 }
 
 template <int DT>
 bool dispatch_rows(const bls_ctx *ctx, int vb, int lanes, int unroll, const int64_t *ridx, const int64_t *segoff,
-                   int64_t nnz, float *Y, hipStream_t st)
+                   int64_t nnz, float *Y, int to_slot, hipStream_t st)
 {
     switch (vb) {
-    case 16: return dispatch_unroll<DT, 16>(ctx, lanes, unroll, ridx, segoff, nnz, Y, st);
-    case 8: return dispatch_unroll<DT, 8>(ctx, lanes, unroll, ridx, segoff, nnz, Y, st);
-    case 4: return dispatch_unroll<DT, 4>(ctx, lanes, unroll, ridx, segoff, nnz, Y, st);
+    case 16: return dispatch_unroll<DT, 16>(ctx, lanes, unroll, ridx, segoff, nnz, Y, to_slot, st);
+    case 8: return dispatch_unroll<DT, 8>(ctx, lanes, unroll, ridx, segoff, nnz, Y, to_slot, st);
+    case 4: return dispatch_unroll<DT, 4>(ctx, lanes, unroll, ridx, segoff, nnz, Y, to_slot, st);
     }
     return false;
 }
@@ -377,7 +378,7 @@ bool dispatch_rows(const bls_ctx *ctx, int vb, int lanes, int unroll, const int6
 
 }  // namespace
 
-int bls_launch_pool(bls_ctx *ctx, const int64_t *ridx, const int64_t *segoff, int64_t nnz, float *Y, hipStream_t st)
+int bls_launch_pool(bls_ctx *ctx, const int64_t *ridx, const int64_t *segoff, int64_t nnz, float *Y, int to_slot, hipStream_t st)
 {
     const int64_t row_bytes = (int64_t)ctx->D * (ctx->dtype == BLS_FP16 ? 2 : 4);
     // bytes per lane and row, rows in flight per lane: BLS_POOL_VB / BLS_POOL_U override the defaults
@@ -390,13 +391,13 @@ int bls_launch_pool(bls_ctx *ctx, const int64_t *ridx, const int64_t *segoff, in
     if (row_bytes % vb == 0 && row_bytes <= 64 * (int64_t)vb) {
         int lanes = 1;
         while ((int64_t)lanes * vb < row_bytes) lanes <<= 1;
-        done = ctx->dtype == BLS_FP16 ? dispatch_rows<BLS_FP16>(ctx, vb, lanes, unroll, ridx, segoff, nnz, Y, st)
-                                      : dispatch_rows<BLS_FP32>(ctx, vb, lanes, unroll, ridx, segoff, nnz, Y, st);
+        done = ctx->dtype == BLS_FP16 ? dispatch_rows<BLS_FP16>(ctx, vb, lanes, unroll, ridx, segoff, nnz, Y, to_slot, st)
+                                      : dispatch_rows<BLS_FP32>(ctx, vb, lanes, unroll, ridx, segoff, nnz, Y, to_slot, st);
     }
     if (!done) {
         dim3 grid((unsigned)((ctx->B + kThreads / 64 - 1) / (kThreads / 64)), ctx->Q);
-        if (ctx->dtype == BLS_FP16) pool_rows_generic<BLS_FP16><<<grid, kThreads, 0, st>>>(ctx->desc, ridx, segoff, nnz, Y);
-        else pool_rows_generic<BLS_FP32><<<grid, kThreads, 0, st>>>(ctx->desc, ridx, segoff, nnz, Y);
+        if (ctx->dtype == BLS_FP16) pool_rows_generic<BLS_FP16><<<grid, kThreads, 0, st>>>(ctx->desc, ridx, segoff, nnz, Y, to_slot);
+        else pool_rows_generic<BLS_FP32><<<grid, kThreads, 0, st>>>(ctx->desc, ridx, segoff, nnz, Y, to_slot);
     }
     BLS_HIP(ctx, hipGetLastError());
     return BLS_OK;

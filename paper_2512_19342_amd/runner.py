@@ -71,6 +71,16 @@ class Pipeline:
         c.bls_alltoallv_local(self.send, slot, stream)
         return it, slot
 
+    def issue_fused(self, indices: torch.Tensor, offsets: torch.Tensor, nnz: int, stream=None):
+        """plan, take a ring slot, pool straight into it (no pooled or send buffer)."""
+        c = self.ctx
+        assert nnz <= self.max_nnz
+        c.bls_plan(indices, offsets, nnz, self.sendcounts, self.sdispls, self.recvcounts, self.rdispls,
+                   self.ridx, self.segoff, self.perm, self.ws, stream)
+        it, slot = c.bls_ring_advance(stream)
+        c.bls_embbag_pool_put(self.ridx, self.segoff, nnz, slot, stream)
+        return it, slot
+
     def complete(self, it: int, out: torch.Tensor, stream=None):
         self.ctx.bls_unpack(it, out, stream)
 

@@ -259,3 +259,61 @@ def test_pool_launch_variants(vb, unroll, nb, monkeypatch):
         ref = oracle.pipeline(c, [t.numpy() for t in tabs], batches[0][0].numpy(), batches[0][1].numpy())
         for k in ("Y", "Out"):
             assert np.array_equal(bits(got[0][k]), bits(ref[k])), (w.name, k)
+
+
+FUSED = [synth.workload(1), synth.workload(2), synth.workload(3, "small"), synth.workload(4, "small"),
+         synth.workload(5, "small")] + [
+    synth.custom("edge", k=2, values="gauss", table_dtype=dt, seed=29, index_dist=("zipf", 1.1), **EDGE[i])
+    for i in (2, 4, 5, 6, 7, 8, 10) for dt in ("fp32", "fp16")]
+
+
+@pytest.mark.parametrize("w", FUSED, ids=lambda w: f"{w.name}-{w.table_dtype}-D{w.D}-P{w.P}")
+def test_pool_put_equals_staged_path(w):
+    """bls_embbag_pool_put (pool straight into the ring slot) must leave the receive regions and
+    the output exactly as pool + pack + alltoallv do, and as the oracle says."""
+    from paper_2512_19342_amd.runner import Pipeline
+    if w.name in ("cfg3s", "cfg4s"):
+        w.values = "gauss"
+    dev = torch.device("cuda:0")
+    tabs_cpu = [synth.make_table(w, t) for t in range(w.T)]
+    pipe = Pipeline(w, [t.to(dev) for t in tabs_cpu], 1 << 21)
+    c = case_of(w)
+    tabs_np = [t.numpy() for t in tabs_cpu]
+    pending = []
+    for it in range(3):
+        ix, off = synth.make_batch(w, it)
+        nnz = int(off[-1])
+        if len(pending) == pipe.ctx.K:
+            j, out, ref = pending.pop(0)
+            pipe.complete(j, out)
+            assert np.array_equal(bits(out.cpu().numpy()), bits(ref["Out"])), (w.name, j)
+        j, slot = pipe.issue_fused(ix.to(dev), off.to(dev), nnz)
+        ref = oracle.pipeline(c, tabs_np, ix.numpy(), off.numpy())
+        assert np.array_equal(bits(pipe.slot_view(slot).cpu().numpy()), bits(ref["R"])), (w.name, it)
+        pending.append((j, pipe.new_out(), ref))
+    for j, out, ref in pending:
+        pipe.complete(j, out)
+        assert np.array_equal(bits(out.cpu().numpy()), bits(ref["Out"])), (w.name, j)
+    pipe.ctx.bls_check()
+
+
+def test_pool_put_needs_the_current_slot():
+    import paper_2512_19342_amd as B
+    from paper_2512_19342_amd.runner import Pipeline
+    w = synth.workload(4, "small")
+    dev = torch.device("cuda:0")
+    pipe = Pipeline(w, [synth.make_table(w, t).to(dev) for t in range(w.T)], 1 << 21)
+    ix, off = synth.make_batch(w, 0)
+    nnz = int(off[-1])
+    with pytest.raises(B.BlsError) as e:                  # no iteration started
+        pipe.ctx.bls_embbag_pool_put(pipe.ridx, pipe.segoff, 0, 0)
+    assert e.value.code == B.BLS_EORDER
+    j, slot = pipe.issue_fused(ix.to(dev), off.to(dev), nnz)
+    with pytest.raises(B.BlsError) as e:                  # slot already filled
+        pipe.ctx.bls_embbag_pool_put(pipe.ridx, pipe.segoff, nnz, slot)
+    assert e.value.code == B.BLS_EORDER
+    with pytest.raises(B.BlsError) as e:
+        pipe.ctx.bls_embbag_pool_put(pipe.ridx, pipe.segoff, nnz, 99)
+    assert e.value.code == B.BLS_EINVAL
+    pipe.complete(j, pipe.new_out())
+    pipe.ctx.bls_check()
