@@ -2,8 +2,8 @@
 //
 // Every lookup belongs to exactly one segment (owner d, requester s, local table, local
 // sample), and segments are numbered in owner order, so
-//   1. count   - the length of every segment (table-wise: the bag length; row-wise: one
-//                wavefront per bag splits its lookups over the P owners with ballots),
+//   1. count   - the length of every segment (table-wise: the bag length; row-wise: a
+//                group of lanes per bag splits its lookups over the P owners with ballots),
 //   2. scan    - an exclusive scan of the segment lengths (LDS-staged, three phases) gives
 //                segoff, and the alltoallv counts and displacements are differences of
 //                segoff at the (d, s) block edges - no atomics, no separate histogram,
@@ -54,24 +54,32 @@ __device__ __forceinline__ int owner_of_row(int64_t ix, int64_t rps)
     return rps <= 0xffffffffLL && ix <= 0xffffffffLL ? (int)((uint32_t)ix / (uint32_t)rps) : (int)(ix / rps);
 }
 
-// Row-wise: one wavefront per bag (t, b).  Lane o < P accumulates the number of the
-// bag's lookups that fall in owner o's block of rows.
+// Row-wise: a group of G >= P lanes per bag (t, b), several bags per wavefront.  One ballot
+// per owner tells every group how many of its lookups fall in that owner's block of rows;
+// lane o of the group accumulates owner o's count.
+template <int G>
 __global__ __launch_bounds__(kThreads) void plan_count_rowwise(DevDesc dd, const int64_t *__restrict__ idx,
                                                                const int64_t *__restrict__ off, int64_t nnz,
                                                                int64_t *__restrict__ seglen)
 {
     const int lane = threadIdx.x & 63;
+    const int li = lane & (G - 1), gbase = lane & ~(G - 1);
+    const unsigned long long gmask = G == 64 ? ~0ull : (1ull << (G & 63)) - 1ull;
     const int t = blockIdx.y;
-    const uint32_t b = blockIdx.x * (kThreads / 64) + (threadIdx.x >> 6);
-    if (b >= (uint32_t)dd.B) return;                     // uniform per wavefront
-    const int64_t g = (int64_t)t * dd.B + b;
-    const int64_t lo = off[g], hi = off[g + 1];
-    int64_t len = hi - lo;
-    if (lo < 0 || hi > nnz || len < 0) { if (lane == 0) flag_error(dd); len = 0; }
+    const uint32_t b = blockIdx.x * (kThreads / G) + threadIdx.x / G;
+    const bool live = b < (uint32_t)dd.B;
+    int64_t lo = 0, len = 0;
+    if (live) {
+        const int64_t g = (int64_t)t * dd.B + b;
+        lo = off[g];
+        const int64_t hi = off[g + 1];
+        len = hi - lo;
+        if (lo < 0 || hi > nnz || len < 0) { if (li == 0) flag_error(dd); len = 0; }
+    }
     const int64_t rows = dd.rows[t], rps = dd.rps[t];
     int64_t cnt = 0;
-    for (int64_t c = 0; c < len; c += 64) {
-        const int64_t j = c + lane;
+    for (int64_t c = 0; __any(c < len); c += G) {
+        const int64_t j = c + li;
         int d = -1;
         if (j < len) {
             const int64_t ix = idx[lo + j];
@@ -79,14 +87,14 @@ __global__ __launch_bounds__(kThreads) void plan_count_rowwise(DevDesc dd, const
             else d = owner_of_row(ix, rps);
         }
         for (int o = 0; o < dd.P; ++o) {
-            const unsigned long long m = __ballot(d == o);
-            if (lane == o) cnt += __popcll(m);
+            const unsigned long long m = (__ballot(d == o) >> gbase) & gmask;
+            if (li == o) cnt += __popcll(m);
         }
     }
-    if (lane < dd.P) {
+    if (live && li < dd.P) {
         int s; uint32_t b_loc, n;
         bls_split_sample(dd, b, s, b_loc, n);
-        seglen[bls_sigma(dd, lane * dd.T + t, s, b_loc, n)] = cnt;
+        seglen[bls_sigma(dd, li * dd.T + t, s, b_loc, n)] = cnt;
     }
 }
 
@@ -256,9 +264,10 @@ __global__ __launch_bounds__(kThreads) void plan_scatter_runs(DevDesc dd, const 
     }
 }
 
-// Row-wise: one wavefront per bag.  Lane o < P holds the start of owner o's segment and
-// how many of the bag's lookups it has already received; a lookup's place is that start
-// plus the number of earlier lanes with the same owner.
+// Row-wise: a group of G >= P lanes per bag.  Lane o of the group holds the start of owner
+// o's segment and how many of the bag's lookups it has already received; a lookup's place is
+// that start plus the number of earlier lanes of the group with the same owner.
+template <int G>
 __global__ __launch_bounds__(kThreads) void plan_scatter_rowwise(DevDesc dd, const int64_t *__restrict__ idx,
                                                                  const int64_t *__restrict__ off, int64_t nnz,
                                                                  const int64_t *__restrict__ segoff,
@@ -267,24 +276,30 @@ __global__ __launch_bounds__(kThreads) void plan_scatter_rowwise(DevDesc dd, con
                                                                  const int64_t *__restrict__ rabs)
 {
     const int lane = threadIdx.x & 63;
+    const int li = lane & (G - 1), gbase = lane & ~(G - 1);
+    const unsigned long long gmask = G == 64 ? ~0ull : (1ull << (G & 63)) - 1ull;
+    const unsigned long long below = (1ull << li) - 1ull;
     const int t = blockIdx.y;
-    const uint32_t b = blockIdx.x * (kThreads / 64) + (threadIdx.x >> 6);
-    if (b >= (uint32_t)dd.B) return;                     // uniform per wavefront
-    const int64_t g = (int64_t)t * dd.B + b;
-    const int64_t lo = off[g], hi = off[g + 1];
-    const int64_t len = hi - lo;
-    if (lo < 0 || hi > nnz || len < 0) return;           // flagged by the count kernel
-    const int64_t rows = dd.rows[t], rps = dd.rps[t];
-    int s; uint32_t b_loc, n;
-    bls_split_sample(dd, b, s, b_loc, n);
+    const uint32_t b = blockIdx.x * (kThreads / G) + threadIdx.x / G;
+    const bool live = b < (uint32_t)dd.B;
+    int64_t lo = 0, len = 0;
     int64_t next = 0, to_send = 0;                        // lane o: next free place of owner o
-    if (lane < dd.P) {
-        next = segoff[bls_sigma(dd, lane * dd.T + t, s, b_loc, n)];
-        if (perm) to_send = sabs[s * dd.P + lane] - rabs[lane * dd.P + s];
+    if (live) {
+        const int64_t g = (int64_t)t * dd.B + b;
+        lo = off[g];
+        const int64_t hi = off[g + 1];
+        len = hi - lo;
+        if (lo < 0 || hi > nnz || len < 0) len = 0;       // flagged by the count kernel
+        if (li < dd.P) {
+            int s; uint32_t b_loc, n;
+            bls_split_sample(dd, b, s, b_loc, n);
+            next = segoff[bls_sigma(dd, li * dd.T + t, s, b_loc, n)];
+            if (perm) to_send = sabs[s * dd.P + li] - rabs[li * dd.P + s];
+        }
     }
-    const unsigned long long below = (1ull << lane) - 1ull;
-    for (int64_t c = 0; c < len; c += 64) {
-        const int64_t j = c + lane;
+    const int64_t rows = dd.rows[t], rps = dd.rps[t];
+    for (int64_t c = 0; __any(c < len); c += G) {
+        const int64_t j = c + li;
         int d = -1;
         int64_t r = 0;
         if (j < len) {
@@ -293,11 +308,11 @@ __global__ __launch_bounds__(kThreads) void plan_scatter_rowwise(DevDesc dd, con
         }
         int rank = 0, add = 0;
         for (int o = 0; o < dd.P; ++o) {
-            const unsigned long long m = __ballot(d == o);
+            const unsigned long long m = (__ballot(d == o) >> gbase) & gmask;
             if (d == o) rank = __popcll(m & below);
-            if (lane == o) add = __popcll(m);
+            if (li == o) add = __popcll(m);
         }
-        const int src = d < 0 ? 0 : d;
+        const int src = gbase + (d < 0 ? 0 : d);
         const int64_t place = __shfl(next, src, 64) + rank;
         const int64_t shift = __shfl(to_send, src, 64);
         if (d >= 0) {
@@ -331,9 +346,16 @@ int bls_launch_plan(bls_ctx *ctx, const int64_t *idx, const int64_t *off, int64_
     const uint32_t B = (uint32_t)ctx->B;
     const bool rowwise = ctx->part_kind == BLS_ROW_WISE;
 
+    // lanes per bag for row-wise partitions: at least P (lane o keeps owner o's counters)
+    const int rg = ctx->P <= 8 ? 8 : ctx->P <= 16 ? 16 : ctx->P <= 32 ? 32 : 64;
+    const dim3 rgrid((B + kThreads / rg - 1) / (kThreads / rg), ctx->T);
     if (rowwise) {
-        dim3 grid((B + kThreads / 64 - 1) / (kThreads / 64), ctx->T);
-        plan_count_rowwise<<<grid, kThreads, 0, st>>>(dd, idx, off, nnz, segoff + 1);
+        switch (rg) {
+        case 8: plan_count_rowwise<8><<<rgrid, kThreads, 0, st>>>(dd, idx, off, nnz, segoff + 1); break;
+        case 16: plan_count_rowwise<16><<<rgrid, kThreads, 0, st>>>(dd, idx, off, nnz, segoff + 1); break;
+        case 32: plan_count_rowwise<32><<<rgrid, kThreads, 0, st>>>(dd, idx, off, nnz, segoff + 1); break;
+        default: plan_count_rowwise<64><<<rgrid, kThreads, 0, st>>>(dd, idx, off, nnz, segoff + 1); break;
+        }
     } else {
         dim3 grid((B + kThreads - 1) / kThreads, ctx->Q);
         plan_count_tablewise<<<grid, kThreads, 0, st>>>(dd, off, nnz, segoff + 1);
@@ -344,8 +366,12 @@ int bls_launch_plan(bls_ctx *ctx, const int64_t *idx, const int64_t *off, int64_
     plan_finish<<<1, kThreads, 0, st>>>(dd, segoff, sendcounts, sdispls, recvcounts, rdispls, sabs, rabs);
     if (nnz > 0) {
         if (rowwise) {
-            dim3 grid((B + kThreads / 64 - 1) / (kThreads / 64), ctx->T);
-            plan_scatter_rowwise<<<grid, kThreads, 0, st>>>(dd, idx, off, nnz, segoff, ridx, perm, sabs, rabs);
+            switch (rg) {
+            case 8: plan_scatter_rowwise<8><<<rgrid, kThreads, 0, st>>>(dd, idx, off, nnz, segoff, ridx, perm, sabs, rabs); break;
+            case 16: plan_scatter_rowwise<16><<<rgrid, kThreads, 0, st>>>(dd, idx, off, nnz, segoff, ridx, perm, sabs, rabs); break;
+            case 32: plan_scatter_rowwise<32><<<rgrid, kThreads, 0, st>>>(dd, idx, off, nnz, segoff, ridx, perm, sabs, rabs); break;
+            default: plan_scatter_rowwise<64><<<rgrid, kThreads, 0, st>>>(dd, idx, off, nnz, segoff, ridx, perm, sabs, rabs); break;
+            }
         } else {
             const int64_t runs = (int64_t)ctx->Q * ctx->P;
             const int64_t per_run = nnz / runs + 1;
