@@ -172,14 +172,23 @@ __global__ __launch_bounds__(kThreads) void pool_rows(DevDesc dd, const int64_t 
 template <int G, int DT, int VB, int U>
 __global__ __launch_bounds__(kThreads) void pool_stream(DevDesc dd, const int64_t *__restrict__ ridx,
                                                         const int64_t *__restrict__ segoff, int64_t nnz,
-                                                        float *__restrict__ Y, int to_slot, int nb_max, uint32_t chunks_per_s)
+                                                        float *__restrict__ Y, int to_slot, int nb_max, uint32_t chunks_per_s, uint32_t wgx)
 {
     using A = Acc<DT, VB>;
-    const int q = blockIdx.y;
+    // wgx = 0: grid y = q.  Otherwise a flat grid dealt out so that the workgroups an XCD receives
+    // (every eighth one) all belong to the same few tables: q = 8 * (round of tables) + XCD.
+    uint32_t bx = blockIdx.x;
+    int q = blockIdx.y;
+    if (wgx) {
+        const uint32_t xcd = blockIdx.x & 7u, r = blockIdx.x >> 3;
+        q = (int)((r / wgx) * 8u + xcd);
+        bx = r % wgx;
+        if (q >= dd.Q) return;
+    }
     const int lane = threadIdx.x & 63;
     const int li = lane & (G - 1);
     const int gbase = lane & ~(G - 1);
-    const uint32_t gx = blockIdx.x * (kThreads / G) + threadIdx.x / G;
+    const uint32_t gx = bx * (kThreads / G) + threadIdx.x / G;
     const uint32_t s = gx / chunks_per_s;
     const uint32_t chunk = gx - s * chunks_per_s;
     const uint32_t row_bytes = (uint32_t)dd.D * (DT == BLS_FP16 ? 2u : 4u);
@@ -328,8 +337,13 @@ void launch_rows(const bls_ctx *ctx, const int64_t *ridx, const int64_t *segoff,
         const int64_t n_max = ctx->B / ctx->P + (ctx->B % ctx->P ? 1 : 0);
         const uint32_t chunks = (uint32_t)((n_max + nb - 1) / nb);
         const int64_t groups = (int64_t)chunks * ctx->P;
-        dim3 grid((unsigned)((groups + per_block - 1) / per_block), ctx->Q);
-        pool_stream<G, DT, VB, UU><<<grid, kThreads, 0, st>>>(ctx->desc, ridx, segoff, nnz, Y, to_slot, nb, chunks);
+        const uint32_t wgx = (uint32_t)((groups + per_block - 1) / per_block);
+        if (env_int("BLS_POOL_XCD", 1)) {
+            const uint64_t flat = (uint64_t)((ctx->Q + 7) / 8) * 8u * wgx;
+            pool_stream<G, DT, VB, UU><<<dim3((unsigned)flat), kThreads, 0, st>>>(ctx->desc, ridx, segoff, nnz, Y, to_slot, nb, chunks, wgx);
+        } else {
+            pool_stream<G, DT, VB, UU><<<dim3(wgx, ctx->Q), kThreads, 0, st>>>(ctx->desc, ridx, segoff, nnz, Y, to_slot, nb, chunks, 0u);
+        }
     } else {
         dim3 grid((unsigned)((ctx->B + per_block - 1) / per_block), ctx->Q);
         pool_rows<G, DT, VB, UU><<<grid, kThreads, 0, st>>>(ctx->desc, ridx, segoff, nnz, Y, to_slot);

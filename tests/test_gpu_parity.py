@@ -236,12 +236,14 @@ def test_host_side_argument_errors():
     assert e.value.code == B.BLS_EINVAL
 
 
-@pytest.mark.parametrize("vb,unroll,nb", [(16, 8, 1), (16, 4, 3), (16, 16, 16), (8, 8, 0), (8, 4, 7), (4, 8, 0), (4, 16, 2)])
-def test_pool_launch_variants(vb, unroll, nb, monkeypatch):
+@pytest.mark.parametrize("vb,unroll,nb,xcd", [(16, 8, 1, 0), (16, 4, 3, 1), (16, 16, 16, 0), (8, 8, 0, 1), (8, 4, 7, 0),
+                                              (4, 8, 0, 0), (4, 16, 2, 1)])
+def test_pool_launch_variants(vb, unroll, nb, xcd, monkeypatch):
     """The tuning overrides pick other lane widths, unroll depths and segments per group;
     every variant must give the same bits."""
     monkeypatch.setenv("BLS_POOL_VB", str(vb))
     monkeypatch.setenv("BLS_POOL_U", str(unroll))
+    monkeypatch.setenv("BLS_POOL_XCD", str(xcd))
     if nb:
         monkeypatch.setenv("BLS_POOL_NB", str(nb))
     works = [synth.workload(c, "small") for c in (3, 4, 5)]
