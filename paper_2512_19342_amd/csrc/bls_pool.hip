@@ -17,6 +17,7 @@
 // the lengths of the streams that share a wavefront.
 #include <algorithm>
 #include <cstdlib>
+#include <type_traits>
 
 #include "bls_internal.h"
 
@@ -24,7 +25,6 @@ namespace {
 
 constexpr int kThreads = 256;
 constexpr uint32_t kBadRow = 0xffffffffu;
-constexpr uint64_t kNoRow = ~0ull;
 
 __device__ __forceinline__ void flag_error(const DevDesc &dd) { atomicOr(dd.err, 1); }
 
@@ -95,6 +95,13 @@ template <int DT, int VB> struct Acc {
 // 64-bit value of lane (gbase + k), k uniform.  A whole-wavefront group reads it into scalar
 // registers; narrower groups use the lane permute network (two ds_bpermute, no vector ALU
 // work beyond the address), which pipelines when several are issued back to back.
+template <int G>
+__device__ __forceinline__ uint32_t group_broadcast32(uint32_t v, int gbase4, int k)
+{
+    if constexpr (G == 64) return (uint32_t)__builtin_amdgcn_readlane((int)v, k);
+    else return (uint32_t)__builtin_amdgcn_ds_bpermute(gbase4 + 4 * k, (int)v);
+}
+
 template <int G>
 __device__ __forceinline__ uint64_t group_broadcast64(uint64_t v, int gbase4, int k)
 {
@@ -169,7 +176,9 @@ __global__ __launch_bounds__(kThreads) void pool_rows(DevDesc dd, const int64_t 
 
 // G >= 4 lanes stream up to nb_max (< G) consecutive segments of one (q, s) block.
 // grid: x over groups (s-major, then chunks of nb_max samples), y = q.
-template <int G, int DT, int VB, int U>
+// WIDE: row positions as 64-bit byte offsets; otherwise 32-bit, in units of VB bytes (shards
+// below 2^32 * VB bytes), which halves the lane exchanges and the registers they occupy.
+template <int G, int DT, int VB, int U, bool WIDE>
 __global__ __launch_bounds__(kThreads) void pool_stream(DevDesc dd, const int64_t *__restrict__ ridx,
                                                         const int64_t *__restrict__ segoff, int64_t nnz,
                                                         float *__restrict__ Y, int to_slot, int nb_max, uint32_t chunks_per_s, uint32_t wgx)
@@ -244,39 +253,49 @@ __global__ __launch_bounds__(kThreads) void pool_stream(DevDesc dd, const int64_
     };
     flush();
 
-    // this lane's row of block c0 as a byte offset into the shard (kNoRow: none or out of range)
-    auto fetch = [&](int c0) -> uint64_t {
-        uint64_t m = kNoRow;
+    // this lane's row of block c0 as a position in the shard (all ones: none or out of range)
+    using pos_t = typename std::conditional<WIDE, uint64_t, uint32_t>::type;
+    constexpr pos_t kNone = (pos_t)~(pos_t)0;
+    const uint32_t row_units = WIDE ? row_bytes : row_bytes / VB;
+    auto fetch = [&](int c0) -> pos_t {
+        pos_t m = kNone;
         if (c0 + li < total) {
             const int64_t r = ridx[beg + c0 + li];
             if (r < 0 || r >= shard_rows) flag_error(dd);
-            else m = (uint64_t)r * row_bytes;
+            else m = (pos_t)((pos_t)r * row_units);
         }
         return m;
     };
-    uint64_t mine = fetch(0);
+    auto is_row = [&](pos_t p) -> bool {
+        if constexpr (WIDE) return (uint32_t)(p >> 32) != 0xffffffffu;
+        else return p != kNone;
+    };
+    pos_t mine = fetch(0);
     typename A::Raw v[U];
 #pragma unroll
     for (int u = 0; u < U; ++u) v[u] = A::none();
     for (int c0 = 0; __any(c0 < total); c0 += G) {
-        const uint64_t ahead = fetch(c0 + G);                // next block of row numbers, in flight
+        const pos_t ahead = fetch(c0 + G);                   // next block of row numbers, in flight
         const int left = total - c0;
         const int rem = left < 0 ? 0 : (left > G ? G : left);
         for (int j = 0; __any(j < rem); j += U) {
-            uint64_t off[U];
+            pos_t off[U];
 #pragma unroll
-            for (int u = 0; u < U; ++u) off[u] = group_broadcast64<G>(mine, gbase * 4, j + u);
+            for (int u = 0; u < U; ++u) {
+                if constexpr (WIDE) off[u] = group_broadcast64<G>(mine, gbase * 4, j + u);
+                else off[u] = group_broadcast32<G>(mine, gbase * 4, j + u);
+            }
             // lanes without a row keep stale registers and skip the add: nothing to clear
 #pragma unroll
             for (int u = 0; u < U; ++u)
-                if ((uint32_t)(off[u] >> 32) != 0xffffffffu) v[u] = A::load(base + off[u]);
+                if (is_row(off[u])) v[u] = A::load(base + (WIDE ? (uint64_t)off[u] : (uint64_t)off[u] * VB));
             // every load of the batch has landed before the first add: said once, here, so that
             // no wait is placed between the conditional loads of the next batch
             __builtin_amdgcn_s_waitcnt(0x0f70);              // vmcnt(0)
             const int at = c0 + j;                           // stream position of the batch (uniform)
 #pragma unroll
             for (int u = 0; u < U; ++u) {
-                if ((uint32_t)(off[u] >> 32) != 0xffffffffu) acc.add(v[u]);
+                if (is_row(off[u])) acc.add(v[u]);
                 pos = at + u + 1 < total ? at + u + 1 : total;
                 flush();
             }
@@ -338,12 +357,15 @@ void launch_rows(const bls_ctx *ctx, const int64_t *ridx, const int64_t *segoff,
         const uint32_t chunks = (uint32_t)((n_max + nb - 1) / nb);
         const int64_t groups = (int64_t)chunks * ctx->P;
         const uint32_t wgx = (uint32_t)((groups + per_block - 1) / per_block);
-        if (env_int("BLS_POOL_XCD", 1)) {
-            const uint64_t flat = (uint64_t)((ctx->Q + 7) / 8) * 8u * wgx;
-            pool_stream<G, DT, VB, UU><<<dim3((unsigned)flat), kThreads, 0, st>>>(ctx->desc, ridx, segoff, nnz, Y, to_slot, nb, chunks, wgx);
-        } else {
-            pool_stream<G, DT, VB, UU><<<dim3(wgx, ctx->Q), kThreads, 0, st>>>(ctx->desc, ridx, segoff, nnz, Y, to_slot, nb, chunks, 0u);
-        }
+        const bool xcd = env_int("BLS_POOL_XCD", 1) != 0;
+        const dim3 grid = xcd ? dim3((unsigned)((uint64_t)((ctx->Q + 7) / 8) * 8u * wgx)) : dim3(wgx, ctx->Q);
+        const uint32_t deal = xcd ? wgx : 0u;
+        // 32-bit row positions unless some shard is too large for them
+        const int64_t row_bytes = (int64_t)ctx->D * (DT == BLS_FP16 ? 2 : 4);
+        bool wide = env_int("BLS_POOL_WIDE", 0) != 0;
+        for (int q = 0; q < ctx->Q; ++q) wide = wide || ctx->q_rows[q] * (row_bytes / VB) >= 0xffffffffLL;
+        if (wide) pool_stream<G, DT, VB, UU, true><<<grid, kThreads, 0, st>>>(ctx->desc, ridx, segoff, nnz, Y, to_slot, nb, chunks, deal);
+        else pool_stream<G, DT, VB, UU, false><<<grid, kThreads, 0, st>>>(ctx->desc, ridx, segoff, nnz, Y, to_slot, nb, chunks, deal);
     } else {
         dim3 grid((unsigned)((ctx->B + per_block - 1) / per_block), ctx->Q);
         pool_rows<G, DT, VB, UU><<<grid, kThreads, 0, st>>>(ctx->desc, ridx, segoff, nnz, Y, to_slot);

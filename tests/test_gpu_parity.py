@@ -244,6 +244,7 @@ def test_pool_launch_variants(vb, unroll, nb, xcd, monkeypatch):
     monkeypatch.setenv("BLS_POOL_VB", str(vb))
     monkeypatch.setenv("BLS_POOL_U", str(unroll))
     monkeypatch.setenv("BLS_POOL_XCD", str(xcd))
+    monkeypatch.setenv("BLS_POOL_WIDE", str(1 - xcd))
     if nb:
         monkeypatch.setenv("BLS_POOL_NB", str(nb))
     works = [synth.workload(c, "small") for c in (3, 4, 5)]
