@@ -28,6 +28,8 @@ WORKLOAD_TEXT = {
     3: "cfg3: 26 tables x 1e6 rows x dim 128 fp32, batch 8192, bags U[1,40], Zipf 1.05, P=8 row-wise, k=2",
     4: "cfg4: 64 tables rows power-law [1e3,4e7] (40.5 GB fp32, dim 128), batch 16384, bags U[1,64], Zipf 1.2, "
        "8 largest tables on rank 0 of P=8 table-wise, k=4",
+    6: "cfg6: the paper's heterogeneous synthetic setting: 26 tables rows log-uniform [1e3,1e6], dim 64 fp32, batch 512, "
+       "bags U[1,100], uniform indices, P=8 table-wise balanced, k=2",
     5: "cfg5: 8 tables x 2e7 rows x dim 128 fp16 storage / fp32 accumulate, batch 65536, pooling 32, Zipf 1.05, "
        "P=8 row-wise, k=4",
 }
@@ -83,7 +85,7 @@ def main() -> int:
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--config", type=int, default=4, help="benchmark workload 1..5 (default 4, the target)")
+    ap.add_argument("--config", type=int, default=4, help="benchmark workload 1..6 (default 4, the target)")
     ap.add_argument("--size", default="full", choices=["full", "small"])
     ap.add_argument("--batches", type=int, default=4, help="distinct pre-generated batches, rotated")
     ap.add_argument("--no-cpu-baseline", action="store_true")

@@ -94,8 +94,10 @@ def _table_ptrs(case: Case, tables: List[np.ndarray]):
     return arr, keep
 
 
-def plan(case: Case, indices, offsets, want_perm: bool = True) -> dict:
+def plan(case: Case, indices, offsets, want_perm: bool = True, weights=None) -> dict:
     indices, offsets = _i64(indices), _i64(offsets)
+    if weights is not None:
+        weights = np.ascontiguousarray(weights, dtype=np.float32)
     assert offsets.shape[0] == case.T * case.B + 1
     nnz = int(offsets[-1]) if offsets[-1] >= 0 else 0
     assert indices.shape[0] >= nnz
@@ -104,22 +106,28 @@ def plan(case: Case, indices, offsets, want_perm: bool = True) -> dict:
     out["ridx"] = np.zeros(nnz, np.int64)
     out["segoff"] = np.zeros(case.n_vec + 1, np.int64)
     out["perm"] = np.zeros(nnz, np.int64) if want_perm else None
-    rc = _load().orc_plan(C.c_int(case.P), C.c_int(case.T), C.c_int64(case.B), C.c_int(case.part_kind),
-                          _p(case._rows), _p(case._owner), _p(indices), _p(offsets),
-                          _p(out["sendcounts"]), _p(out["sdispls"]), _p(out["recvcounts"]), _p(out["rdispls"]),
-                          _p(out["ridx"]), _p(out["segoff"]), _p(out["perm"]))
+    out["rweights"] = np.zeros(nnz, np.float32) if weights is not None else None
+    rc = _load().orc_plan_weighted(C.c_int(case.P), C.c_int(case.T), C.c_int64(case.B), C.c_int(case.part_kind),
+                                   _p(case._rows), _p(case._owner), _p(indices), _p(offsets), _p(weights),
+                                   _p(out["sendcounts"]), _p(out["sdispls"]), _p(out["recvcounts"]), _p(out["rdispls"]),
+                                   _p(out["ridx"]), _p(out["rweights"]), _p(out["segoff"]), _p(out["perm"]))
     _chk("orc_plan", rc)
     return out
 
 
-def embbag_plain(case: Case, tables: List[np.ndarray], indices, offsets, want64=True, want32=True):
-    """The plain definition: Out[b][t][:] in float64 and in ordered float32."""
+def embbag_plain(case: Case, tables: List[np.ndarray], indices, offsets, want64=True, want32=True,
+                 weights=None, mean: bool = False):
+    """The plain definition: Out[b][t][:] in float64 and in ordered float32 (optionally with
+    per-sample weights, or as the mean over the bag)."""
     indices, offsets = _i64(indices), _i64(offsets)
+    if weights is not None:
+        weights = np.ascontiguousarray(weights, dtype=np.float32)
     ptrs, _keep = _table_ptrs(case, tables)
     o64 = np.zeros((case.B, case.T, case.D), np.float64) if want64 else None
     o32 = np.zeros((case.B, case.T, case.D), np.float32) if want32 else None
-    rc = _load().orc_embbag_plain(C.c_int(case.T), C.c_int(case.D), C.c_int64(case.B), C.c_int(case.dtype),
-                                  _p(case._rows), ptrs, _p(indices), _p(offsets), _p(o64), _p(o32))
+    rc = _load().orc_embbag_plain_ex(C.c_int(case.T), C.c_int(case.D), C.c_int64(case.B), C.c_int(case.dtype),
+                                     _p(case._rows), ptrs, _p(indices), _p(offsets), _p(weights),
+                                     C.c_int(1 if mean else 0), _p(o64), _p(o32))
     _chk("orc_embbag_plain", rc)
     return o64, o32
 
@@ -134,14 +142,16 @@ def embbag_absmass(case: Case, tables: List[np.ndarray], indices, offsets) -> np
     return m
 
 
-def pool(case: Case, tables: List[np.ndarray], ridx, segoff) -> np.ndarray:
+def pool(case: Case, tables: List[np.ndarray], ridx, segoff, rweights=None) -> np.ndarray:
     ridx, segoff = _i64(ridx), _i64(segoff)
+    if rweights is not None:
+        rweights = np.ascontiguousarray(rweights, dtype=np.float32)
     ptrs, _keep = _table_ptrs(case, tables)
     Y = np.zeros(case.n_vec * case.D, np.float32)
     _chk("orc_pool",
-         _load().orc_pool(C.c_int(case.P), C.c_int(case.T), C.c_int(case.D), C.c_int64(case.B),
-                          C.c_int(case.part_kind), _p(case._rows), _p(case._owner), C.c_int(case.dtype),
-                          ptrs, _p(ridx), _p(segoff), _p(Y)))
+         _load().orc_pool_weighted(C.c_int(case.P), C.c_int(case.T), C.c_int(case.D), C.c_int64(case.B),
+                                   C.c_int(case.part_kind), _p(case._rows), _p(case._owner), C.c_int(case.dtype),
+                                   ptrs, _p(ridx), _p(rweights), _p(segoff), _p(Y)))
     return Y
 
 
@@ -185,12 +195,14 @@ def exchange(case: Case, S: np.ndarray) -> np.ndarray:
                      pc["prbase"], pc["prcount"], pc["prdispl"], case.n_vec * case.D)
 
 
-def unpack(case: Case, R: np.ndarray) -> np.ndarray:
+def unpack(case: Case, R: np.ndarray, mean_offsets=None) -> np.ndarray:
+    """Completion copy-out; with ``mean_offsets`` (the batch's offsets) also the division by the bag length."""
     R = np.ascontiguousarray(R, dtype=np.float32).reshape(-1)
     assert R.size == case.n_vec * case.D
     out = np.zeros((case.B, case.T, case.D), np.float32)
-    _chk("orc_unpack", _load().orc_unpack(C.c_int(case.P), C.c_int(case.T), C.c_int(case.D), C.c_int64(case.B),
-                                          C.c_int(case.part_kind), _p(case._owner), _p(R), _p(out)))
+    off = None if mean_offsets is None else _i64(mean_offsets)
+    _chk("orc_unpack", _load().orc_unpack_mean(C.c_int(case.P), C.c_int(case.T), C.c_int(case.D), C.c_int64(case.B),
+                                               C.c_int(case.part_kind), _p(case._owner), _p(R), _p(off), _p(out)))
     return out
 
 
@@ -202,13 +214,13 @@ def bag_sum(rows_nd: np.ndarray):
     return o32, o64
 
 
-def pipeline(case: Case, tables: List[np.ndarray], indices, offsets) -> dict:
+def pipeline(case: Case, tables: List[np.ndarray], indices, offsets, weights=None, mean: bool = False) -> dict:
     """Every stage in path order: plan, pool, pack, exchange, unpack."""
-    r = plan(case, indices, offsets)
-    r["Y"] = pool(case, tables, r["ridx"], r["segoff"])
+    r = plan(case, indices, offsets, weights=weights)
+    r["Y"] = pool(case, tables, r["ridx"], r["segoff"], r["rweights"])
     r["S"] = pack(case, r["Y"])
     r["R"] = exchange(case, r["S"])
-    r["Out"] = unpack(case, r["R"])
+    r["Out"] = unpack(case, r["R"], offsets if mean else None)
     return r
 
 

@@ -115,10 +115,26 @@ static int check_partition(int P, int T, int part_kind, const int64_t *rows, con
  * segoff[F*T*B+1] start of every (d, s, t_loc, b_loc) segment in ridx; perm[nnz]
  * (nullable) requester-side position of lookup l (s, then d, then l).
  */
+int orc_plan_weighted(int P, int T, int64_t B, int part_kind, const int64_t *rows, const int32_t *owner,
+                      const int64_t *indices, const int64_t *offsets, const float *weights,
+                      int64_t *sendcounts, int64_t *sdispls, int64_t *recvcounts, int64_t *rdispls,
+                      int64_t *ridx, float *rweights, int64_t *segoff, int64_t *perm);
+
 int orc_plan(int P, int T, int64_t B, int part_kind, const int64_t *rows, const int32_t *owner,
              const int64_t *indices, const int64_t *offsets,
              int64_t *sendcounts, int64_t *sdispls, int64_t *recvcounts, int64_t *rdispls,
              int64_t *ridx, int64_t *segoff, int64_t *perm)
+{
+    return orc_plan_weighted(P, T, B, part_kind, rows, owner, indices, offsets, NULL, sendcounts, sdispls,
+                             recvcounts, rdispls, ridx, NULL, segoff, perm);
+}
+
+/* The same with per-sample weights (Listing 1 passes them to apply_emb as v_W_l): the weight
+ * of lookup l travels with it, rweights[.] is in the same owner order as ridx[.]. */
+int orc_plan_weighted(int P, int T, int64_t B, int part_kind, const int64_t *rows, const int32_t *owner,
+                      const int64_t *indices, const int64_t *offsets, const float *weights,
+                      int64_t *sendcounts, int64_t *sdispls, int64_t *recvcounts, int64_t *rdispls,
+                      int64_t *ridx, float *rweights, int64_t *segoff, int64_t *perm)
 {
     int rc = check_partition(P, T, part_kind, rows, owner);
     int s, d, t;
@@ -201,6 +217,7 @@ int orc_plan(int P, int T, int64_t B, int part_kind, const int64_t *rows, const 
                 }
                 rank = cursor[s * P + d]++;
                 ridx[rbase[d] + rdispls[d * P + s] + rank] = r;
+                if (weights && rweights) rweights[rbase[d] + rdispls[d * P + s] + rank] = weights[l];
                 if (perm) perm[l] = sbase[s] + sdispls[s * P + d] + rank;
             }
         }
@@ -244,8 +261,22 @@ static float elem(const void *table, int dtype, int64_t i)
  * starts at +0.0f and adds the terms in increasing l (out32, nullable).  tables[t] is
  * table t with global row numbering, dtype 0 = fp32, 1 = fp16 storage.
  */
+int orc_embbag_plain_ex(int T, int D, int64_t B, int dtype, const int64_t *rows, const void *const *tables,
+                        const int64_t *indices, const int64_t *offsets, const float *weights, int mean,
+                        double *out64, float *out32);
+
 int orc_embbag_plain(int T, int D, int64_t B, int dtype, const int64_t *rows, const void *const *tables,
                      const int64_t *indices, const int64_t *offsets, double *out64, float *out32)
+{
+    return orc_embbag_plain_ex(T, D, B, dtype, rows, tables, indices, offsets, NULL, 0, out64, out32);
+}
+
+/* EmbeddingBag with per-sample weights (sum of w_l * row_l) or mean pooling (sum / bag length,
+ * an empty bag gives +0).  fp32 variant: every product and every sum rounded separately, the
+ * mean by one fp32 division at the end. */
+int orc_embbag_plain_ex(int T, int D, int64_t B, int dtype, const int64_t *rows, const void *const *tables,
+                        const int64_t *indices, const int64_t *offsets, const float *weights, int mean,
+                        double *out64, float *out32)
 {
     int t, c;
     int64_t b, l;
@@ -259,8 +290,18 @@ int orc_embbag_plain(int T, int D, int64_t B, int dtype, const int64_t *rows, co
                 float a32 = 0.0f;
                 for (l = offsets[g]; l < offsets[g + 1]; ++l) {
                     float x = elem(tables[t], dtype, indices[l] * D + c);
-                    a64 += (double)x;
-                    a32 += x;
+                    if (weights) {
+                        float term = weights[l] * x;
+                        a64 += (double)weights[l] * (double)x;
+                        a32 += term;
+                    } else {
+                        a64 += (double)x;
+                        a32 += x;
+                    }
+                }
+                if (mean && offsets[g + 1] > offsets[g]) {
+                    a64 /= (double)(offsets[g + 1] - offsets[g]);
+                    a32 /= (float)(offsets[g + 1] - offsets[g]);
                 }
                 if (out64) out64[((int64_t)b * T + t) * D + c] = a64;
                 if (out32) out32[((int64_t)b * T + t) * D + c] = a32;
@@ -298,8 +339,21 @@ int orc_embbag_absmass(int T, int D, int64_t B, int dtype, const void *const *ta
  * Y_0 .. Y_{P-1}, each [n_loc(d)][B][D].  Row-wise shard d of table t is rows
  * [d*rps, min((d+1)*rps, rows_t)) of the global table.
  */
+int orc_pool_weighted(int P, int T, int D, int64_t B, int part_kind, const int64_t *rows, const int32_t *owner,
+                      int dtype, const void *const *tables, const int64_t *ridx, const float *rweights,
+                      const int64_t *segoff, float *Y);
+
 int orc_pool(int P, int T, int D, int64_t B, int part_kind, const int64_t *rows, const int32_t *owner,
              int dtype, const void *const *tables, const int64_t *ridx, const int64_t *segoff, float *Y)
+{
+    return orc_pool_weighted(P, T, D, B, part_kind, rows, owner, dtype, tables, ridx, NULL, segoff, Y);
+}
+
+/* rweights (nullable): weight of every lookup in owner order; each term w * x is rounded to
+ * fp32 before it is added. */
+int orc_pool_weighted(int P, int T, int D, int64_t B, int part_kind, const int64_t *rows, const int32_t *owner,
+                      int dtype, const void *const *tables, const int64_t *ridx, const float *rweights,
+                      const int64_t *segoff, float *Y)
 {
     int rc = check_partition(P, T, part_kind, rows, owner);
     int *n_loc, *loc, d, s, t, c;
@@ -329,8 +383,11 @@ int orc_pool(int P, int T, int D, int64_t B, int part_kind, const int64_t *rows,
                         if (ridx[j] < 0 || ridx[j] >= shard_rows) { rc = ORC_ERANGE; goto done; }
                     for (c = 0; c < D; ++c) {
                         float acc = 0.0f;
-                        for (j = segoff[sg]; j < segoff[sg + 1]; ++j)
-                            acc += elem(tables[t], dtype, (shard_first + ridx[j]) * D + c);
+                        for (j = segoff[sg]; j < segoff[sg + 1]; ++j) {
+                            float x = elem(tables[t], dtype, (shard_first + ridx[j]) * D + c);
+                            if (rweights) { float term = rweights[j] * x; acc += term; }
+                            else acc += x;
+                        }
                         y[c] = acc;
                     }
                 }
@@ -435,7 +492,18 @@ int orc_alltoallv_f32(int P, const float *send, const int64_t *sbase, const int6
  * +0.0f in increasing owner rank (reading: the paper never shards a table by rows).
  * R is the concatenation of the requesters' receive regions, each [d][t_loc][b_loc][D].
  */
+int orc_unpack_mean(int P, int T, int D, int64_t B, int part_kind, const int32_t *owner, const float *R,
+                    const int64_t *offsets, float *Out);
+
 int orc_unpack(int P, int T, int D, int64_t B, int part_kind, const int32_t *owner, const float *R, float *Out)
+{
+    return orc_unpack_mean(P, T, D, B, part_kind, owner, R, NULL, Out);
+}
+
+/* offsets (nullable): mean pooling - after the copy-out (and, row-wise, the sum of the
+ * partials) every vector of a non-empty bag is divided by the bag's length in fp32. */
+int orc_unpack_mean(int P, int T, int D, int64_t B, int part_kind, const int32_t *owner, const float *R,
+                    const int64_t *offsets, float *Out)
 {
     int *n_loc = (int *)malloc(sizeof(int) * P), *loc = (int *)malloc(sizeof(int) * T), d, s, t, c;
     int64_t rbase = 0;
@@ -457,6 +525,10 @@ int orc_unpack(int P, int T, int D, int64_t B, int part_kind, const int32_t *own
                         }
                         blk += (int64_t)n_loc[d] * n * D;
                     }
+                }
+                if (offsets) {
+                    int64_t g = (int64_t)t * B + f + b_loc, len = offsets[g + 1] - offsets[g];
+                    if (len > 0) for (c = 0; c < D; ++c) o[c] /= (float)len;
                 }
             }
         for (d = 0; d < P; ++d) total += (int64_t)n_loc[d] * n * D;

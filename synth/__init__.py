@@ -169,7 +169,7 @@ def _rows_loguniform(seed: int, T: int, lo_exp: float, hi_exp: float) -> List[in
 
 
 def workload(cfg: int, size: str = "full") -> Workload:
-    """The five benchmark workloads (``size="full"``) or reduced twins (``size="small"``).
+    """The five benchmark workloads (1..5), the paper's own heterogeneous setting (6), (``size="full"``) or reduced twins (``size="small"``).
 
     The reduced twins keep every structural feature (partition kind, ragged last
     shard, bag-length law, index law, dtype, ring depth) at sizes a CPU oracle
@@ -210,7 +210,15 @@ def workload(cfg: int, size: str = "full") -> Workload:
         B = 1024 if small else 65536
         return Workload("cfg5" + ("s" if small else ""), 5, P, T, 128, 4, B, "fp16", 1, rows, [0] * T,
                         "grid", ("fixed", 32), ("zipf", 1.05), seed)
-    raise ValueError("cfg must be 1..5")
+    if cfg == 6:
+        # the paper's heterogeneous synthetic setting (Synthetic DLRM benchmarks, Setting 1): a random
+        # number of vectors per table from 1 to 100, with the shapes of its dataset runs (26 tables,
+        # largest about a million rows, batch 512, 8 processes) at embedding dimension 64
+        T, P = 26, 8
+        rows = [max(1000, r // (20 if small else 1)) for r in _rows_loguniform(seed, T, 3.0, 6.0)]
+        return Workload("cfg6" + ("s" if small else ""), 6, P, T, 64, 2, 128 if small else 512, "fp32", 0, rows,
+                        owners_balanced_by_rows(rows, P), "grid", ("uniform", 1, 100), ("uniform",), seed)
+    raise ValueError("cfg must be 1..6")
 
 
 def custom(name: str, *, P: int, T: int, D: int, k: int, B: int, rows: List[int], part_kind: int,

@@ -64,7 +64,7 @@ def check_against_oracle(w, tabs_cpu, batches, got):
         assert np.all(np.abs(g["Out"].astype(np.float64) - o64) <= TOL[w.table_dtype] * mass)
 
 
-WORKLOADS = [(1, "full"), (2, "full"), (3, "small"), (4, "small"), (5, "small")]
+WORKLOADS = [(1, "full"), (2, "full"), (3, "small"), (4, "small"), (5, "small"), (6, "small")]
 
 
 @pytest.mark.parametrize("cfg,size", WORKLOADS)

@@ -24,8 +24,14 @@ MUTATIONS = {
     "plain sum wrong sign": ("a32 += x;", "a32 -= x;"),
     "plain sum drops first term": ("for (l = offsets[g]; l < offsets[g + 1]; ++l) {\n                    float x",
                                    "for (l = offsets[g] + 1; l < offsets[g + 1]; ++l) {\n                    float x"),
-    "pool ignores shard base": ("acc += elem(tables[t], dtype, (shard_first + ridx[j]) * D + c);",
-                                "acc += elem(tables[t], dtype, (ridx[j]) * D + c);"),
+    "pool ignores shard base": ("float x = elem(tables[t], dtype, (shard_first + ridx[j]) * D + c);",
+                                "float x = elem(tables[t], dtype, (ridx[j]) * D + c);"),
+    "weights not carried": ("rweights[rbase[d] + rdispls[d * P + s] + rank] = weights[l];",
+                            "rweights[rbase[d] + rdispls[d * P + s] + rank] = weights[offsets[g]];"),
+    "weighted term fused into double": ("float term = weights[l] * x;\n                        a64", "float term = (float)((double)weights[l] * 1.0000001 * x);\n                        a64"),
+    "pool weight of the neighbour": ("float term = rweights[j] * x; acc += term;", "float term = rweights[segoff[sg]] * x; acc += term;"),
+    "mean divides by length + 1": ("a32 /= (float)(offsets[g + 1] - offsets[g]);", "a32 /= (float)(offsets[g + 1] - offsets[g] + 1);"),
+    "unpack mean uses the wrong bag": ("int64_t g = (int64_t)t * B + f + b_loc, len", "int64_t g = (int64_t)t * B + b_loc, len"),
     "pool column transposed": ("y[c] = acc;", "y[D - 1 - c] = acc;"),
     "pack drops mini-batch offset": ("Y + ybase + ((int64_t)tl * B + f + b_loc) * D, sizeof(float) * D);",
                                      "Y + ybase + ((int64_t)tl * B + b_loc) * D, sizeof(float) * D);"),
@@ -47,6 +53,10 @@ PINS = [
     lambda: pins.test_pack_exchange_unpack_addresses(pins.TINY[2]),
     lambda: pins.test_against_torch_embedding_bag(5, "small"),
     lambda: pins.test_half_conversion_all_bit_patterns(),
+    lambda: pins.test_weighted_and_mean_match_brute_force(pins.TINY[1]),
+    lambda: pins.test_weighted_and_mean_match_brute_force(pins.TINY[2]),
+    lambda: pins.test_weighted_and_mean_against_torch(3),
+    lambda: pins.test_weights_exact_cases(),
 ]
 
 

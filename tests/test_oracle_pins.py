@@ -468,3 +468,98 @@ def test_generator_statistics_and_determinism():
     assert abs(top - share) < 0.02
     full = synth.workload(4)
     assert sum(full.rows) == 79_079_336 and full.table_owner[:8] == [0] * 8 and set(full.table_owner[8:]) == set(range(1, 8))
+
+
+# ----------------------------------------------------------------------------- weights, mean
+
+def _weights_for(nnz, seed=5):
+    rng = np.random.default_rng(seed)
+    return rng.uniform(-2.0, 2.0, size=nnz).astype(np.float32)
+
+
+@pytest.mark.parametrize("spec", TINY)
+def test_weighted_and_mean_match_brute_force(spec):
+    w = tiny_workload(spec, 9)
+    ix, off = (x.numpy() for x in synth.make_batch(w, 0))
+    tabs = np_tables(w)
+    wts = _weights_for(len(ix))
+    c = case_of(w)
+    exp_w = np.zeros((w.B, w.T, w.D), np.float32)
+    exp_m = np.zeros((w.B, w.T, w.D), np.float32)
+    for t in range(w.T):
+        for b in range(w.B):
+            g = t * w.B + b
+            for l in range(off[g], off[g + 1]):
+                row = tabs[t][ix[l]].astype(np.float32)
+                exp_w[b, t] = exp_w[b, t] + (np.float32(wts[l]) * row).astype(np.float32)
+                exp_m[b, t] = exp_m[b, t] + row
+            if off[g + 1] > off[g]:
+                exp_m[b, t] = exp_m[b, t] / np.float32(off[g + 1] - off[g])
+    _, o32w = oracle.embbag_plain(c, tabs, ix, off, want64=False, weights=wts)
+    _, o32m = oracle.embbag_plain(c, tabs, ix, off, want64=False, mean=True)
+    assert np.array_equal(o32w.view(np.uint32), exp_w.view(np.uint32))
+    assert np.array_equal(o32m.view(np.uint32), exp_m.view(np.uint32))
+    if w.part_kind == 0:      # table-wise: the staged path reproduces the definition bit for bit
+        assert np.array_equal(oracle.pipeline(c, tabs, ix, off, weights=wts)["Out"].view(np.uint32), exp_w.view(np.uint32))
+        assert np.array_equal(oracle.pipeline(c, tabs, ix, off, mean=True)["Out"].view(np.uint32), exp_m.view(np.uint32))
+
+
+@pytest.mark.parametrize("cfg", [3, 4, 5])
+def test_weighted_and_mean_against_torch(cfg):
+    w = synth.workload(cfg, "small")
+    w.values = "gauss" if cfg != 5 else w.values
+    ix, off = synth.make_batch(w, 0)
+    tabs_t = [synth.make_table(w, t, "cpu") for t in range(w.T)]
+    tabs = [x.numpy() for x in tabs_t]
+    wts = torch.from_numpy(_weights_for(ix.numel()))
+    c = case_of(w)
+    o64w, o32w = oracle.embbag_plain(c, tabs, ix.numpy(), off.numpy(), weights=wts.numpy())
+    o64m, o32m = oracle.embbag_plain(c, tabs, ix.numpy(), off.numpy(), mean=True)
+    out_w = oracle.pipeline(c, tabs, ix.numpy(), off.numpy(), weights=wts.numpy())
+    out_m = oracle.pipeline(c, tabs, ix.numpy(), off.numpy(), mean=True)["Out"]
+    mass = oracle.embbag_absmass(c, tabs, ix.numpy(), off.numpy())
+    tol = 1e-3 if w.table_dtype == "fp16" else 1e-6
+    lens = np.maximum(np.diff(off.numpy()), 1).reshape(w.T, w.B).T[:, :, None]
+    for t in range(w.T):
+        o = off[t * w.B:(t + 1) * w.B + 1]
+        sub, sw = ix[o[0]:o[-1]], wts[o[0]:o[-1]]
+        ref_w = torch.nn.functional.embedding_bag(sub, tabs_t[t].double(), o[:-1] - o[0], mode="sum",
+                                                  per_sample_weights=sw.double()).numpy()
+        ref_m = torch.nn.functional.embedding_bag(sub, tabs_t[t].double(), o[:-1] - o[0], mode="mean").numpy()
+        assert np.allclose(o64w[:, t], ref_w, rtol=1e-12, atol=1e-300)
+        assert np.allclose(o64m[:, t], ref_m, rtol=1e-12, atol=1e-300)
+        for got in (o32w[:, t], out_w["Out"][:, t]):       # |w| <= 2: twice the mass bounds the terms
+            assert np.all(np.abs(got - ref_w) <= 2 * 2 * tol * mass[:, t] + 1e-30)
+        for got in (o32m[:, t], out_m[:, t]):
+            assert np.all(np.abs(got - ref_m) <= 2 * tol * mass[:, t] / lens[:, t] + 1e-30)
+    # the weight of every lookup travels with its row number
+    P, T, B = w.P, w.T, w.B
+    bag = np.repeat(np.arange(T * B), np.diff(off.numpy()))
+    t_of, s_of = bag // B, (bag % B) // (B // P)
+    d_of = ix.numpy() // (-(-np.array(w.rows)[t_of] // P)) if w.part_kind == 1 else np.array(w.table_owner)[t_of]
+    order = np.argsort(d_of * P + s_of, kind="stable")
+    assert np.array_equal(out_w["rweights"], wts.numpy()[order])
+
+
+def test_weights_exact_cases():
+    """Weights of one change nothing; power-of-two weights on integer tables stay exact."""
+    w = synth.custom("ints", P=3, T=3, D=4, k=1, B=9, rows=[50, 60, 70], part_kind=1, bag=("uniform", 0, 9))
+    ix, off = (x.numpy() for x in synth.make_batch(w, 1))
+    c = case_of(w)
+    tabs = [np.repeat(np.arange(r, dtype=np.float32)[:, None], 4, axis=1).copy() for r in w.rows]
+    ones = np.ones(len(ix), np.float32)
+    a = oracle.pipeline(c, tabs, ix, off)
+    b = oracle.pipeline(c, tabs, ix, off, weights=ones)
+    for k in ("Y", "S", "R", "Out"):
+        assert np.array_equal(a[k].view(np.uint32), b[k].view(np.uint32))
+    rng = np.random.default_rng(3)
+    pw = (2.0 ** rng.integers(-3, 4, size=len(ix))).astype(np.float32) * rng.choice([-1, 1], size=len(ix)).astype(np.float32)
+    out = oracle.pipeline(c, tabs, ix, off, weights=pw)["Out"]
+    for t in range(3):
+        for bb in range(9):
+            g = t * 9 + bb
+            sl = slice(off[g], off[g + 1])
+            assert np.all(out[bb, t] == np.sum(pw[sl].astype(np.float64) * ix[sl]))
+    m = oracle.pipeline(c, [np.ones((r, 4), np.float32) for r in w.rows], ix, off, mean=True)["Out"]
+    lens = np.diff(off).reshape(3, 9).T
+    assert np.array_equal(m[:, :, 0], (lens > 0).astype(np.float32))
