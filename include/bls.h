@@ -159,11 +159,33 @@ int bls_alltoallv_local(bls_ctx *ctx, const float *d_send, int32_t slot, void *h
 int bls_embbag_pool_put(bls_ctx *ctx, const int64_t *d_ridx, const int64_t *d_segoff, int64_t nnz,
                         int32_t slot, void *hip_stream);
 
+/*
+ * Per-sample weights (Listing 1 hands them to apply_emb as v_W_l).  bls_plan_weighted is
+ * bls_plan that also carries the weight of every lookup along: d_weights[nnz] in input order,
+ * d_rweights[nnz] out in the order of d_ridx.  The weighted pooling calls then compute
+ *   Y_d[t_loc][b][:] = sum over the segment of  w * row,
+ * each product rounded to fp32 and then added (no fused multiply-add), otherwise exactly as
+ * bls_embbag_pool / bls_embbag_pool_put.
+ */
+int bls_plan_weighted(bls_ctx *ctx, const int64_t *d_indices, const int64_t *d_offsets, const float *d_weights,
+                      int64_t nnz, int64_t *d_sendcounts, int64_t *d_sdispls, int64_t *d_recvcounts,
+                      int64_t *d_rdispls, int64_t *d_ridx, float *d_rweights, int64_t *d_segoff, int64_t *d_perm,
+                      void *d_ws, size_t ws_bytes, void *hip_stream);
+int bls_embbag_pool_weighted(bls_ctx *ctx, const int64_t *d_ridx, const float *d_rweights, const int64_t *d_segoff,
+                             int64_t nnz, float *d_pooled, void *hip_stream);
+int bls_embbag_pool_put_weighted(bls_ctx *ctx, const int64_t *d_ridx, const float *d_rweights,
+                                 const int64_t *d_segoff, int64_t nnz, int32_t slot, void *hip_stream);
+
 /* Alltoallv completion for iteration `iter`, which must be the oldest in flight
  * (wait() completes the tail request and pops it): copy the receive regions of its
  * slot to d_out[B][T][D] fp32 and free the slot.  Table-wise: a copy.  Row-wise: the P
  * partial sums of every (b, t) are added from +0 in increasing owner rank. */
 int bls_unpack(bls_ctx *ctx, int64_t iter, float *d_out, void *hip_stream);
+
+/* Completion with mean pooling: as bls_unpack, and every vector of a non-empty bag is then
+ * divided (one fp32 division per element) by the bag's length offsets[g+1] - offsets[g];
+ * d_offsets is the iteration's offsets array, device memory. */
+int bls_unpack_mean(bls_ctx *ctx, int64_t iter, const int64_t *d_offsets, float *d_out, void *hip_stream);
 
 /* Ring state for callers and tests: next iteration number, oldest in flight, K. */
 int bls_ring_state(const bls_ctx *ctx, int64_t *head, int64_t *tail, int32_t *K);

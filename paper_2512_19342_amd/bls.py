@@ -19,9 +19,10 @@ BLS_FP32, BLS_FP16 = 0, 1
 BLS_TABLE_WISE, BLS_ROW_WISE = 0, 1
 
 EXPORTS = [
-    "bls_create", "bls_destroy", "bls_set_shard", "bls_sizes", "bls_pooled_counts", "bls_plan",
-    "bls_embbag_pool", "bls_embbag_pool_put", "bls_pack", "bls_set_ring", "bls_ring_advance", "bls_alltoallv_local",
-    "bls_unpack", "bls_ring_state", "bls_check", "bls_last_error",
+    "bls_create", "bls_destroy", "bls_set_shard", "bls_sizes", "bls_pooled_counts", "bls_plan", "bls_plan_weighted",
+    "bls_embbag_pool", "bls_embbag_pool_weighted", "bls_embbag_pool_put", "bls_embbag_pool_put_weighted", "bls_pack",
+    "bls_set_ring", "bls_ring_advance", "bls_alltoallv_local", "bls_unpack", "bls_unpack_mean", "bls_ring_state",
+    "bls_check", "bls_last_error",
 ]
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
@@ -54,7 +55,12 @@ def lib() -> C.CDLL:
         L.bls_sizes.argtypes = [vp, C.c_int64] + [C.POINTER(C.c_size_t)] * 4
         L.bls_pooled_counts.argtypes = [vp] + [C.POINTER(C.c_int64)] * 4
         L.bls_plan.argtypes = [vp, i64p, i64p, C.c_int64, i64p, i64p, i64p, i64p, i64p, i64p, i64p, vp, C.c_size_t, vp]
+        L.bls_plan_weighted.argtypes = [vp, i64p, i64p, vp, C.c_int64, i64p, i64p, i64p, i64p, i64p, vp, i64p, i64p, vp,
+                                        C.c_size_t, vp]
         L.bls_embbag_pool.argtypes = [vp, i64p, i64p, C.c_int64, vp, vp]
+        L.bls_embbag_pool_weighted.argtypes = [vp, i64p, vp, i64p, C.c_int64, vp, vp]
+        L.bls_embbag_pool_put_weighted.argtypes = [vp, i64p, vp, i64p, C.c_int64, C.c_int32, vp]
+        L.bls_unpack_mean.argtypes = [vp, C.c_int64, i64p, vp, vp]
         L.bls_embbag_pool_put.argtypes = [vp, i64p, i64p, C.c_int64, C.c_int32, vp]
         L.bls_pack.argtypes = [vp, vp, vp, vp]
         L.bls_set_ring.argtypes = [vp, vp, C.c_size_t]
@@ -157,6 +163,23 @@ class Context:
         self._call("bls_plan", _ptr(indices), _ptr(offsets), int(nnz), _ptr(sendcounts), _ptr(sdispls), _ptr(recvcounts),
                    _ptr(rdispls), _ptr(ridx), _ptr(segoff), _ptr(perm), _ptr(ws), ws.numel() * ws.element_size(),
                    _stream(stream))
+
+    def bls_plan_weighted(self, indices, offsets, weights, nnz, sendcounts, sdispls, recvcounts, rdispls, ridx, rweights,
+                          segoff, perm, ws, stream=None):
+        self._call("bls_plan_weighted", _ptr(indices), _ptr(offsets), _ptr(weights), int(nnz), _ptr(sendcounts),
+                   _ptr(sdispls), _ptr(recvcounts), _ptr(rdispls), _ptr(ridx), _ptr(rweights), _ptr(segoff), _ptr(perm),
+                   _ptr(ws), ws.numel() * ws.element_size(), _stream(stream))
+
+    def bls_embbag_pool_weighted(self, ridx, rweights, segoff, nnz, pooled, stream=None):
+        self._call("bls_embbag_pool_weighted", _ptr(ridx), _ptr(rweights), _ptr(segoff), int(nnz), _ptr(pooled),
+                   _stream(stream))
+
+    def bls_embbag_pool_put_weighted(self, ridx, rweights, segoff, nnz, slot, stream=None):
+        self._call("bls_embbag_pool_put_weighted", _ptr(ridx), _ptr(rweights), _ptr(segoff), int(nnz), int(slot),
+                   _stream(stream))
+
+    def bls_unpack_mean(self, it, offsets, out, stream=None):
+        self._call("bls_unpack_mean", int(it), _ptr(offsets), _ptr(out), _stream(stream))
 
     def bls_embbag_pool(self, ridx, segoff, nnz, pooled, stream=None):
         self._call("bls_embbag_pool", _ptr(ridx), _ptr(segoff), int(nnz), _ptr(pooled), _stream(stream))

@@ -209,11 +209,11 @@ int bls_commit(bls_ctx *ctx)
 
 // ---- entry points that launch kernels -------------------------------------------------
 
-extern "C" int bls_plan(bls_ctx *ctx, const int64_t *d_indices, const int64_t *d_offsets, int64_t nnz,
-                        int64_t *d_sendcounts, int64_t *d_sdispls, int64_t *d_recvcounts, int64_t *d_rdispls,
-                        int64_t *d_ridx, int64_t *d_segoff, int64_t *d_perm, void *d_ws, size_t ws_bytes, void *hip_stream)
+static int plan_common(bls_ctx *ctx, const int64_t *d_indices, const int64_t *d_offsets, const float *d_weights, int64_t nnz,
+                       int64_t *d_sendcounts, int64_t *d_sdispls, int64_t *d_recvcounts, int64_t *d_rdispls,
+                       int64_t *d_ridx, float *d_rweights, int64_t *d_segoff, int64_t *d_perm, void *d_ws, size_t ws_bytes,
+                       void *hip_stream)
 {
-    if (!ctx) return BLS_EINVAL;
     if (nnz < 0 || !d_offsets || !d_sendcounts || !d_sdispls || !d_recvcounts || !d_rdispls || !d_segoff || !d_ws)
         return bls_fail(ctx, BLS_EINVAL, "bls_plan: NULL argument or negative nnz");
     if (nnz > 0 && (!d_indices || !d_ridx)) return bls_fail(ctx, BLS_EINVAL, "bls_plan: NULL indices or ridx with nnz > 0");
@@ -222,18 +222,52 @@ extern "C" int bls_plan(bls_ctx *ctx, const int64_t *d_indices, const int64_t *d
     int rc = bls_commit(ctx);
     if (rc) return rc;
     return bls_launch_plan(ctx, d_indices, d_offsets, nnz, d_sendcounts, d_sdispls, d_recvcounts, d_rdispls, d_ridx,
-                           d_segoff, d_perm, d_ws, ws_bytes, (hipStream_t)hip_stream);
+                           d_segoff, d_perm, d_weights, d_rweights, d_ws, ws_bytes, (hipStream_t)hip_stream);
+}
+
+extern "C" int bls_plan(bls_ctx *ctx, const int64_t *d_indices, const int64_t *d_offsets, int64_t nnz,
+                        int64_t *d_sendcounts, int64_t *d_sdispls, int64_t *d_recvcounts, int64_t *d_rdispls,
+                        int64_t *d_ridx, int64_t *d_segoff, int64_t *d_perm, void *d_ws, size_t ws_bytes, void *hip_stream)
+{
+    if (!ctx) return BLS_EINVAL;
+    return plan_common(ctx, d_indices, d_offsets, nullptr, nnz, d_sendcounts, d_sdispls, d_recvcounts, d_rdispls, d_ridx,
+                       nullptr, d_segoff, d_perm, d_ws, ws_bytes, hip_stream);
+}
+
+extern "C" int bls_plan_weighted(bls_ctx *ctx, const int64_t *d_indices, const int64_t *d_offsets, const float *d_weights,
+                                 int64_t nnz, int64_t *d_sendcounts, int64_t *d_sdispls, int64_t *d_recvcounts,
+                                 int64_t *d_rdispls, int64_t *d_ridx, float *d_rweights, int64_t *d_segoff, int64_t *d_perm,
+                                 void *d_ws, size_t ws_bytes, void *hip_stream)
+{
+    if (!ctx) return BLS_EINVAL;
+    if (nnz > 0 && (!d_weights || !d_rweights)) return bls_fail(ctx, BLS_EINVAL, "bls_plan_weighted: NULL weights");
+    return plan_common(ctx, d_indices, d_offsets, d_weights, nnz, d_sendcounts, d_sdispls, d_recvcounts, d_rdispls, d_ridx,
+                       d_rweights, d_segoff, d_perm, d_ws, ws_bytes, hip_stream);
+}
+
+static int pool_common(bls_ctx *ctx, const int64_t *d_ridx, const float *d_rweights, const int64_t *d_segoff, int64_t nnz,
+                       float *d_pooled, void *hip_stream)
+{
+    if (nnz < 0 || !d_segoff || !d_pooled || (nnz > 0 && !d_ridx)) return bls_fail(ctx, BLS_EINVAL, "bls_embbag_pool: NULL argument");
+    if (((uintptr_t)d_pooled & 15u) != 0) return bls_fail(ctx, BLS_EINVAL, "bls_embbag_pool: output must be 16-byte aligned");
+    int rc = bls_commit(ctx);
+    if (rc) return rc;
+    return bls_launch_pool(ctx, d_ridx, d_rweights, d_segoff, nnz, d_pooled, 0, (hipStream_t)hip_stream);
 }
 
 extern "C" int bls_embbag_pool(bls_ctx *ctx, const int64_t *d_ridx, const int64_t *d_segoff, int64_t nnz,
                                float *d_pooled, void *hip_stream)
 {
     if (!ctx) return BLS_EINVAL;
-    if (nnz < 0 || !d_segoff || !d_pooled || (nnz > 0 && !d_ridx)) return bls_fail(ctx, BLS_EINVAL, "bls_embbag_pool: NULL argument");
-    if (((uintptr_t)d_pooled & 15u) != 0) return bls_fail(ctx, BLS_EINVAL, "bls_embbag_pool: output must be 16-byte aligned");
-    int rc = bls_commit(ctx);
-    if (rc) return rc;
-    return bls_launch_pool(ctx, d_ridx, d_segoff, nnz, d_pooled, 0, (hipStream_t)hip_stream);
+    return pool_common(ctx, d_ridx, nullptr, d_segoff, nnz, d_pooled, hip_stream);
+}
+
+extern "C" int bls_embbag_pool_weighted(bls_ctx *ctx, const int64_t *d_ridx, const float *d_rweights, const int64_t *d_segoff,
+                                        int64_t nnz, float *d_pooled, void *hip_stream)
+{
+    if (!ctx) return BLS_EINVAL;
+    if (nnz > 0 && !d_rweights) return bls_fail(ctx, BLS_EINVAL, "bls_embbag_pool_weighted: NULL weights");
+    return pool_common(ctx, d_ridx, nnz > 0 ? d_rweights : nullptr, d_segoff, nnz, d_pooled, hip_stream);
 }
 
 extern "C" int bls_pack(bls_ctx *ctx, const float *d_pooled, float *d_send, void *hip_stream)
@@ -324,15 +358,14 @@ extern "C" int bls_alltoallv_local(bls_ctx *ctx, const float *d_send, int32_t sl
     return BLS_OK;
 }
 
-extern "C" int bls_embbag_pool_put(bls_ctx *ctx, const int64_t *d_ridx, const int64_t *d_segoff, int64_t nnz,
-                                   int32_t slot, void *hip_stream)
+static int put_common(bls_ctx *ctx, const int64_t *d_ridx, const float *d_rweights, const int64_t *d_segoff, int64_t nnz,
+                      int32_t slot, void *hip_stream)
 {
-    if (!ctx) return BLS_EINVAL;
     if (nnz < 0 || !d_segoff || (nnz > 0 && !d_ridx)) return bls_fail(ctx, BLS_EINVAL, "bls_embbag_pool_put: NULL argument");
     RingSlot *r = nullptr;
     int rc = slot_to_fill(ctx, slot, "bls_embbag_pool_put", &r);
     if (rc) return rc;
-    rc = bls_launch_pool(ctx, d_ridx, d_segoff, nnz, (float *)(ctx->slots + (size_t)slot * ctx->slot_bytes), 1,
+    rc = bls_launch_pool(ctx, d_ridx, d_rweights, d_segoff, nnz, (float *)(ctx->slots + (size_t)slot * ctx->slot_bytes), 1,
                          (hipStream_t)hip_stream);
     if (rc) return rc;
     BLS_HIP(ctx, hipEventRecord(r->filled, (hipStream_t)hip_stream));
@@ -340,9 +373,23 @@ extern "C" int bls_embbag_pool_put(bls_ctx *ctx, const int64_t *d_ridx, const in
     return BLS_OK;
 }
 
-extern "C" int bls_unpack(bls_ctx *ctx, int64_t iter, float *d_out, void *hip_stream)
+extern "C" int bls_embbag_pool_put(bls_ctx *ctx, const int64_t *d_ridx, const int64_t *d_segoff, int64_t nnz,
+                                   int32_t slot, void *hip_stream)
 {
     if (!ctx) return BLS_EINVAL;
+    return put_common(ctx, d_ridx, nullptr, d_segoff, nnz, slot, hip_stream);
+}
+
+extern "C" int bls_embbag_pool_put_weighted(bls_ctx *ctx, const int64_t *d_ridx, const float *d_rweights,
+                                            const int64_t *d_segoff, int64_t nnz, int32_t slot, void *hip_stream)
+{
+    if (!ctx) return BLS_EINVAL;
+    if (nnz > 0 && !d_rweights) return bls_fail(ctx, BLS_EINVAL, "bls_embbag_pool_put_weighted: NULL weights");
+    return put_common(ctx, d_ridx, nnz > 0 ? d_rweights : nullptr, d_segoff, nnz, slot, hip_stream);
+}
+
+static int unpack_common(bls_ctx *ctx, int64_t iter, const int64_t *mean_off, float *d_out, void *hip_stream)
+{
     if (ctx->head == ctx->tail) return bls_fail(ctx, BLS_ERING_EMPTY, "bls_unpack: nothing in flight");
     if (iter != ctx->tail) return bls_fail(ctx, BLS_EORDER, "bls_unpack: not the oldest iteration in flight");
     if (!d_out || ((uintptr_t)d_out & 15u) != 0) return bls_fail(ctx, BLS_EINVAL, "bls_unpack: NULL or misaligned output");
@@ -352,13 +399,27 @@ extern "C" int bls_unpack(bls_ctx *ctx, int64_t iter, float *d_out, void *hip_st
     int rc = bls_commit(ctx);
     if (rc) return rc;
     BLS_HIP(ctx, hipStreamWaitEvent((hipStream_t)hip_stream, r.filled, 0));
-    rc = bls_launch_unpack(ctx, (const float *)(ctx->slots + (size_t)slot * ctx->slot_bytes), d_out, (hipStream_t)hip_stream);
+    rc = bls_launch_unpack(ctx, (const float *)(ctx->slots + (size_t)slot * ctx->slot_bytes), d_out, mean_off,
+                           (hipStream_t)hip_stream);
     if (rc) return rc;
     BLS_HIP(ctx, hipEventRecord(r.released, (hipStream_t)hip_stream));
     r.has_released = true;
     r.state = 0;
     ctx->tail = iter + 1;
     return BLS_OK;
+}
+
+extern "C" int bls_unpack(bls_ctx *ctx, int64_t iter, float *d_out, void *hip_stream)
+{
+    if (!ctx) return BLS_EINVAL;
+    return unpack_common(ctx, iter, nullptr, d_out, hip_stream);
+}
+
+extern "C" int bls_unpack_mean(bls_ctx *ctx, int64_t iter, const int64_t *d_offsets, float *d_out, void *hip_stream)
+{
+    if (!ctx) return BLS_EINVAL;
+    if (!d_offsets) return bls_fail(ctx, BLS_EINVAL, "bls_unpack_mean: NULL offsets");
+    return unpack_common(ctx, iter, d_offsets, d_out, hip_stream);
 }
 
 extern "C" int bls_check(bls_ctx *ctx, void *hip_stream)

@@ -85,14 +85,16 @@ int bls_commit(bls_ctx *ctx);   // upload descriptor tables if needed; requires 
 // launches, defined next to their kernels
 int bls_launch_plan(bls_ctx *ctx, const int64_t *idx, const int64_t *off, int64_t nnz, int64_t *sendcounts,
                     int64_t *sdispls, int64_t *recvcounts, int64_t *rdispls, int64_t *ridx, int64_t *segoff,
-                    int64_t *perm, void *ws, size_t ws_bytes, hipStream_t st);
+                    int64_t *perm, const float *w_in, float *w_out, void *ws, size_t ws_bytes, hipStream_t st);
 size_t bls_plan_ws_bytes(const bls_ctx *ctx);
 // to_slot = 0: Y in pooled order (y); 1: Y is a ring slot, vectors go to receive order (rho)
-int bls_launch_pool(bls_ctx *ctx, const int64_t *ridx, const int64_t *segoff, int64_t nnz, float *Y, int to_slot,
-                    hipStream_t st);
+// rw: weight of every lookup in ridx order, or NULL
+int bls_launch_pool(bls_ctx *ctx, const int64_t *ridx, const float *rw, const int64_t *segoff, int64_t nnz, float *Y,
+                    int to_slot, hipStream_t st);
 int bls_launch_pack(bls_ctx *ctx, const float *Y, float *S, hipStream_t st);
 int bls_launch_exchange(bls_ctx *ctx, const float *S, float *R, hipStream_t st);
-int bls_launch_unpack(bls_ctx *ctx, const float *R, float *out, hipStream_t st);
+// mean_off: the batch's offsets for mean pooling (divide by the bag length), or NULL
+int bls_launch_unpack(bls_ctx *ctx, const float *R, float *out, const int64_t *mean_off, hipStream_t st);
 
 // ---- device helpers ----------------------------------------------------------------
 #ifdef __HIPCC__

@@ -20,9 +20,21 @@ inline int lanes_for(int64_t cols)
     return g;
 }
 
+__device__ __forceinline__ void vdiv(float4 &a, float x) { a.x /= x; a.y /= x; a.z /= x; a.w /= x; }
+__device__ __forceinline__ void vdiv(float &a, float x) { a /= x; }
+
+// Length of bag (t, b) as a float divisor for mean pooling; 1 for an empty or malformed bag.
+__device__ __forceinline__ float bag_divisor(const DevDesc &dd, const int64_t *off, int t, uint32_t b)
+{
+    const int64_t g = (int64_t)t * dd.B + b;
+    const int64_t len = off[g + 1] - off[g];
+    return len > 0 ? (float)len : 1.f;
+}
+
 template <int MODE, class V>
 __global__ __launch_bounds__(kThreads) void move_vectors(DevDesc dd, const float *__restrict__ src,
-                                                         float *__restrict__ dst, int lg)
+                                                         float *__restrict__ dst, int lg,
+                                                         const int64_t *__restrict__ mean_off)
 {
     constexpr int VEC = sizeof(V) / sizeof(float);
     const int G = 1 << lg;
@@ -46,7 +58,12 @@ __global__ __launch_bounds__(kThreads) void move_vectors(DevDesc dd, const float
     const V *__restrict__ ps = reinterpret_cast<const V *>(src + from * dd.D);
     V *__restrict__ pd = reinterpret_cast<V *>(dst + to * dd.D);
     const int cols = dd.D / VEC;
-    for (int c = li; c < cols; c += G) pd[c] = ps[c];
+    if (MODE == kUnpackTable && mean_off) {
+        const float div = bag_divisor(dd, mean_off, dd.q_t[q], b);
+        for (int c = li; c < cols; c += G) { V x = ps[c]; vdiv(x, div); pd[c] = x; }
+    } else {
+        for (int c = li; c < cols; c += G) pd[c] = ps[c];
+    }
 }
 
 __device__ __forceinline__ void vadd(float4 &a, const float4 &x) { a.x += x.x; a.y += x.y; a.z += x.z; a.w += x.w; }
@@ -58,7 +75,8 @@ __device__ __forceinline__ void vzero(float &a) { a = 0.f; }
 // partial vector rank d sent for (t, b).  Grid y = t.
 template <class V>
 __global__ __launch_bounds__(kThreads) void unpack_rowwise(DevDesc dd, const float *__restrict__ R,
-                                                           float *__restrict__ out, int lg)
+                                                           float *__restrict__ out, int lg,
+                                                           const int64_t *__restrict__ mean_off)
 {
     constexpr int VEC = sizeof(V) / sizeof(float);
     const int G = 1 << lg;
@@ -70,6 +88,7 @@ __global__ __launch_bounds__(kThreads) void unpack_rowwise(DevDesc dd, const flo
     bls_split_sample(dd, b, s, b_loc, n);
     V *__restrict__ pd = reinterpret_cast<V *>(out + ((int64_t)b * dd.T + t) * dd.D);
     const int cols = dd.D / VEC;
+    const float div = mean_off ? bag_divisor(dd, mean_off, t, b) : 1.f;
     for (int c = li; c < cols; c += G) {
         V acc;
         vzero(acc);
@@ -77,12 +96,13 @@ __global__ __launch_bounds__(kThreads) void unpack_rowwise(DevDesc dd, const flo
             const V *__restrict__ ps = reinterpret_cast<const V *>(R + bls_rho(dd, d * dd.T + t, s, b_loc, n) * dd.D);
             vadd(acc, ps[c]);
         }
+        if (mean_off) vdiv(acc, div);
         pd[c] = acc;
     }
 }
 
 template <int MODE>
-int launch_move(bls_ctx *ctx, const float *src, float *dst, hipStream_t st)
+int launch_move(bls_ctx *ctx, const float *src, float *dst, const int64_t *mean_off, hipStream_t st)
 {
     const bool vec = ctx->D % 4 == 0;
     const int g = lanes_for(vec ? ctx->D / 4 : ctx->D);
@@ -90,32 +110,32 @@ int launch_move(bls_ctx *ctx, const float *src, float *dst, hipStream_t st)
     while ((1 << lg) < g) ++lg;
     const uint32_t per_block = kThreads >> lg;
     dim3 grid((unsigned)((ctx->B + per_block - 1) / per_block), ctx->Q);
-    if (vec) move_vectors<MODE, float4><<<grid, kThreads, 0, st>>>(ctx->desc, src, dst, lg);
-    else move_vectors<MODE, float><<<grid, kThreads, 0, st>>>(ctx->desc, src, dst, lg);
+    if (vec) move_vectors<MODE, float4><<<grid, kThreads, 0, st>>>(ctx->desc, src, dst, lg, mean_off);
+    else move_vectors<MODE, float><<<grid, kThreads, 0, st>>>(ctx->desc, src, dst, lg, mean_off);
     BLS_HIP(ctx, hipGetLastError());
     return BLS_OK;
 }
 
 }  // namespace
 
-int bls_launch_pack(bls_ctx *ctx, const float *Y, float *S, hipStream_t st) { return launch_move<kPack>(ctx, Y, S, st); }
+int bls_launch_pack(bls_ctx *ctx, const float *Y, float *S, hipStream_t st) { return launch_move<kPack>(ctx, Y, S, nullptr, st); }
 
 int bls_launch_exchange(bls_ctx *ctx, const float *S, float *R, hipStream_t st)
 {
-    return launch_move<kExchange>(ctx, S, R, st);
+    return launch_move<kExchange>(ctx, S, R, nullptr, st);
 }
 
-int bls_launch_unpack(bls_ctx *ctx, const float *R, float *out, hipStream_t st)
+int bls_launch_unpack(bls_ctx *ctx, const float *R, float *out, const int64_t *mean_off, hipStream_t st)
 {
-    if (ctx->part_kind == BLS_TABLE_WISE) return launch_move<kUnpackTable>(ctx, R, out, st);
+    if (ctx->part_kind == BLS_TABLE_WISE) return launch_move<kUnpackTable>(ctx, R, out, mean_off, st);
     const bool vec = ctx->D % 4 == 0;
     const int g = lanes_for(vec ? ctx->D / 4 : ctx->D);
     int lg = 0;
     while ((1 << lg) < g) ++lg;
     const uint32_t per_block = kThreads >> lg;
     dim3 grid((unsigned)((ctx->B + per_block - 1) / per_block), ctx->T);
-    if (vec) unpack_rowwise<float4><<<grid, kThreads, 0, st>>>(ctx->desc, R, out, lg);
-    else unpack_rowwise<float><<<grid, kThreads, 0, st>>>(ctx->desc, R, out, lg);
+    if (vec) unpack_rowwise<float4><<<grid, kThreads, 0, st>>>(ctx->desc, R, out, lg, mean_off);
+    else unpack_rowwise<float><<<grid, kThreads, 0, st>>>(ctx->desc, R, out, lg, mean_off);
     BLS_HIP(ctx, hipGetLastError());
     return BLS_OK;
 }

@@ -229,7 +229,8 @@ __global__ __launch_bounds__(kThreads) void plan_scatter_runs(DevDesc dd, const 
                                                               const int64_t *__restrict__ segoff,
                                                               int64_t *__restrict__ ridx, int64_t *__restrict__ perm,
                                                               const int64_t *__restrict__ sabs,
-                                                              const int64_t *__restrict__ rabs)
+                                                              const int64_t *__restrict__ rabs,
+                                                              const float *__restrict__ w_in, float *__restrict__ w_out)
 {
     constexpr int kPer = 4;
     for (int run = blockIdx.y; run < dd.Q * dd.P; run += gridDim.y) {
@@ -257,6 +258,7 @@ __global__ __launch_bounds__(kThreads) void plan_scatter_runs(DevDesc dd, const 
                 if (i < len) {
                     if (v[k] < 0 || v[k] >= rows) { flag_error(dd); v[k] = 0; }
                     ridx[dst + i] = v[k];
+                    if (w_in) w_out[dst + i] = w_in[lo + i];
                     if (perm) perm[lo + i] = dst + i + to_send;
                 }
             }
@@ -273,7 +275,8 @@ __global__ __launch_bounds__(kThreads) void plan_scatter_rowwise(DevDesc dd, con
                                                                  const int64_t *__restrict__ segoff,
                                                                  int64_t *__restrict__ ridx, int64_t *__restrict__ perm,
                                                                  const int64_t *__restrict__ sabs,
-                                                                 const int64_t *__restrict__ rabs)
+                                                                 const int64_t *__restrict__ rabs,
+                                                                 const float *__restrict__ w_in, float *__restrict__ w_out)
 {
     const int lane = threadIdx.x & 63;
     const int li = lane & (G - 1), gbase = lane & ~(G - 1);
@@ -318,6 +321,7 @@ __global__ __launch_bounds__(kThreads) void plan_scatter_rowwise(DevDesc dd, con
         if (d >= 0) {
             if (place >= 0 && place < nnz) {
                 ridx[place] = r;
+                if (w_in) w_out[place] = w_in[lo + j];
                 if (perm) perm[lo + j] = place + shift;
             } else flag_error(dd);
         }
@@ -336,7 +340,7 @@ size_t bls_plan_ws_bytes(const bls_ctx *ctx)
 
 int bls_launch_plan(bls_ctx *ctx, const int64_t *idx, const int64_t *off, int64_t nnz, int64_t *sendcounts,
                     int64_t *sdispls, int64_t *recvcounts, int64_t *rdispls, int64_t *ridx, int64_t *segoff,
-                    int64_t *perm, void *ws, size_t ws_bytes, hipStream_t st)
+                    int64_t *perm, const float *w_in, float *w_out, void *ws, size_t ws_bytes, hipStream_t st)
 {
     (void)ws_bytes;
     const DevDesc &dd = ctx->desc;
@@ -367,17 +371,17 @@ int bls_launch_plan(bls_ctx *ctx, const int64_t *idx, const int64_t *off, int64_
     if (nnz > 0) {
         if (rowwise) {
             switch (rg) {
-            case 8: plan_scatter_rowwise<8><<<rgrid, kThreads, 0, st>>>(dd, idx, off, nnz, segoff, ridx, perm, sabs, rabs); break;
-            case 16: plan_scatter_rowwise<16><<<rgrid, kThreads, 0, st>>>(dd, idx, off, nnz, segoff, ridx, perm, sabs, rabs); break;
-            case 32: plan_scatter_rowwise<32><<<rgrid, kThreads, 0, st>>>(dd, idx, off, nnz, segoff, ridx, perm, sabs, rabs); break;
-            default: plan_scatter_rowwise<64><<<rgrid, kThreads, 0, st>>>(dd, idx, off, nnz, segoff, ridx, perm, sabs, rabs); break;
+            case 8: plan_scatter_rowwise<8><<<rgrid, kThreads, 0, st>>>(dd, idx, off, nnz, segoff, ridx, perm, sabs, rabs, w_in, w_out); break;
+            case 16: plan_scatter_rowwise<16><<<rgrid, kThreads, 0, st>>>(dd, idx, off, nnz, segoff, ridx, perm, sabs, rabs, w_in, w_out); break;
+            case 32: plan_scatter_rowwise<32><<<rgrid, kThreads, 0, st>>>(dd, idx, off, nnz, segoff, ridx, perm, sabs, rabs, w_in, w_out); break;
+            default: plan_scatter_rowwise<64><<<rgrid, kThreads, 0, st>>>(dd, idx, off, nnz, segoff, ridx, perm, sabs, rabs, w_in, w_out); break;
             }
         } else {
             const int64_t runs = (int64_t)ctx->Q * ctx->P;
             const int64_t per_run = nnz / runs + 1;
             const unsigned gx = (unsigned)std::min<int64_t>(256, std::max<int64_t>(1, (per_run + 2047) / 2048));
             dim3 grid(gx, (unsigned)std::min<int64_t>(runs, 65535));
-            plan_scatter_runs<<<grid, kThreads, 0, st>>>(dd, idx, off, nnz, segoff, ridx, perm, sabs, rabs);
+            plan_scatter_runs<<<grid, kThreads, 0, st>>>(dd, idx, off, nnz, segoff, ridx, perm, sabs, rabs, w_in, w_out);
         }
     }
     BLS_HIP(ctx, hipGetLastError());

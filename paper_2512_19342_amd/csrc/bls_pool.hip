@@ -78,6 +78,20 @@ template <int DT, int VB> struct Acc {
             else a[i] += __uint_as_float(r.w[i]);
         }
     }
+    // per-sample weight: the product is rounded to fp32, then added (no fused multiply-add)
+    __device__ __forceinline__ void add_weighted(const Raw &r, float w)
+    {
+#pragma unroll
+        for (int i = 0; i < NW; ++i) {
+            if constexpr (DT == BLS_FP16) {
+                const float p0 = w * half_lo(r.w[i]), p1 = w * half_hi(r.w[i]);
+                a[2 * i] += p0; a[2 * i + 1] += p1;
+            } else {
+                const float p0 = w * __uint_as_float(r.w[i]);
+                a[i] += p0;
+            }
+        }
+    }
     __device__ __forceinline__ void store(float *p) const
     {
         if constexpr (NV % 4 == 0) {
@@ -120,6 +134,7 @@ __device__ __forceinline__ uint64_t group_broadcast64(uint64_t v, int gbase4, in
 // grid: x over groups of samples, y = q (owner, local table).
 template <int G, int DT, int VB, int U>
 __global__ __launch_bounds__(kThreads) void pool_rows(DevDesc dd, const int64_t *__restrict__ ridx,
+                                                      const float *__restrict__ rw,
                                                       const int64_t *__restrict__ segoff, int64_t nnz,
                                                       float *__restrict__ Y, int to_slot)
 {
@@ -152,23 +167,33 @@ __global__ __launch_bounds__(kThreads) void pool_rows(DevDesc dd, const int64_t 
         const int64_t left = len - c0;
         const int rem = left < 0 ? 0 : (left > G ? G : (int)left);
         uint32_t mine = kBadRow;
+        float wmine = 0.f;
         if (li < rem) {
             const int64_t r = ridx[beg + c0 + li];
             if (r < 0 || r >= shard_rows) flag_error(dd);
             else mine = (uint32_t)r;
+            if (rw) wmine = rw[beg + c0 + li];
         }
         for (int j = 0; __any(j < rem); j += U) {
             uint32_t r[U];
+            float wt[U];
             typename A::Raw v[U];
 #pragma unroll
-            for (int u = 0; u < U; ++u) r[u] = (uint32_t)__shfl((int)mine, gbase + ((j + u) & (G - 1)), 64);
+            for (int u = 0; u < U; ++u) {
+                r[u] = (uint32_t)__shfl((int)mine, gbase + ((j + u) & (G - 1)), 64);
+                wt[u] = __shfl(wmine, gbase + ((j + u) & (G - 1)), 64);
+            }
 #pragma unroll
             for (int u = 0; u < U; ++u) {
                 v[u] = A::none();
                 if (j + u < rem && r[u] != kBadRow && col_ok) v[u] = A::load(base + (uint64_t)r[u] * row_bytes);
+                else wt[u] = 0.f;
             }
 #pragma unroll
-            for (int u = 0; u < U; ++u) acc.add(v[u]);      // adding +0 for skipped rows changes nothing
+            for (int u = 0; u < U; ++u) {                   // adding +0 for skipped rows changes nothing
+                if (rw) acc.add_weighted(v[u], wt[u]);
+                else acc.add(v[u]);
+            }
         }
     }
     if (live && col_ok) acc.store(Y + out * dd.D + li * A::NV);
@@ -178,8 +203,10 @@ __global__ __launch_bounds__(kThreads) void pool_rows(DevDesc dd, const int64_t 
 // grid: x over groups (s-major, then chunks of nb_max samples), y = q.
 // WIDE: row positions as 64-bit byte offsets; otherwise 32-bit, in units of VB bytes (shards
 // below 2^32 * VB bytes), which halves the lane exchanges and the registers they occupy.
-template <int G, int DT, int VB, int U, bool WIDE>
+// WGT: per-sample weights rw[] (in ridx order) multiply every row before it is added.
+template <int G, int DT, int VB, int U, bool WIDE, bool WGT>
 __global__ __launch_bounds__(kThreads) void pool_stream(DevDesc dd, const int64_t *__restrict__ ridx,
+                                                        const float *__restrict__ rw,
                                                         const int64_t *__restrict__ segoff, int64_t nnz,
                                                         float *__restrict__ Y, int to_slot, int nb_max, uint32_t chunks_per_s, uint32_t wgx)
 {
@@ -270,20 +297,28 @@ __global__ __launch_bounds__(kThreads) void pool_stream(DevDesc dd, const int64_
         if constexpr (WIDE) return (uint32_t)(p >> 32) != 0xffffffffu;
         else return p != kNone;
     };
+    auto fetch_weight = [&](int c0) -> float {
+        if constexpr (WGT) return c0 + li < total ? rw[beg + c0 + li] : 0.f;
+        else return 0.f;
+    };
     pos_t mine = fetch(0);
+    float wmine = fetch_weight(0);
     typename A::Raw v[U];
 #pragma unroll
     for (int u = 0; u < U; ++u) v[u] = A::none();
     for (int c0 = 0; __any(c0 < total); c0 += G) {
         const pos_t ahead = fetch(c0 + G);                   // next block of row numbers, in flight
+        const float wahead = fetch_weight(c0 + G);
         const int left = total - c0;
         const int rem = left < 0 ? 0 : (left > G ? G : left);
         for (int j = 0; __any(j < rem); j += U) {
             pos_t off[U];
+            float wt[WGT ? U : 1];
 #pragma unroll
             for (int u = 0; u < U; ++u) {
                 if constexpr (WIDE) off[u] = group_broadcast64<G>(mine, gbase * 4, j + u);
                 else off[u] = group_broadcast32<G>(mine, gbase * 4, j + u);
+                if constexpr (WGT) wt[u] = __uint_as_float(group_broadcast32<G>(__float_as_uint(wmine), gbase * 4, j + u));
             }
             // lanes without a row keep stale registers and skip the add: nothing to clear
 #pragma unroll
@@ -295,12 +330,16 @@ __global__ __launch_bounds__(kThreads) void pool_stream(DevDesc dd, const int64_
             const int at = c0 + j;                           // stream position of the batch (uniform)
 #pragma unroll
             for (int u = 0; u < U; ++u) {
-                if (is_row(off[u])) acc.add(v[u]);
+                if (is_row(off[u])) {
+                    if constexpr (WGT) acc.add_weighted(v[u], wt[u]);
+                    else acc.add(v[u]);
+                }
                 pos = at + u + 1 < total ? at + u + 1 : total;
                 flush();
             }
         }
         mine = ahead;
+        wmine = wahead;
     }
 }
 
@@ -308,6 +347,7 @@ __global__ __launch_bounds__(kThreads) void pool_stream(DevDesc dd, const int64_
 // columns, scalar loads.
 template <int DT>
 __global__ __launch_bounds__(kThreads) void pool_rows_generic(DevDesc dd, const int64_t *__restrict__ ridx,
+                                                              const float *__restrict__ rw,
                                                               const int64_t *__restrict__ segoff, int64_t nnz,
                                                               float *__restrict__ Y, int to_slot)
 {
@@ -329,7 +369,9 @@ __global__ __launch_bounds__(kThreads) void pool_rows_generic(DevDesc dd, const 
             const int64_t r = ridx[j];
             if (r < 0 || r >= shard_rows) { if (c == 0) flag_error(dd); continue; }
             const int64_t e = r * dd.D + c;
-            acc += DT == BLS_FP16 ? half_bits(((const unsigned short *)base)[e]) : ((const float *)base)[e];
+            const float x = DT == BLS_FP16 ? half_bits(((const unsigned short *)base)[e]) : ((const float *)base)[e];
+            if (rw) { const float term = rw[j] * x; acc += term; }
+            else acc += x;
         }
         y[c] = acc;
     }
@@ -342,7 +384,7 @@ int env_int(const char *name, int dflt)
 }
 
 template <int G, int DT, int VB, int U>
-void launch_rows(const bls_ctx *ctx, const int64_t *ridx, const int64_t *segoff, int64_t nnz, float *Y, int to_slot, hipStream_t st)
+void launch_rows(const bls_ctx *ctx, const int64_t *ridx, const float *rw, const int64_t *segoff, int64_t nnz, float *Y, int to_slot, hipStream_t st)
 {
     constexpr int UU = U < G ? U : G;
     const uint32_t per_block = kThreads / G;
@@ -364,49 +406,54 @@ void launch_rows(const bls_ctx *ctx, const int64_t *ridx, const int64_t *segoff,
         const int64_t row_bytes = (int64_t)ctx->D * (DT == BLS_FP16 ? 2 : 4);
         bool wide = env_int("BLS_POOL_WIDE", 0) != 0;
         for (int q = 0; q < ctx->Q; ++q) wide = wide || ctx->q_rows[q] * (row_bytes / VB) >= 0xffffffffLL;
-        if (wide) pool_stream<G, DT, VB, UU, true><<<grid, kThreads, 0, st>>>(ctx->desc, ridx, segoff, nnz, Y, to_slot, nb, chunks, deal);
-        else pool_stream<G, DT, VB, UU, false><<<grid, kThreads, 0, st>>>(ctx->desc, ridx, segoff, nnz, Y, to_slot, nb, chunks, deal);
+        if (rw) {
+            if (wide) pool_stream<G, DT, VB, UU, true, true><<<grid, kThreads, 0, st>>>(ctx->desc, ridx, rw, segoff, nnz, Y, to_slot, nb, chunks, deal);
+            else pool_stream<G, DT, VB, UU, false, true><<<grid, kThreads, 0, st>>>(ctx->desc, ridx, rw, segoff, nnz, Y, to_slot, nb, chunks, deal);
+        } else {
+            if (wide) pool_stream<G, DT, VB, UU, true, false><<<grid, kThreads, 0, st>>>(ctx->desc, ridx, rw, segoff, nnz, Y, to_slot, nb, chunks, deal);
+            else pool_stream<G, DT, VB, UU, false, false><<<grid, kThreads, 0, st>>>(ctx->desc, ridx, rw, segoff, nnz, Y, to_slot, nb, chunks, deal);
+        }
     } else {
         dim3 grid((unsigned)((ctx->B + per_block - 1) / per_block), ctx->Q);
-        pool_rows<G, DT, VB, UU><<<grid, kThreads, 0, st>>>(ctx->desc, ridx, segoff, nnz, Y, to_slot);
+        pool_rows<G, DT, VB, UU><<<grid, kThreads, 0, st>>>(ctx->desc, ridx, rw, segoff, nnz, Y, to_slot);
     }
 }
 
 template <int DT, int VB, int U>
-bool dispatch_lanes(const bls_ctx *ctx, int lanes, const int64_t *ridx, const int64_t *segoff, int64_t nnz, float *Y,
-                    int to_slot, hipStream_t st)
+bool dispatch_lanes(const bls_ctx *ctx, int lanes, const int64_t *ridx, const float *rw, const int64_t *segoff, int64_t nnz,
+                    float *Y, int to_slot, hipStream_t st)
 {
     switch (lanes) {
-    case 1: if constexpr (VB == 16) { launch_rows<1, DT, VB, U>(ctx, ridx, segoff, nnz, Y, to_slot, st); return true; } break;
-    case 2: if constexpr (VB == 16) { launch_rows<2, DT, VB, U>(ctx, ridx, segoff, nnz, Y, to_slot, st); return true; } break;
-    case 4: if constexpr (VB == 16) { launch_rows<4, DT, VB, U>(ctx, ridx, segoff, nnz, Y, to_slot, st); return true; } break;
-    case 8: if constexpr (VB == 16) { launch_rows<8, DT, VB, U>(ctx, ridx, segoff, nnz, Y, to_slot, st); return true; } break;
-    case 16: if constexpr (VB >= 8) { launch_rows<16, DT, VB, U>(ctx, ridx, segoff, nnz, Y, to_slot, st); return true; } break;
-    case 32: launch_rows<32, DT, VB, U>(ctx, ridx, segoff, nnz, Y, to_slot, st); return true;
-    case 64: launch_rows<64, DT, VB, U>(ctx, ridx, segoff, nnz, Y, to_slot, st); return true;
+    case 1: if constexpr (VB == 16) { launch_rows<1, DT, VB, U>(ctx, ridx, rw, segoff, nnz, Y, to_slot, st); return true; } break;
+    case 2: if constexpr (VB == 16) { launch_rows<2, DT, VB, U>(ctx, ridx, rw, segoff, nnz, Y, to_slot, st); return true; } break;
+    case 4: if constexpr (VB == 16) { launch_rows<4, DT, VB, U>(ctx, ridx, rw, segoff, nnz, Y, to_slot, st); return true; } break;
+    case 8: if constexpr (VB == 16) { launch_rows<8, DT, VB, U>(ctx, ridx, rw, segoff, nnz, Y, to_slot, st); return true; } break;
+    case 16: if constexpr (VB >= 8) { launch_rows<16, DT, VB, U>(ctx, ridx, rw, segoff, nnz, Y, to_slot, st); return true; } break;
+    case 32: launch_rows<32, DT, VB, U>(ctx, ridx, rw, segoff, nnz, Y, to_slot, st); return true;
+    case 64: launch_rows<64, DT, VB, U>(ctx, ridx, rw, segoff, nnz, Y, to_slot, st); return true;
     }
     return false;
 }
 
 template <int DT, int VB>
-bool dispatch_unroll(const bls_ctx *ctx, int lanes, int unroll, const int64_t *ridx, const int64_t *segoff, int64_t nnz,
-                     float *Y, int to_slot, hipStream_t st)
+bool dispatch_unroll(const bls_ctx *ctx, int lanes, int unroll, const int64_t *ridx, const float *rw, const int64_t *segoff,
+                     int64_t nnz, float *Y, int to_slot, hipStream_t st)
 {
     switch (unroll) {
-    case 4: return dispatch_lanes<DT, VB, 4>(ctx, lanes, ridx, segoff, nnz, Y, to_slot, st);
-    case 16: return dispatch_lanes<DT, VB, 16>(ctx, lanes, ridx, segoff, nnz, Y, to_slot, st);
-    default: return dispatch_lanes<DT, VB, 8>(ctx, lanes, ridx, segoff, nnz, Y, to_slot, st);
+    case 4: return dispatch_lanes<DT, VB, 4>(ctx, lanes, ridx, rw, segoff, nnz, Y, to_slot, st);
+    case 16: return dispatch_lanes<DT, VB, 16>(ctx, lanes, ridx, rw, segoff, nnz, Y, to_slot, st);
+    default: return dispatch_lanes<DT, VB, 8>(ctx, lanes, ridx, rw, segoff, nnz, Y, to_slot, st);
     }
 }
 
 template <int DT>
-bool dispatch_rows(const bls_ctx *ctx, int vb, int lanes, int unroll, const int64_t *ridx, const int64_t *segoff,
-                   int64_t nnz, float *Y, int to_slot, hipStream_t st)
+bool dispatch_rows(const bls_ctx *ctx, int vb, int lanes, int unroll, const int64_t *ridx, const float *rw,
+                   const int64_t *segoff, int64_t nnz, float *Y, int to_slot, hipStream_t st)
 {
     switch (vb) {
-    case 16: return dispatch_unroll<DT, 16>(ctx, lanes, unroll, ridx, segoff, nnz, Y, to_slot, st);
-    case 8: return dispatch_unroll<DT, 8>(ctx, lanes, unroll, ridx, segoff, nnz, Y, to_slot, st);
-    case 4: return dispatch_unroll<DT, 4>(ctx, lanes, unroll, ridx, segoff, nnz, Y, to_slot, st);
+    case 16: return dispatch_unroll<DT, 16>(ctx, lanes, unroll, ridx, rw, segoff, nnz, Y, to_slot, st);
+    case 8: return dispatch_unroll<DT, 8>(ctx, lanes, unroll, ridx, rw, segoff, nnz, Y, to_slot, st);
+    case 4: return dispatch_unroll<DT, 4>(ctx, lanes, unroll, ridx, rw, segoff, nnz, Y, to_slot, st);
     }
     return false;
 }
@@ -414,7 +461,7 @@ bool dispatch_rows(const bls_ctx *ctx, int vb, int lanes, int unroll, const int6
 
 }  // namespace
 
-int bls_launch_pool(bls_ctx *ctx, const int64_t *ridx, const int64_t *segoff, int64_t nnz, float *Y, int to_slot, hipStream_t st)
+int bls_launch_pool(bls_ctx *ctx, const int64_t *ridx, const float *rw, const int64_t *segoff, int64_t nnz, float *Y, int to_slot, hipStream_t st)
 {
     const int64_t row_bytes = (int64_t)ctx->D * (ctx->dtype == BLS_FP16 ? 2 : 4);
     // bytes per lane and row, rows in flight per lane: BLS_POOL_VB / BLS_POOL_U override the defaults
@@ -427,13 +474,13 @@ int bls_launch_pool(bls_ctx *ctx, const int64_t *ridx, const int64_t *segoff, in
     if (row_bytes % vb == 0 && row_bytes <= 64 * (int64_t)vb) {
         int lanes = 1;
         while ((int64_t)lanes * vb < row_bytes) lanes <<= 1;
-        done = ctx->dtype == BLS_FP16 ? dispatch_rows<BLS_FP16>(ctx, vb, lanes, unroll, ridx, segoff, nnz, Y, to_slot, st)
-                                      : dispatch_rows<BLS_FP32>(ctx, vb, lanes, unroll, ridx, segoff, nnz, Y, to_slot, st);
+        done = ctx->dtype == BLS_FP16 ? dispatch_rows<BLS_FP16>(ctx, vb, lanes, unroll, ridx, rw, segoff, nnz, Y, to_slot, st)
+                                      : dispatch_rows<BLS_FP32>(ctx, vb, lanes, unroll, ridx, rw, segoff, nnz, Y, to_slot, st);
     }
     if (!done) {
         dim3 grid((unsigned)((ctx->B + kThreads / 64 - 1) / (kThreads / 64)), ctx->Q);
-        if (ctx->dtype == BLS_FP16) pool_rows_generic<BLS_FP16><<<grid, kThreads, 0, st>>>(ctx->desc, ridx, segoff, nnz, Y, to_slot);
-        else pool_rows_generic<BLS_FP32><<<grid, kThreads, 0, st>>>(ctx->desc, ridx, segoff, nnz, Y, to_slot);
+        if (ctx->dtype == BLS_FP16) pool_rows_generic<BLS_FP16><<<grid, kThreads, 0, st>>>(ctx->desc, ridx, rw, segoff, nnz, Y, to_slot);
+        else pool_rows_generic<BLS_FP32><<<grid, kThreads, 0, st>>>(ctx->desc, ridx, rw, segoff, nnz, Y, to_slot);
     }
     BLS_HIP(ctx, hipGetLastError());
     return BLS_OK;

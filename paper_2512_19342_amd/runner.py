@@ -47,6 +47,7 @@ class Pipeline:
         self.ridx = torch.zeros(max(self.max_nnz, 1), **i64)
         self.segoff = torch.zeros(c.n_vec + 1, **i64)
         self.perm = torch.zeros(max(self.max_nnz, 1), **i64) if want_perm else None
+        self.rweights = None                                   # allocated on first weighted call
         self.ws = torch.zeros((sz["plan_ws_bytes"] + 7) // 8, **i64)
         nfl = c.n_vec * w.D
         self.pooled = torch.zeros(nfl, dtype=torch.float32, device=dev)
@@ -81,8 +82,29 @@ class Pipeline:
         c.bls_embbag_pool_put(self.ridx, self.segoff, nnz, slot, stream)
         return it, slot
 
-    def complete(self, it: int, out: torch.Tensor, stream=None):
-        self.ctx.bls_unpack(it, out, stream)
+    def issue_weighted(self, indices, offsets, weights, nnz: int, fused: bool = False, stream=None):
+        """As issue / issue_fused with per-sample weights (float32, input order)."""
+        c = self.ctx
+        assert nnz <= self.max_nnz
+        if self.rweights is None:
+            self.rweights = torch.zeros(max(self.max_nnz, 1), dtype=torch.float32, device=self.dev)
+        c.bls_plan_weighted(indices, offsets, weights, nnz, self.sendcounts, self.sdispls, self.recvcounts, self.rdispls,
+                            self.ridx, self.rweights, self.segoff, self.perm, self.ws, stream)
+        if fused:
+            it, slot = c.bls_ring_advance(stream)
+            c.bls_embbag_pool_put_weighted(self.ridx, self.rweights, self.segoff, nnz, slot, stream)
+            return it, slot
+        c.bls_embbag_pool_weighted(self.ridx, self.rweights, self.segoff, nnz, self.pooled, stream)
+        c.bls_pack(self.pooled, self.send, stream)
+        it, slot = c.bls_ring_advance(stream)
+        c.bls_alltoallv_local(self.send, slot, stream)
+        return it, slot
+
+    def complete(self, it: int, out: torch.Tensor, stream=None, mean_offsets: Optional[torch.Tensor] = None):
+        if mean_offsets is not None:
+            self.ctx.bls_unpack_mean(it, mean_offsets, out, stream)
+        else:
+            self.ctx.bls_unpack(it, out, stream)
 
     def step(self, indices, offsets, nnz, out, stream=None):
         it, _ = self.issue(indices, offsets, nnz, stream)

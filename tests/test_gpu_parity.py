@@ -320,3 +320,50 @@ def test_pool_put_needs_the_current_slot():
     assert e.value.code == B.BLS_EINVAL
     pipe.complete(j, pipe.new_out())
     pipe.ctx.bls_check()
+
+
+WEIGHTED = [synth.workload(2), synth.workload(3, "small"), synth.workload(4, "small"), synth.workload(5, "small"),
+            synth.workload(6, "small")] + [
+    synth.custom("edge", k=1, values="gauss", table_dtype=dt, seed=31, index_dist=("zipf", 1.1), **EDGE[i])
+    for i in (1, 2, 4, 5, 6, 7, 8, 10) for dt in ("fp32", "fp16")]
+
+
+@pytest.mark.parametrize("w", WEIGHTED, ids=lambda w: f"{w.name}-{w.table_dtype}-D{w.D}-P{w.P}-part{w.part_kind}")
+def test_weighted_and_mean_pooling(w):
+    """Per-sample weights (every product rounded, then added) through the staged and the fused
+    owner side, and mean pooling at completion, bit for bit against the oracle."""
+    from paper_2512_19342_amd.runner import Pipeline
+    if w.name in ("cfg3s", "cfg4s", "cfg6s"):
+        w.values = "gauss"
+    dev = torch.device("cuda:0")
+    tabs_cpu = [synth.make_table(w, t) for t in range(w.T)]
+    pipe = Pipeline(w, [t.to(dev) for t in tabs_cpu], 1 << 21)
+    c = case_of(w)
+    tabs_np = [t.numpy() for t in tabs_cpu]
+    ix, off = synth.make_batch(w, 4)
+    nnz = int(off[-1])
+    rng = np.random.default_rng(nnz)
+    wts = torch.from_numpy(rng.uniform(-2.0, 2.0, size=nnz).astype(np.float32))
+    ref = oracle.pipeline(c, tabs_np, ix.numpy(), off.numpy(), weights=wts.numpy())
+    d_ix, d_off, d_w = ix.to(dev), off.to(dev), wts.to(dev)
+    for fused in (False, True):
+        out = pipe.new_out()
+        j, slot = pipe.issue_weighted(d_ix, d_off, d_w, nnz, fused=fused)
+        assert np.array_equal(pipe.ridx[:nnz].cpu().numpy(), ref["ridx"])
+        assert np.array_equal(bits(pipe.rweights[:nnz].cpu().numpy()), bits(ref["rweights"]))
+        if not fused:
+            assert np.array_equal(bits(pipe.pooled.cpu().numpy()), bits(ref["Y"]))
+        assert np.array_equal(bits(pipe.slot_view(slot).cpu().numpy()), bits(ref["R"])), fused
+        pipe.complete(j, out)
+        assert np.array_equal(bits(out.cpu().numpy()), bits(ref["Out"])), fused
+    o64, _ = oracle.embbag_plain(c, tabs_np, ix.numpy(), off.numpy(), want32=False, weights=wts.numpy())
+    mass = oracle.embbag_absmass(c, tabs_np, ix.numpy(), off.numpy())
+    assert np.all(np.abs(out.cpu().numpy().astype(np.float64) - o64) <= 4 * TOL[w.table_dtype] * mass + 1e-30)
+    # mean pooling
+    refm = oracle.pipeline(c, tabs_np, ix.numpy(), off.numpy(), mean=True)["Out"]
+    for fused in (False, True):
+        out = pipe.new_out()
+        j, slot = (pipe.issue_fused if fused else pipe.issue)(d_ix, d_off, nnz)
+        pipe.complete(j, out, mean_offsets=d_off)
+        assert np.array_equal(bits(out.cpu().numpy()), bits(refm)), fused
+    pipe.ctx.bls_check()
