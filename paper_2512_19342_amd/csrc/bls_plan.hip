@@ -18,6 +18,7 @@ namespace {
 constexpr int kThreads = 256;
 constexpr int kItems = 16;                       // scan items per thread
 constexpr int kChunk = kThreads * kItems;        // scan items per block
+constexpr int kSmallScanTiles = 2;               // up to this many tiles one workgroup scans alone
 
 __device__ __forceinline__ void flag_error(const DevDesc &dd) { atomicOr(dd.err, 1); }
 
@@ -147,15 +148,13 @@ __global__ __launch_bounds__(kThreads) void scan_spine(int64_t *__restrict__ sum
     }
 }
 
-__global__ __launch_bounds__(kThreads) void scan_apply(int64_t *__restrict__ v, int64_t n,
-                                                       const int64_t *__restrict__ sums, int64_t *__restrict__ head)
+// Inclusive scan of one tile v[base .. base + kChunk) in place, offset by `carry`; returns
+// carry + the tile's total (the same value in every thread).  Items are staged in LDS so that
+// global accesses stay coalesced while every thread owns a contiguous run; one padding word
+// per run keeps the per-thread walks off one bank.
+__device__ __forceinline__ int64_t scan_tile(int64_t *__restrict__ v, int64_t n, int64_t base, int64_t carry,
+                                             int64_t *tile, int64_t *part)
 {
-    // items staged in LDS so that global accesses stay coalesced while every thread owns a
-    // contiguous run; one padding word per run keeps the per-thread walks off one bank
-    __shared__ int64_t tile[kChunk + kThreads];
-    __shared__ int64_t part[kThreads / 64];
-    const int64_t base = (int64_t)blockIdx.x * kChunk;
-    if (blockIdx.x == 0 && threadIdx.x == 0) *head = 0;   // segoff[0]
 #pragma unroll
     for (int k = 0; k < kItems; ++k) {
         const int e = k * kThreads + threadIdx.x;
@@ -171,8 +170,11 @@ __global__ __launch_bounds__(kThreads) void scan_apply(int64_t *__restrict__ v, 
     const int64_t inc = wave_inclusive_scan(run, lane);
     if (lane == 63) part[wv] = inc;
     __syncthreads();
-    int64_t before = sums[blockIdx.x] + inc - run;
-    for (int w = 0; w < wv; ++w) before += part[w];
+    int64_t before = carry + inc - run, total = carry;
+    for (int w = 0; w < kThreads / 64; ++w) {
+        if (w < wv) before += part[w];
+        total += part[w];
+    }
 #pragma unroll
     for (int k = 0; k < kItems; ++k) tile[mine + k] += before;
     __syncthreads();
@@ -182,16 +184,26 @@ __global__ __launch_bounds__(kThreads) void scan_apply(int64_t *__restrict__ v, 
         const int64_t i = base + e;
         if (i < n) v[i] = tile[e + e / kItems];
     }
+    __syncthreads();                                  // tile and part may be reused by the caller
+    return total;
 }
 
-// One block: counts and displacements from segoff at the (d, s) block edges.
-// sabs[s][d] / rabs[d][s]: absolute start of bucket (s, d) in requester / owner order.
-__global__ __launch_bounds__(kThreads) void plan_finish(DevDesc dd, const int64_t *__restrict__ segoff,
-                                                        int64_t *__restrict__ sendcounts, int64_t *__restrict__ sdispls,
-                                                        int64_t *__restrict__ recvcounts, int64_t *__restrict__ rdispls,
-                                                        int64_t *__restrict__ sabs, int64_t *__restrict__ rabs)
+__global__ __launch_bounds__(kThreads) void scan_apply(int64_t *__restrict__ v, int64_t n,
+                                                       const int64_t *__restrict__ sums, int64_t *__restrict__ head)
 {
-    __shared__ int64_t rowtot[64];
+    __shared__ int64_t tile[kChunk + kThreads];
+    __shared__ int64_t part[kThreads / 64];
+    if (blockIdx.x == 0 && threadIdx.x == 0) *head = 0;   // segoff[0]
+    scan_tile(v, n, (int64_t)blockIdx.x * kChunk, sums[blockIdx.x], tile, part);
+}
+
+// Counts and displacements from segoff at the (d, s) block edges, by one workgroup.
+// sabs[s][d] / rabs[d][s]: absolute start of bucket (s, d) in requester / owner order.
+__device__ __forceinline__ void finish_counts(const DevDesc &dd, const int64_t *__restrict__ segoff,
+                                              int64_t *__restrict__ sendcounts, int64_t *__restrict__ sdispls,
+                                              int64_t *__restrict__ recvcounts, int64_t *__restrict__ rdispls,
+                                              int64_t *__restrict__ sabs, int64_t *__restrict__ rabs, int64_t *rowtot)
+{
     const int P = dd.P;
     for (int e = threadIdx.x; e < P * P; e += kThreads) {
         const int d = e / P, s = e - d * P;
@@ -217,6 +229,32 @@ __global__ __launch_bounds__(kThreads) void plan_finish(DevDesc dd, const int64_
         for (int r = 0; r < s; ++r) sbase += rowtot[r];
         for (int d = 0; d < P; ++d) sabs[s * P + d] = sbase + sdispls[s * P + d];
     }
+}
+
+__global__ __launch_bounds__(kThreads) void plan_finish(DevDesc dd, const int64_t *__restrict__ segoff,
+                                                        int64_t *__restrict__ sendcounts, int64_t *__restrict__ sdispls,
+                                                        int64_t *__restrict__ recvcounts, int64_t *__restrict__ rdispls,
+                                                        int64_t *__restrict__ sabs, int64_t *__restrict__ rabs)
+{
+    __shared__ int64_t rowtot[64];
+    finish_counts(dd, segoff, sendcounts, sdispls, recvcounts, rdispls, sabs, rabs, rowtot);
+}
+
+// Small problems are bound by the number of launches: one workgroup scans all tiles in turn and
+// derives the counts, in place of the three scan kernels and plan_finish.
+__global__ __launch_bounds__(kThreads) void plan_scan_small(DevDesc dd, int64_t *__restrict__ segoff, int64_t n,
+                                                            int64_t *__restrict__ sendcounts, int64_t *__restrict__ sdispls,
+                                                            int64_t *__restrict__ recvcounts, int64_t *__restrict__ rdispls,
+                                                            int64_t *__restrict__ sabs, int64_t *__restrict__ rabs)
+{
+    __shared__ int64_t tile[kChunk + kThreads];
+    __shared__ int64_t part[kThreads / 64];
+    __shared__ int64_t rowtot[64];
+    if (threadIdx.x == 0) segoff[0] = 0;
+    int64_t carry = 0;
+    for (int64_t base = 0; base < n; base += kChunk) carry = scan_tile(segoff + 1, n, base, carry, tile, part);
+    __syncthreads();                                  // every segoff entry written by this workgroup is visible to it
+    finish_counts(dd, segoff, sendcounts, sdispls, recvcounts, rdispls, sabs, rabs, rowtot);
 }
 
 // ---- 3. scatter ------------------------------------------------------------------------
@@ -364,10 +402,14 @@ int bls_launch_plan(bls_ctx *ctx, const int64_t *idx, const int64_t *off, int64_
         dim3 grid((B + kThreads - 1) / kThreads, ctx->Q);
         plan_count_tablewise<<<grid, kThreads, 0, st>>>(dd, off, nnz, segoff + 1);
     }
-    scan_block_sums<<<dim3((unsigned)nblk), kThreads, 0, st>>>(segoff + 1, nseg, sums);
-    scan_spine<<<1, kThreads, 0, st>>>(sums, nblk);
-    scan_apply<<<dim3((unsigned)nblk), kThreads, 0, st>>>(segoff + 1, nseg, sums, segoff);
-    plan_finish<<<1, kThreads, 0, st>>>(dd, segoff, sendcounts, sdispls, recvcounts, rdispls, sabs, rabs);
+    if (nblk <= kSmallScanTiles) {
+        plan_scan_small<<<1, kThreads, 0, st>>>(dd, segoff, nseg, sendcounts, sdispls, recvcounts, rdispls, sabs, rabs);
+    } else {
+        scan_block_sums<<<dim3((unsigned)nblk), kThreads, 0, st>>>(segoff + 1, nseg, sums);
+        scan_spine<<<1, kThreads, 0, st>>>(sums, nblk);
+        scan_apply<<<dim3((unsigned)nblk), kThreads, 0, st>>>(segoff + 1, nseg, sums, segoff);
+        plan_finish<<<1, kThreads, 0, st>>>(dd, segoff, sendcounts, sdispls, recvcounts, rdispls, sabs, rabs);
+    }
     if (nnz > 0) {
         if (rowwise) {
             switch (rg) {

@@ -25,6 +25,7 @@ namespace {
 
 constexpr int kThreads = 256;
 constexpr uint32_t kBadRow = 0xffffffffu;
+constexpr int kRowsInFlight = 8;   // U: independent row loads issued per lane before the first add
 
 __device__ __forceinline__ void flag_error(const DevDesc &dd) { atomicOr(dd.err, 1); }
 
@@ -435,25 +436,14 @@ bool dispatch_lanes(const bls_ctx *ctx, int lanes, const int64_t *ridx, const fl
     return false;
 }
 
-template <int DT, int VB>
-bool dispatch_unroll(const bls_ctx *ctx, int lanes, int unroll, const int64_t *ridx, const float *rw, const int64_t *segoff,
-                     int64_t nnz, float *Y, int to_slot, hipStream_t st)
-{
-    switch (unroll) {
-    case 4: return dispatch_lanes<DT, VB, 4>(ctx, lanes, ridx, rw, segoff, nnz, Y, to_slot, st);
-    case 16: return dispatch_lanes<DT, VB, 16>(ctx, lanes, ridx, rw, segoff, nnz, Y, to_slot, st);
-    default: return dispatch_lanes<DT, VB, 8>(ctx, lanes, ridx, rw, segoff, nnz, Y, to_slot, st);
-    }
-}
-
 template <int DT>
-bool dispatch_rows(const bls_ctx *ctx, int vb, int lanes, int unroll, const int64_t *ridx, const float *rw,
+bool dispatch_rows(const bls_ctx *ctx, int vb, int lanes, const int64_t *ridx, const float *rw,
                    const int64_t *segoff, int64_t nnz, float *Y, int to_slot, hipStream_t st)
 {
     switch (vb) {
-    case 16: return dispatch_unroll<DT, 16>(ctx, lanes, unroll, ridx, rw, segoff, nnz, Y, to_slot, st);
-    case 8: return dispatch_unroll<DT, 8>(ctx, lanes, unroll, ridx, rw, segoff, nnz, Y, to_slot, st);
-    case 4: return dispatch_unroll<DT, 4>(ctx, lanes, unroll, ridx, rw, segoff, nnz, Y, to_slot, st);
+    case 16: return dispatch_lanes<DT, 16, kRowsInFlight>(ctx, lanes, ridx, rw, segoff, nnz, Y, to_slot, st);
+    case 8: return dispatch_lanes<DT, 8, kRowsInFlight>(ctx, lanes, ridx, rw, segoff, nnz, Y, to_slot, st);
+    case 4: return dispatch_lanes<DT, 4, kRowsInFlight>(ctx, lanes, ridx, rw, segoff, nnz, Y, to_slot, st);
     }
     return false;
 }
@@ -464,9 +454,8 @@ bool dispatch_rows(const bls_ctx *ctx, int vb, int lanes, int unroll, const int6
 int bls_launch_pool(bls_ctx *ctx, const int64_t *ridx, const float *rw, const int64_t *segoff, int64_t nnz, float *Y, int to_slot, hipStream_t st)
 {
     const int64_t row_bytes = (int64_t)ctx->D * (ctx->dtype == BLS_FP16 ? 2 : 4);
-    // bytes per lane and row, rows in flight per lane: BLS_POOL_VB / BLS_POOL_U override the defaults
+    // bytes per lane and row: 16 when the row length allows; BLS_POOL_VB overrides (for tests)
     int vb = env_int("BLS_POOL_VB", 16);
-    const int unroll = env_int("BLS_POOL_U", 8);
     if (vb != 16 && vb != 8 && vb != 4) vb = 16;
     while (vb > 4 && row_bytes % vb != 0) vb >>= 1;          // lanes must split the row evenly
     while (vb < 16 && row_bytes > 64 * (int64_t)vb) vb <<= 1; // and 64 of them must cover it
@@ -474,8 +463,8 @@ int bls_launch_pool(bls_ctx *ctx, const int64_t *ridx, const float *rw, const in
     if (row_bytes % vb == 0 && row_bytes <= 64 * (int64_t)vb) {
         int lanes = 1;
         while ((int64_t)lanes * vb < row_bytes) lanes <<= 1;
-        done = ctx->dtype == BLS_FP16 ? dispatch_rows<BLS_FP16>(ctx, vb, lanes, unroll, ridx, rw, segoff, nnz, Y, to_slot, st)
-                                      : dispatch_rows<BLS_FP32>(ctx, vb, lanes, unroll, ridx, rw, segoff, nnz, Y, to_slot, st);
+        done = ctx->dtype == BLS_FP16 ? dispatch_rows<BLS_FP16>(ctx, vb, lanes, ridx, rw, segoff, nnz, Y, to_slot, st)
+                                      : dispatch_rows<BLS_FP32>(ctx, vb, lanes, ridx, rw, segoff, nnz, Y, to_slot, st);
     }
     if (!done) {
         dim3 grid((unsigned)((ctx->B + kThreads / 64 - 1) / (kThreads / 64)), ctx->Q);

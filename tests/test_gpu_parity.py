@@ -99,7 +99,9 @@ EDGE = [
     dict(P=2, T=2, D=320, B=40, part_kind=1, rows=[500, 333], bag=("uniform", 0, 20)),       # rows > 1 KB
     dict(P=8, T=2, D=128, B=300, part_kind=1, rows=[4097, 1000], bag=("uniform", 0, 200)),   # long bags over 8 owners
     dict(P=64, T=2, D=8, B=130, part_kind=1, rows=[5000, 129], bag=("uniform", 0, 90)),      # maximum P
-    dict(P=5, T=7, D=64, B=5000, part_kind=0, rows=[1000] * 7, bag=("uniform", 0, 3)),       # several scan blocks
+    dict(P=5, T=7, D=64, B=5000, part_kind=0, rows=[1000] * 7, bag=("uniform", 0, 3)),       # several scan tiles, one workgroup
+    dict(P=4, T=16, D=8, B=2000, part_kind=1, rows=[300] * 16, bag=("uniform", 0, 3)),       # 32 scan tiles: multi-block scan
+    dict(P=3, T=40, D=4, B=3001, part_kind=0, rows=[64] * 40, bag=("uniform", 0, 2)),        # 30 scan tiles, table-wise
 ]
 
 
@@ -236,13 +238,11 @@ def test_host_side_argument_errors():
     assert e.value.code == B.BLS_EINVAL
 
 
-@pytest.mark.parametrize("vb,unroll,nb,xcd", [(16, 8, 1, 0), (16, 4, 3, 1), (16, 16, 16, 0), (8, 8, 0, 1), (8, 4, 7, 0),
-                                              (4, 8, 0, 0), (4, 16, 2, 1)])
-def test_pool_launch_variants(vb, unroll, nb, xcd, monkeypatch):
-    """The tuning overrides pick other lane widths, unroll depths and segments per group;
-    every variant must give the same bits."""
+@pytest.mark.parametrize("vb,nb,xcd", [(16, 1, 0), (16, 3, 1), (16, 16, 0), (8, 0, 1), (8, 7, 0), (4, 0, 0), (4, 2, 1)])
+def test_pool_launch_variants(vb, nb, xcd, monkeypatch):
+    """The overrides pick other lane widths, segments per group, grid mappings and row-position
+    widths; every variant must give the same bits."""
     monkeypatch.setenv("BLS_POOL_VB", str(vb))
-    monkeypatch.setenv("BLS_POOL_U", str(unroll))
     monkeypatch.setenv("BLS_POOL_XCD", str(xcd))
     monkeypatch.setenv("BLS_POOL_WIDE", str(1 - xcd))
     if nb:
