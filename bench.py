@@ -92,6 +92,8 @@ def main() -> int:
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="CPU time to spend on the oracle baseline")
     ap.add_argument("--index-dist", default=None, choices=[None, "uniform"],
                     help="cache-defeating control: uniform indices instead of the workload's law")
+    ap.add_argument("--timed-only", action="store_true",
+                    help="only the warm-up and the timed staged steps (for profiler runs: no fused, ring or copy sections)")
     ap.add_argument("--bag-fixed", type=int, default=0, help="experiment: every bag has this many lookups")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -165,69 +167,71 @@ def main() -> int:
     c.bls_check()
     note(f"{args.steps} timed steps: {dt / args.steps * 1e3:.3f} ms per step")
 
-    # achievable ceiling for the permute stages: a plain device copy of one pooled buffer
-    cp = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
-    pipe.send.copy_(pipe.pooled)
-    cp[0].record()
-    for _ in range(10):
+    copy_gbps = dtf = dtr = fused_lookups = None
+    if not args.timed_only:
+        # achievable ceiling for the permute stages: a plain device copy of one pooled buffer
+        cp = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
         pipe.send.copy_(pipe.pooled)
-    cp[1].record()
-    torch.cuda.synchronize()
-    copy_gbps = 2 * pipe.pooled.numel() * 4 / (cp[0].elapsed_time(cp[1]) / 10 * 1e-3) / 1e9
+        cp[0].record()
+        for _ in range(10):
+            pipe.send.copy_(pipe.pooled)
+        cp[1].record()
+        torch.cuda.synchronize()
+        copy_gbps = 2 * pipe.pooled.numel() * 4 / (cp[0].elapsed_time(cp[1]) / 10 * 1e-3) / 1e9
 
-    # the same work with the owner side fused (bls_embbag_pool_put: no pooled or send buffer);
-    # reported beside the staged path, never as `value`
-    def fused_step(i: int):
-        ix, off = batches[i % len(batches)]
-        nnz = nnzs[i % len(batches)]
-        c.bls_plan(ix, off, nnz, pipe.sendcounts, pipe.sdispls, pipe.recvcounts, pipe.rdispls,
-                   pipe.ridx, pipe.segoff, None, pipe.ws)
-        it, slot = c.bls_ring_advance()
-        c.bls_embbag_pool_put(pipe.ridx, pipe.segoff, nnz, slot)
-        c.bls_unpack(it, out)
-        return nnz
+        # the same work with the owner side fused (bls_embbag_pool_put: no pooled or send buffer);
+        # reported beside the staged path, never as `value`
+        def fused_step(i: int):
+            ix, off = batches[i % len(batches)]
+            nnz = nnzs[i % len(batches)]
+            c.bls_plan(ix, off, nnz, pipe.sendcounts, pipe.sdispls, pipe.recvcounts, pipe.rdispls,
+                       pipe.ridx, pipe.segoff, None, pipe.ws)
+            it, slot = c.bls_ring_advance()
+            c.bls_embbag_pool_put(pipe.ridx, pipe.segoff, nnz, slot)
+            c.bls_unpack(it, out)
+            return nnz
 
-    for i in range(args.warmup):
-        fused_step(i)
-    torch.cuda.synchronize()
-    tf = time.perf_counter()
-    fused_lookups = 0
-    for i in range(args.steps):
-        fused_lookups += fused_step(args.warmup + i)
-    torch.cuda.synchronize()
-    dtf = time.perf_counter() - tf
-    c.bls_check()
-    note(f"{args.steps} fused steps: {dtf / args.steps * 1e3:.3f} ms per step")
+        for i in range(args.warmup):
+            fused_step(i)
+        torch.cuda.synchronize()
+        tf = time.perf_counter()
+        fused_lookups = 0
+        for i in range(args.steps):
+            fused_lookups += fused_step(args.warmup + i)
+        torch.cuda.synchronize()
+        dtf = time.perf_counter() - tf
+        c.bls_check()
+        note(f"{args.steps} fused steps: {dtf / args.steps * 1e3:.3f} ms per step")
 
-    # the ring at work: K-1 iterations stay in flight, completion runs on a second stream
-    side = torch.cuda.Stream()
-    outs = [pipe.new_out() for _ in range(c.K)]
+        # the ring at work: K-1 iterations stay in flight, completion runs on a second stream
+        side = torch.cuda.Stream()
+        outs = [pipe.new_out() for _ in range(c.K)]
 
-    def issue(i: int):
-        ix, off = batches[i % len(batches)]
-        nnz = nnzs[i % len(batches)]
-        c.bls_plan(ix, off, nnz, pipe.sendcounts, pipe.sdispls, pipe.recvcounts, pipe.rdispls,
-                   pipe.ridx, pipe.segoff, None, pipe.ws)
-        c.bls_embbag_pool(pipe.ridx, pipe.segoff, nnz, pipe.pooled)
-        c.bls_pack(pipe.pooled, pipe.send)
-        it, slot = c.bls_ring_advance()
-        c.bls_alltoallv_local(pipe.send, slot)
-        return it
+        def issue(i: int):
+            ix, off = batches[i % len(batches)]
+            nnz = nnzs[i % len(batches)]
+            c.bls_plan(ix, off, nnz, pipe.sendcounts, pipe.sdispls, pipe.recvcounts, pipe.rdispls,
+                       pipe.ridx, pipe.segoff, None, pipe.ws)
+            c.bls_embbag_pool(pipe.ridx, pipe.segoff, nnz, pipe.pooled)
+            c.bls_pack(pipe.pooled, pipe.send)
+            it, slot = c.bls_ring_advance()
+            c.bls_alltoallv_local(pipe.send, slot)
+            return it
 
-    torch.cuda.synchronize()
-    tr = time.perf_counter()
-    flying = []
-    for i in range(args.steps):
-        if len(flying) == c.K:
-            j = flying.pop(0)
+        torch.cuda.synchronize()
+        tr = time.perf_counter()
+        flying = []
+        for i in range(args.steps):
+            if len(flying) == c.K:
+                j = flying.pop(0)
+                c.bls_unpack(j, outs[j % c.K], side)
+            flying.append(issue(i))
+        for j in flying:
             c.bls_unpack(j, outs[j % c.K], side)
-        flying.append(issue(i))
-    for j in flying:
-        c.bls_unpack(j, outs[j % c.K], side)
-    torch.cuda.synchronize()
-    dtr = time.perf_counter() - tr
-    c.bls_check()
-    note(f"{args.steps} steps with up to {c.K} iterations in flight: {dtr / args.steps * 1e3:.3f} ms per step")
+        torch.cuda.synchronize()
+        dtr = time.perf_counter() - tr
+        c.bls_check()
+        note(f"{args.steps} steps with up to {c.K} iterations in flight: {dtr / args.steps * 1e3:.3f} ms per step")
 
     stage_ms = {n: sum(e[k].elapsed_time(e[k + 1]) for e in events) / args.steps for k, n in enumerate(names)}
     mean_nnz = lookups / args.steps
@@ -255,10 +259,12 @@ def main() -> int:
                      "pool_plus_pack_frac_of_peak": pool_pack_gbps / PEAK_HBM_GBPS},
         "stage_ms": stage_ms,
         "stage_gbps": {n: sb[n] / (stage_ms[n] * 1e-3) / 1e9 for n in names},
-        "fused_owner_side": {"entry_point": "bls_plan + bls_embbag_pool_put + bls_unpack", "ms_per_step": dtf / args.steps * 1e3,
-                             "lookups_per_s": fused_lookups / dtf},
-        "ring_in_flight": {"K": c.K, "ms_per_step": dtr / args.steps * 1e3,
-                           "note": "staged path, completion deferred K-1 iterations on a second stream"},
+        "fused_owner_side": None if dtf is None else {
+            "entry_point": "bls_plan + bls_embbag_pool_put + bls_unpack", "ms_per_step": dtf / args.steps * 1e3,
+            "lookups_per_s": fused_lookups / dtf},
+        "ring_in_flight": None if dtr is None else {
+            "K": c.K, "ms_per_step": dtr / args.steps * 1e3,
+            "note": "staged path, completion deferred K-1 iterations on a second stream"},
         "bucket_pool_pack": {"ms": stage_ms["plan"] + stage_ms["pool"] + stage_ms["pack"],
                              "lookups_per_s": mean_nnz / ((stage_ms["plan"] + stage_ms["pool"] + stage_ms["pack"]) * 1e-3)},
         "plain_copy_gbps": copy_gbps,
