@@ -187,6 +187,35 @@ int bls_unpack(bls_ctx *ctx, int64_t iter, float *d_out, void *hip_stream);
  * d_offsets is the iteration's offsets array, device memory. */
 int bls_unpack_mean(bls_ctx *ctx, int64_t iter, const int64_t *d_offsets, float *d_out, void *hip_stream);
 
+/*
+ * Per-rank issue and completion: the work of bls_embbag_pool_put and bls_unpack split by
+ * rank, so that every simulated rank can run on a stream of its own and fall behind the others
+ * by up to K iterations (section "Bound": the fastest and the slowest process are at most
+ * k iterations apart; Listing 2: the loop that keeps up to `bound` requests unfinished).
+ *
+ * bls_rank_put: owner `rank` pools its local tables (or shards) for every requester and puts the
+ *   vectors into R(*, iter mod K) - the puts of Alltoallv initiation.  `iter` must be this
+ *   rank's next iteration (0, 1, 2, ...).  The call makes the stream wait until every requester
+ *   has copied iteration iter - K out of the slot, and records the arrival of this owner's
+ *   blocks (one event per slot and owner: the role of the paper's tag counters).  BLS_ERING_FULL
+ *   if some requester has not yet been asked to complete iteration iter - K.  d_rweights may
+ *   be NULL (no per-sample weights).  d_ridx / d_segoff as produced by bls_plan for that iteration.
+ * bls_rank_complete: requester `rank` completes its oldest iteration `iter`: the stream waits
+ *   for the arrival of all P owners' blocks (every owner must already have been asked to put
+ *   `iter`, else BLS_EORDER), then rows [first(rank), first(rank+1)) of d_out[B][T][D] are
+ *   written (divided by the bag length if d_mean_offsets is not NULL) and the rank's share of
+ *   the slot is released.
+ * Do not interleave these with bls_ring_advance / bls_unpack while iterations are in flight, and let the
+ * device go idle (bls_check) before switching from one style to the other: the two keep separate events.
+ * bls_rank_delay keeps a stream busy for about `microseconds` (at most 1 s; a bounded sleep
+ * loop in one lane): the injected delays of the paper's Setting 2, for experiments.
+ */
+int bls_rank_put(bls_ctx *ctx, int32_t rank, const int64_t *d_ridx, const float *d_rweights, const int64_t *d_segoff,
+                 int64_t nnz, int64_t iter, void *hip_stream);
+int bls_rank_complete(bls_ctx *ctx, int32_t rank, int64_t iter, const int64_t *d_mean_offsets, float *d_out,
+                      void *hip_stream);
+int bls_rank_delay(bls_ctx *ctx, uint32_t microseconds, void *hip_stream);
+
 /* Ring state for callers and tests: next iteration number, oldest in flight, K. */
 int bls_ring_state(const bls_ctx *ctx, int64_t *head, int64_t *tail, int32_t *K);
 

@@ -22,7 +22,7 @@ EXPORTS = [
     "bls_create", "bls_destroy", "bls_set_shard", "bls_sizes", "bls_pooled_counts", "bls_plan", "bls_plan_weighted",
     "bls_embbag_pool", "bls_embbag_pool_weighted", "bls_embbag_pool_put", "bls_embbag_pool_put_weighted", "bls_pack",
     "bls_set_ring", "bls_ring_advance", "bls_alltoallv_local", "bls_unpack", "bls_unpack_mean", "bls_ring_state",
-    "bls_check", "bls_last_error",
+    "bls_rank_put", "bls_rank_complete", "bls_rank_delay", "bls_check", "bls_last_error",
 ]
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
@@ -61,6 +61,9 @@ def lib() -> C.CDLL:
         L.bls_embbag_pool_weighted.argtypes = [vp, i64p, vp, i64p, C.c_int64, vp, vp]
         L.bls_embbag_pool_put_weighted.argtypes = [vp, i64p, vp, i64p, C.c_int64, C.c_int32, vp]
         L.bls_unpack_mean.argtypes = [vp, C.c_int64, i64p, vp, vp]
+        L.bls_rank_put.argtypes = [vp, C.c_int32, i64p, vp, i64p, C.c_int64, C.c_int64, vp]
+        L.bls_rank_complete.argtypes = [vp, C.c_int32, C.c_int64, i64p, vp, vp]
+        L.bls_rank_delay.argtypes = [vp, C.c_uint32, vp]
         L.bls_embbag_pool_put.argtypes = [vp, i64p, i64p, C.c_int64, C.c_int32, vp]
         L.bls_pack.argtypes = [vp, vp, vp, vp]
         L.bls_set_ring.argtypes = [vp, vp, C.c_size_t]
@@ -200,6 +203,15 @@ class Context:
 
     def bls_unpack(self, it, out, stream=None):
         self._call("bls_unpack", int(it), _ptr(out), _stream(stream))
+
+    def bls_rank_put(self, rank, ridx, rweights, segoff, nnz, it, stream=None):
+        self._call("bls_rank_put", int(rank), _ptr(ridx), _ptr(rweights), _ptr(segoff), int(nnz), int(it), _stream(stream))
+
+    def bls_rank_complete(self, rank, it, mean_offsets, out, stream=None):
+        self._call("bls_rank_complete", int(rank), int(it), _ptr(mean_offsets), _ptr(out), _stream(stream))
+
+    def bls_rank_delay(self, microseconds, stream=None):
+        self._call("bls_rank_delay", int(microseconds), _stream(stream))
 
     def bls_ring_state(self):
         h, t, k = C.c_int64(), C.c_int64(), C.c_int32()

@@ -93,6 +93,8 @@ extern "C" int bls_destroy(bls_ctx *ctx)
                 if (r.filled) (void)hipEventDestroy(r.filled);
                 if (r.released) (void)hipEventDestroy(r.released);
             }
+            for (auto e : ctx->rr.arrived) if (e) (void)hipEventDestroy(e);
+            for (auto e : ctx->rr.released) if (e) (void)hipEventDestroy(e);
             if (ctx->blob) { (void)hipDeviceSynchronize(); (void)hipFree(ctx->blob); }
             if (cur != ctx->device) (void)hipSetDevice(cur);
         }
@@ -252,7 +254,7 @@ static int pool_common(bls_ctx *ctx, const int64_t *d_ridx, const float *d_rweig
     if (((uintptr_t)d_pooled & 15u) != 0) return bls_fail(ctx, BLS_EINVAL, "bls_embbag_pool: output must be 16-byte aligned");
     int rc = bls_commit(ctx);
     if (rc) return rc;
-    return bls_launch_pool(ctx, d_ridx, d_rweights, d_segoff, nnz, d_pooled, 0, (hipStream_t)hip_stream);
+    return bls_launch_pool(ctx, d_ridx, d_rweights, d_segoff, nnz, d_pooled, 0, 0, ctx->Q, (hipStream_t)hip_stream);
 }
 
 extern "C" int bls_embbag_pool(bls_ctx *ctx, const int64_t *d_ridx, const int64_t *d_segoff, int64_t nnz,
@@ -305,6 +307,9 @@ extern "C" int bls_ring_advance(bls_ctx *ctx, int64_t *iter_out, int32_t *slot_o
 {
     if (!ctx || !iter_out || !slot_out) return BLS_EINVAL;
     if (ctx->head - ctx->tail >= ctx->K) return bls_fail(ctx, BLS_ERING_FULL, "bls_ring_advance: K iterations in flight");
+    for (int r = 0; r < (int)ctx->rr.put_next.size(); ++r)
+        if (ctx->rr.put_next[r] != ctx->rr.done_next[r] || ctx->rr.put_next[r] != ctx->rr.put_next[0])
+            return bls_fail(ctx, BLS_EORDER, "bls_ring_advance: per-rank iterations are in flight on this context");
     const int64_t j = ctx->head;
     const int slot = (int)(j % ctx->K);
     RingSlot &r = ctx->ring[slot];
@@ -366,7 +371,7 @@ static int put_common(bls_ctx *ctx, const int64_t *d_ridx, const float *d_rweigh
     int rc = slot_to_fill(ctx, slot, "bls_embbag_pool_put", &r);
     if (rc) return rc;
     rc = bls_launch_pool(ctx, d_ridx, d_rweights, d_segoff, nnz, (float *)(ctx->slots + (size_t)slot * ctx->slot_bytes), 1,
-                         (hipStream_t)hip_stream);
+                         0, ctx->Q, (hipStream_t)hip_stream);
     if (rc) return rc;
     BLS_HIP(ctx, hipEventRecord(r->filled, (hipStream_t)hip_stream));
     r->state = 2;
@@ -399,8 +404,8 @@ static int unpack_common(bls_ctx *ctx, int64_t iter, const int64_t *mean_off, fl
     int rc = bls_commit(ctx);
     if (rc) return rc;
     BLS_HIP(ctx, hipStreamWaitEvent((hipStream_t)hip_stream, r.filled, 0));
-    rc = bls_launch_unpack(ctx, (const float *)(ctx->slots + (size_t)slot * ctx->slot_bytes), d_out, mean_off,
-                           (hipStream_t)hip_stream);
+    rc = bls_launch_unpack(ctx, (const float *)(ctx->slots + (size_t)slot * ctx->slot_bytes), d_out, mean_off, 0u,
+                           (uint32_t)ctx->B, (hipStream_t)hip_stream);
     if (rc) return rc;
     BLS_HIP(ctx, hipEventRecord(r.released, (hipStream_t)hip_stream));
     r.has_released = true;
@@ -420,6 +425,88 @@ extern "C" int bls_unpack_mean(bls_ctx *ctx, int64_t iter, const int64_t *d_offs
     if (!ctx) return BLS_EINVAL;
     if (!d_offsets) return bls_fail(ctx, BLS_EINVAL, "bls_unpack_mean: NULL offsets");
     return unpack_common(ctx, iter, d_offsets, d_out, hip_stream);
+}
+
+// ---- per-rank issue and completion -----------------------------------------------------------
+
+static int rank_ring_init(bls_ctx *ctx)
+{
+    RankRing &rr = ctx->rr;
+    if (!rr.arrived.empty()) return BLS_OK;
+    const size_t n = (size_t)ctx->K * ctx->P;
+    rr.put_next.assign(ctx->P, 0);
+    rr.done_next.assign(ctx->P, 0);
+    rr.arrived.assign(n, nullptr);
+    rr.released.assign(n, nullptr);
+    rr.has_arrived.assign(n, 0);
+    rr.has_released.assign(n, 0);
+    for (size_t i = 0; i < n; ++i) {
+        BLS_HIP(ctx, hipEventCreateWithFlags(&rr.arrived[i], hipEventDisableTiming));
+        BLS_HIP(ctx, hipEventCreateWithFlags(&rr.released[i], hipEventDisableTiming));
+    }
+    return BLS_OK;
+}
+
+extern "C" int bls_rank_put(bls_ctx *ctx, int32_t rank, const int64_t *d_ridx, const float *d_rweights,
+                            const int64_t *d_segoff, int64_t nnz, int64_t iter, void *hip_stream)
+{
+    if (!ctx) return BLS_EINVAL;
+    if (rank < 0 || rank >= ctx->P) return bls_fail(ctx, BLS_EINVAL, "bls_rank_put: rank out of range");
+    if (nnz < 0 || !d_segoff || (nnz > 0 && !d_ridx)) return bls_fail(ctx, BLS_EINVAL, "bls_rank_put: NULL argument");
+    if (!ctx->slots) return bls_fail(ctx, BLS_EINVAL, "bls_rank_put: no ring (bls_set_ring)");
+    if (ctx->head != ctx->tail) return bls_fail(ctx, BLS_EORDER, "bls_rank_put: whole-batch iterations are in flight on this context");
+    int rc = bls_commit(ctx);
+    if (rc) return rc;
+    rc = rank_ring_init(ctx);
+    if (rc) return rc;
+    RankRing &rr = ctx->rr;
+    if (iter != rr.put_next[rank]) return bls_fail(ctx, BLS_EORDER, "bls_rank_put: not this rank's next iteration");
+    // the slot is free again only when every requester has copied iteration iter - K out of it
+    for (int s = 0; s < ctx->P; ++s)
+        if (iter - rr.done_next[s] >= ctx->K) return bls_fail(ctx, BLS_ERING_FULL, "bls_rank_put: a requester still holds the slot");
+    const int slot = (int)(iter % ctx->K);
+    hipStream_t st = (hipStream_t)hip_stream;
+    for (int s = 0; s < ctx->P; ++s)
+        if (rr.has_released[(size_t)slot * ctx->P + s]) BLS_HIP(ctx, hipStreamWaitEvent(st, rr.released[(size_t)slot * ctx->P + s], 0));
+    rc = bls_launch_pool(ctx, d_ridx, nnz > 0 ? d_rweights : nullptr, d_segoff, nnz,
+                         (float *)(ctx->slots + (size_t)slot * ctx->slot_bytes), 1, ctx->nsum[rank], ctx->n_loc[rank], st);
+    if (rc) return rc;
+    BLS_HIP(ctx, hipEventRecord(rr.arrived[(size_t)slot * ctx->P + rank], st));
+    rr.has_arrived[(size_t)slot * ctx->P + rank] = 1;
+    rr.put_next[rank] = iter + 1;
+    return BLS_OK;
+}
+
+extern "C" int bls_rank_complete(bls_ctx *ctx, int32_t rank, int64_t iter, const int64_t *d_mean_offsets, float *d_out,
+                                 void *hip_stream)
+{
+    if (!ctx) return BLS_EINVAL;
+    if (rank < 0 || rank >= ctx->P) return bls_fail(ctx, BLS_EINVAL, "bls_rank_complete: rank out of range");
+    if (!d_out || ((uintptr_t)d_out & 15u) != 0) return bls_fail(ctx, BLS_EINVAL, "bls_rank_complete: NULL or misaligned output");
+    RankRing &rr = ctx->rr;
+    if (rr.arrived.empty()) return bls_fail(ctx, BLS_ERING_EMPTY, "bls_rank_complete: nothing in flight");
+    if (iter != rr.done_next[rank]) return bls_fail(ctx, BLS_EORDER, "bls_rank_complete: not this rank's oldest iteration");
+    for (int d = 0; d < ctx->P; ++d)
+        if (rr.put_next[d] <= iter)
+            return bls_fail(ctx, BLS_EORDER, "bls_rank_complete: an owner has not issued this iteration yet");
+    const int slot = (int)(iter % ctx->K);
+    hipStream_t st = (hipStream_t)hip_stream;
+    // completion = the blocks of all P owners have arrived (the paper polls a tag counter for this)
+    for (int d = 0; d < ctx->P; ++d) BLS_HIP(ctx, hipStreamWaitEvent(st, rr.arrived[(size_t)slot * ctx->P + d], 0));
+    int rc = bls_launch_unpack(ctx, (const float *)(ctx->slots + (size_t)slot * ctx->slot_bytes), d_out, d_mean_offsets,
+                               (uint32_t)ctx->first[rank], (uint32_t)(ctx->first[rank + 1] - ctx->first[rank]), st);
+    if (rc) return rc;
+    BLS_HIP(ctx, hipEventRecord(rr.released[(size_t)slot * ctx->P + rank], st));
+    rr.has_released[(size_t)slot * ctx->P + rank] = 1;
+    rr.done_next[rank] = iter + 1;
+    return BLS_OK;
+}
+
+extern "C" int bls_rank_delay(bls_ctx *ctx, uint32_t microseconds, void *hip_stream)
+{
+    if (!ctx) return BLS_EINVAL;
+    if (microseconds > 1000000u) return bls_fail(ctx, BLS_EINVAL, "bls_rank_delay: at most one second");
+    return bls_launch_delay(ctx, microseconds, (hipStream_t)hip_stream);
 }
 
 extern "C" int bls_check(bls_ctx *ctx, void *hip_stream)

@@ -37,6 +37,15 @@ struct DevDesc {
     int32_t *err;                // error flag, set to 1 by kernels that skip a bad item
 };
 
+// Per-rank issue and completion (bls_rank_put / bls_rank_complete): every rank has its own
+// iteration counters, and every slot one arrival event per owner and one release event per
+// requester - the arrival events play the part of the paper's per-iteration tag counters.
+struct RankRing {
+    std::vector<int64_t> put_next, done_next;     // [P] next iteration rank r puts / completes
+    std::vector<hipEvent_t> arrived, released;    // [K*P] slot-major
+    std::vector<uint8_t> has_arrived, has_released;
+};
+
 struct RingSlot {
     int state = 0;               // 0 free, 1 acquired (exchange not yet enqueued), 2 filled
     int64_t iter = -1;
@@ -67,6 +76,7 @@ struct bls_ctx {
     size_t slot_bytes = 0;
     int64_t head = 0, tail = 0;   // next iteration to start, oldest in flight
     std::vector<RingSlot> ring;
+    RankRing rr;
 
     std::string err;
 };
@@ -88,13 +98,15 @@ int bls_launch_plan(bls_ctx *ctx, const int64_t *idx, const int64_t *off, int64_
                     int64_t *perm, const float *w_in, float *w_out, void *ws, size_t ws_bytes, hipStream_t st);
 size_t bls_plan_ws_bytes(const bls_ctx *ctx);
 // to_slot = 0: Y in pooled order (y); 1: Y is a ring slot, vectors go to receive order (rho)
-// rw: weight of every lookup in ridx order, or NULL
+// rw: weight of every lookup in ridx order, or NULL; (owner, table) pairs q0 .. q0+qn-1 only
 int bls_launch_pool(bls_ctx *ctx, const int64_t *ridx, const float *rw, const int64_t *segoff, int64_t nnz, float *Y,
-                    int to_slot, hipStream_t st);
+                    int to_slot, int q0, int qn, hipStream_t st);
 int bls_launch_pack(bls_ctx *ctx, const float *Y, float *S, hipStream_t st);
 int bls_launch_exchange(bls_ctx *ctx, const float *S, float *R, hipStream_t st);
-// mean_off: the batch's offsets for mean pooling (divide by the bag length), or NULL
-int bls_launch_unpack(bls_ctx *ctx, const float *R, float *out, const int64_t *mean_off, hipStream_t st);
+// mean_off: the batch's offsets for mean pooling (divide by the bag length), or NULL; samples b0 .. b0+bn-1 only
+int bls_launch_unpack(bls_ctx *ctx, const float *R, float *out, const int64_t *mean_off, uint32_t b0, uint32_t bn,
+                      hipStream_t st);
+int bls_launch_delay(bls_ctx *ctx, uint32_t microseconds, hipStream_t st);
 
 // ---- device helpers ----------------------------------------------------------------
 #ifdef __HIPCC__

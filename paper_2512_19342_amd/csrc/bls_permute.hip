@@ -34,14 +34,14 @@ __device__ __forceinline__ float bag_divisor(const DevDesc &dd, const int64_t *o
 template <int MODE, class V>
 __global__ __launch_bounds__(kThreads) void move_vectors(DevDesc dd, const float *__restrict__ src,
                                                          float *__restrict__ dst, int lg,
-                                                         const int64_t *__restrict__ mean_off)
+                                                         const int64_t *__restrict__ mean_off, uint32_t b0, uint32_t bn)
 {
     constexpr int VEC = sizeof(V) / sizeof(float);
     const int G = 1 << lg;
     const int q = blockIdx.y;
     const int li = threadIdx.x & (G - 1);
-    const uint32_t b = blockIdx.x * (uint32_t)(kThreads >> lg) + (threadIdx.x >> lg);
-    if (b >= (uint32_t)dd.B) return;
+    const uint32_t b = b0 + blockIdx.x * (uint32_t)(kThreads >> lg) + (threadIdx.x >> lg);   // samples b0 .. b0+bn-1
+    if (b >= b0 + bn) return;
     int s; uint32_t b_loc, n;
     bls_split_sample(dd, b, s, b_loc, n);
     int64_t from, to;
@@ -76,14 +76,14 @@ __device__ __forceinline__ void vzero(float &a) { a = 0.f; }
 template <class V>
 __global__ __launch_bounds__(kThreads) void unpack_rowwise(DevDesc dd, const float *__restrict__ R,
                                                            float *__restrict__ out, int lg,
-                                                           const int64_t *__restrict__ mean_off)
+                                                           const int64_t *__restrict__ mean_off, uint32_t b0, uint32_t bn)
 {
     constexpr int VEC = sizeof(V) / sizeof(float);
     const int G = 1 << lg;
     const int t = blockIdx.y;
     const int li = threadIdx.x & (G - 1);
-    const uint32_t b = blockIdx.x * (uint32_t)(kThreads >> lg) + (threadIdx.x >> lg);
-    if (b >= (uint32_t)dd.B) return;
+    const uint32_t b = b0 + blockIdx.x * (uint32_t)(kThreads >> lg) + (threadIdx.x >> lg);
+    if (b >= b0 + bn) return;
     int s; uint32_t b_loc, n;
     bls_split_sample(dd, b, s, b_loc, n);
     V *__restrict__ pd = reinterpret_cast<V *>(out + ((int64_t)b * dd.T + t) * dd.D);
@@ -102,40 +102,64 @@ __global__ __launch_bounds__(kThreads) void unpack_rowwise(DevDesc dd, const flo
 }
 
 template <int MODE>
-int launch_move(bls_ctx *ctx, const float *src, float *dst, const int64_t *mean_off, hipStream_t st)
+int launch_move(bls_ctx *ctx, const float *src, float *dst, const int64_t *mean_off, uint32_t b0, uint32_t bn, hipStream_t st)
 {
+    if (bn == 0) return BLS_OK;
     const bool vec = ctx->D % 4 == 0;
     const int g = lanes_for(vec ? ctx->D / 4 : ctx->D);
     int lg = 0;
     while ((1 << lg) < g) ++lg;
     const uint32_t per_block = kThreads >> lg;
-    dim3 grid((unsigned)((ctx->B + per_block - 1) / per_block), ctx->Q);
-    if (vec) move_vectors<MODE, float4><<<grid, kThreads, 0, st>>>(ctx->desc, src, dst, lg, mean_off);
-    else move_vectors<MODE, float><<<grid, kThreads, 0, st>>>(ctx->desc, src, dst, lg, mean_off);
+    dim3 grid((unsigned)((bn + per_block - 1) / per_block), ctx->Q);
+    if (vec) move_vectors<MODE, float4><<<grid, kThreads, 0, st>>>(ctx->desc, src, dst, lg, mean_off, b0, bn);
+    else move_vectors<MODE, float><<<grid, kThreads, 0, st>>>(ctx->desc, src, dst, lg, mean_off, b0, bn);
     BLS_HIP(ctx, hipGetLastError());
     return BLS_OK;
 }
 
+// Keeps a stream busy for about `ticks` of the constant-rate wall clock (a modelled straggler).
+// One lane sleeps in short naps; the loop is bounded, so the kernel always ends.
+__global__ void delay_kernel(unsigned long long ticks, unsigned int max_naps)
+{
+    const unsigned long long t0 = wall_clock64();
+    for (unsigned int i = 0; i < max_naps && wall_clock64() - t0 < ticks; ++i) __builtin_amdgcn_s_sleep(16);
+}
+
 }  // namespace
 
-int bls_launch_pack(bls_ctx *ctx, const float *Y, float *S, hipStream_t st) { return launch_move<kPack>(ctx, Y, S, nullptr, st); }
+int bls_launch_delay(bls_ctx *ctx, uint32_t microseconds, hipStream_t st)
+{
+    int dev = 0, khz = 0;
+    BLS_HIP(ctx, hipGetDevice(&dev));
+    BLS_HIP(ctx, hipDeviceGetAttribute(&khz, hipDeviceAttributeWallClockRate, dev));
+    if (khz <= 0) khz = 100000;                               // 100 MHz
+    const unsigned long long ticks = (unsigned long long)microseconds * (unsigned long long)khz / 1000ull;
+    // a nap is at least 16 * 64 clocks; 64 naps per microsecond asked for is far more than needed
+    delay_kernel<<<1, 1, 0, st>>>(ticks, microseconds * 64u + 1024u);
+    BLS_HIP(ctx, hipGetLastError());
+    return BLS_OK;
+}
+
+int bls_launch_pack(bls_ctx *ctx, const float *Y, float *S, hipStream_t st) { return launch_move<kPack>(ctx, Y, S, nullptr, 0u, (uint32_t)ctx->B, st); }
 
 int bls_launch_exchange(bls_ctx *ctx, const float *S, float *R, hipStream_t st)
 {
-    return launch_move<kExchange>(ctx, S, R, nullptr, st);
+    return launch_move<kExchange>(ctx, S, R, nullptr, 0u, (uint32_t)ctx->B, st);
 }
 
-int bls_launch_unpack(bls_ctx *ctx, const float *R, float *out, const int64_t *mean_off, hipStream_t st)
+int bls_launch_unpack(bls_ctx *ctx, const float *R, float *out, const int64_t *mean_off, uint32_t b0, uint32_t bn,
+                      hipStream_t st)
 {
-    if (ctx->part_kind == BLS_TABLE_WISE) return launch_move<kUnpackTable>(ctx, R, out, mean_off, st);
+    if (bn == 0) return BLS_OK;
+    if (ctx->part_kind == BLS_TABLE_WISE) return launch_move<kUnpackTable>(ctx, R, out, mean_off, b0, bn, st);
     const bool vec = ctx->D % 4 == 0;
     const int g = lanes_for(vec ? ctx->D / 4 : ctx->D);
     int lg = 0;
     while ((1 << lg) < g) ++lg;
     const uint32_t per_block = kThreads >> lg;
-    dim3 grid((unsigned)((ctx->B + per_block - 1) / per_block), ctx->T);
-    if (vec) unpack_rowwise<float4><<<grid, kThreads, 0, st>>>(ctx->desc, R, out, lg, mean_off);
-    else unpack_rowwise<float><<<grid, kThreads, 0, st>>>(ctx->desc, R, out, lg, mean_off);
+    dim3 grid((unsigned)((bn + per_block - 1) / per_block), ctx->T);
+    if (vec) unpack_rowwise<float4><<<grid, kThreads, 0, st>>>(ctx->desc, R, out, lg, mean_off, b0, bn);
+    else unpack_rowwise<float><<<grid, kThreads, 0, st>>>(ctx->desc, R, out, lg, mean_off, b0, bn);
     BLS_HIP(ctx, hipGetLastError());
     return BLS_OK;
 }

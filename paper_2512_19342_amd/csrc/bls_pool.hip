@@ -137,10 +137,10 @@ template <int G, int DT, int VB, int U>
 __global__ __launch_bounds__(kThreads) void pool_rows(DevDesc dd, const int64_t *__restrict__ ridx,
                                                       const float *__restrict__ rw,
                                                       const int64_t *__restrict__ segoff, int64_t nnz,
-                                                      float *__restrict__ Y, int to_slot)
+                                                      float *__restrict__ Y, int to_slot, int q0)
 {
     using A = Acc<DT, VB>;
-    const int q = blockIdx.y;
+    const int q = q0 + blockIdx.y;
     const int li = threadIdx.x & (G - 1);
     const int gbase = (threadIdx.x & 63) & ~(G - 1);
     const uint32_t b = blockIdx.x * (kThreads / G) + threadIdx.x / G;
@@ -209,18 +209,20 @@ template <int G, int DT, int VB, int U, bool WIDE, bool WGT>
 __global__ __launch_bounds__(kThreads) void pool_stream(DevDesc dd, const int64_t *__restrict__ ridx,
                                                         const float *__restrict__ rw,
                                                         const int64_t *__restrict__ segoff, int64_t nnz,
-                                                        float *__restrict__ Y, int to_slot, int nb_max, uint32_t chunks_per_s, uint32_t wgx)
+                                                        float *__restrict__ Y, int to_slot, int nb_max, uint32_t chunks_per_s, uint32_t wgx,
+                                                        int q0, int qn)
 {
     using A = Acc<DT, VB>;
     // wgx = 0: grid y = q.  Otherwise a flat grid dealt out so that the workgroups an XCD receives
     // (every eighth one) all belong to the same few tables: q = 8 * (round of tables) + XCD.
+    // Only the (owner, table) pairs q0 .. q0+qn-1 are worked on (all of them, or one owner's).
     uint32_t bx = blockIdx.x;
-    int q = blockIdx.y;
+    int q = q0 + blockIdx.y;
     if (wgx) {
         const uint32_t xcd = blockIdx.x & 7u, r = blockIdx.x >> 3;
-        q = (int)((r / wgx) * 8u + xcd);
+        q = q0 + (int)((r / wgx) * 8u + xcd);
         bx = r % wgx;
-        if (q >= dd.Q) return;
+        if (q >= q0 + qn) return;
     }
     const int lane = threadIdx.x & 63;
     const int li = lane & (G - 1);
@@ -350,9 +352,9 @@ template <int DT>
 __global__ __launch_bounds__(kThreads) void pool_rows_generic(DevDesc dd, const int64_t *__restrict__ ridx,
                                                               const float *__restrict__ rw,
                                                               const int64_t *__restrict__ segoff, int64_t nnz,
-                                                              float *__restrict__ Y, int to_slot)
+                                                              float *__restrict__ Y, int to_slot, int q0)
 {
-    const int q = blockIdx.y;
+    const int q = q0 + blockIdx.y;
     const int lane = threadIdx.x & 63;
     const uint32_t b = blockIdx.x * (kThreads / 64) + (threadIdx.x >> 6);
     if (b >= (uint32_t)dd.B) return;
@@ -385,7 +387,7 @@ int env_int(const char *name, int dflt)
 }
 
 template <int G, int DT, int VB, int U>
-void launch_rows(const bls_ctx *ctx, const int64_t *ridx, const float *rw, const int64_t *segoff, int64_t nnz, float *Y, int to_slot, hipStream_t st)
+void launch_rows(const bls_ctx *ctx, const int64_t *ridx, const float *rw, const int64_t *segoff, int64_t nnz, float *Y, int to_slot, int q0, int qn, hipStream_t st)
 {
     constexpr int UU = U < G ? U : G;
     const uint32_t per_block = kThreads / G;
@@ -401,49 +403,49 @@ void launch_rows(const bls_ctx *ctx, const int64_t *ridx, const float *rw, const
         const int64_t groups = (int64_t)chunks * ctx->P;
         const uint32_t wgx = (uint32_t)((groups + per_block - 1) / per_block);
         const bool xcd = env_int("BLS_POOL_XCD", 1) != 0;
-        const dim3 grid = xcd ? dim3((unsigned)((uint64_t)((ctx->Q + 7) / 8) * 8u * wgx)) : dim3(wgx, ctx->Q);
+        const dim3 grid = xcd ? dim3((unsigned)((uint64_t)((qn + 7) / 8) * 8u * wgx)) : dim3(wgx, qn);
         const uint32_t deal = xcd ? wgx : 0u;
         // 32-bit row positions unless some shard is too large for them
         const int64_t row_bytes = (int64_t)ctx->D * (DT == BLS_FP16 ? 2 : 4);
         bool wide = env_int("BLS_POOL_WIDE", 0) != 0;
-        for (int q = 0; q < ctx->Q; ++q) wide = wide || ctx->q_rows[q] * (row_bytes / VB) >= 0xffffffffLL;
+        for (int q = q0; q < q0 + qn; ++q) wide = wide || ctx->q_rows[q] * (row_bytes / VB) >= 0xffffffffLL;
         if (rw) {
-            if (wide) pool_stream<G, DT, VB, UU, true, true><<<grid, kThreads, 0, st>>>(ctx->desc, ridx, rw, segoff, nnz, Y, to_slot, nb, chunks, deal);
-            else pool_stream<G, DT, VB, UU, false, true><<<grid, kThreads, 0, st>>>(ctx->desc, ridx, rw, segoff, nnz, Y, to_slot, nb, chunks, deal);
+            if (wide) pool_stream<G, DT, VB, UU, true, true><<<grid, kThreads, 0, st>>>(ctx->desc, ridx, rw, segoff, nnz, Y, to_slot, nb, chunks, deal, q0, qn);
+            else pool_stream<G, DT, VB, UU, false, true><<<grid, kThreads, 0, st>>>(ctx->desc, ridx, rw, segoff, nnz, Y, to_slot, nb, chunks, deal, q0, qn);
         } else {
-            if (wide) pool_stream<G, DT, VB, UU, true, false><<<grid, kThreads, 0, st>>>(ctx->desc, ridx, rw, segoff, nnz, Y, to_slot, nb, chunks, deal);
-            else pool_stream<G, DT, VB, UU, false, false><<<grid, kThreads, 0, st>>>(ctx->desc, ridx, rw, segoff, nnz, Y, to_slot, nb, chunks, deal);
+            if (wide) pool_stream<G, DT, VB, UU, true, false><<<grid, kThreads, 0, st>>>(ctx->desc, ridx, rw, segoff, nnz, Y, to_slot, nb, chunks, deal, q0, qn);
+            else pool_stream<G, DT, VB, UU, false, false><<<grid, kThreads, 0, st>>>(ctx->desc, ridx, rw, segoff, nnz, Y, to_slot, nb, chunks, deal, q0, qn);
         }
     } else {
-        dim3 grid((unsigned)((ctx->B + per_block - 1) / per_block), ctx->Q);
-        pool_rows<G, DT, VB, UU><<<grid, kThreads, 0, st>>>(ctx->desc, ridx, rw, segoff, nnz, Y, to_slot);
+        dim3 grid((unsigned)((ctx->B + per_block - 1) / per_block), qn);
+        pool_rows<G, DT, VB, UU><<<grid, kThreads, 0, st>>>(ctx->desc, ridx, rw, segoff, nnz, Y, to_slot, q0);
     }
 }
 
 template <int DT, int VB, int U>
 bool dispatch_lanes(const bls_ctx *ctx, int lanes, const int64_t *ridx, const float *rw, const int64_t *segoff, int64_t nnz,
-                    float *Y, int to_slot, hipStream_t st)
+                    float *Y, int to_slot, int q0, int qn, hipStream_t st)
 {
     switch (lanes) {
-    case 1: if constexpr (VB == 16) { launch_rows<1, DT, VB, U>(ctx, ridx, rw, segoff, nnz, Y, to_slot, st); return true; } break;
-    case 2: if constexpr (VB == 16) { launch_rows<2, DT, VB, U>(ctx, ridx, rw, segoff, nnz, Y, to_slot, st); return true; } break;
-    case 4: if constexpr (VB == 16) { launch_rows<4, DT, VB, U>(ctx, ridx, rw, segoff, nnz, Y, to_slot, st); return true; } break;
-    case 8: if constexpr (VB == 16) { launch_rows<8, DT, VB, U>(ctx, ridx, rw, segoff, nnz, Y, to_slot, st); return true; } break;
-    case 16: if constexpr (VB >= 8) { launch_rows<16, DT, VB, U>(ctx, ridx, rw, segoff, nnz, Y, to_slot, st); return true; } break;
-    case 32: launch_rows<32, DT, VB, U>(ctx, ridx, rw, segoff, nnz, Y, to_slot, st); return true;
-    case 64: launch_rows<64, DT, VB, U>(ctx, ridx, rw, segoff, nnz, Y, to_slot, st); return true;
+    case 1: if constexpr (VB == 16) { launch_rows<1, DT, VB, U>(ctx, ridx, rw, segoff, nnz, Y, to_slot, q0, qn, st); return true; } break;
+    case 2: if constexpr (VB == 16) { launch_rows<2, DT, VB, U>(ctx, ridx, rw, segoff, nnz, Y, to_slot, q0, qn, st); return true; } break;
+    case 4: if constexpr (VB == 16) { launch_rows<4, DT, VB, U>(ctx, ridx, rw, segoff, nnz, Y, to_slot, q0, qn, st); return true; } break;
+    case 8: if constexpr (VB == 16) { launch_rows<8, DT, VB, U>(ctx, ridx, rw, segoff, nnz, Y, to_slot, q0, qn, st); return true; } break;
+    case 16: if constexpr (VB >= 8) { launch_rows<16, DT, VB, U>(ctx, ridx, rw, segoff, nnz, Y, to_slot, q0, qn, st); return true; } break;
+    case 32: launch_rows<32, DT, VB, U>(ctx, ridx, rw, segoff, nnz, Y, to_slot, q0, qn, st); return true;
+    case 64: launch_rows<64, DT, VB, U>(ctx, ridx, rw, segoff, nnz, Y, to_slot, q0, qn, st); return true;
     }
     return false;
 }
 
 template <int DT>
 bool dispatch_rows(const bls_ctx *ctx, int vb, int lanes, const int64_t *ridx, const float *rw,
-                   const int64_t *segoff, int64_t nnz, float *Y, int to_slot, hipStream_t st)
+                   const int64_t *segoff, int64_t nnz, float *Y, int to_slot, int q0, int qn, hipStream_t st)
 {
     switch (vb) {
-    case 16: return dispatch_lanes<DT, 16, kRowsInFlight>(ctx, lanes, ridx, rw, segoff, nnz, Y, to_slot, st);
-    case 8: return dispatch_lanes<DT, 8, kRowsInFlight>(ctx, lanes, ridx, rw, segoff, nnz, Y, to_slot, st);
-    case 4: return dispatch_lanes<DT, 4, kRowsInFlight>(ctx, lanes, ridx, rw, segoff, nnz, Y, to_slot, st);
+    case 16: return dispatch_lanes<DT, 16, kRowsInFlight>(ctx, lanes, ridx, rw, segoff, nnz, Y, to_slot, q0, qn, st);
+    case 8: return dispatch_lanes<DT, 8, kRowsInFlight>(ctx, lanes, ridx, rw, segoff, nnz, Y, to_slot, q0, qn, st);
+    case 4: return dispatch_lanes<DT, 4, kRowsInFlight>(ctx, lanes, ridx, rw, segoff, nnz, Y, to_slot, q0, qn, st);
     }
     return false;
 }
@@ -451,7 +453,7 @@ bool dispatch_rows(const bls_ctx *ctx, int vb, int lanes, const int64_t *ridx, c
 
 }  // namespace
 
-int bls_launch_pool(bls_ctx *ctx, const int64_t *ridx, const float *rw, const int64_t *segoff, int64_t nnz, float *Y, int to_slot, hipStream_t st)
+int bls_launch_pool(bls_ctx *ctx, const int64_t *ridx, const float *rw, const int64_t *segoff, int64_t nnz, float *Y, int to_slot, int q0, int qn, hipStream_t st)
 {
     const int64_t row_bytes = (int64_t)ctx->D * (ctx->dtype == BLS_FP16 ? 2 : 4);
     // bytes per lane and row: 16 when the row length allows; BLS_POOL_VB overrides (for tests)
@@ -463,13 +465,13 @@ int bls_launch_pool(bls_ctx *ctx, const int64_t *ridx, const float *rw, const in
     if (row_bytes % vb == 0 && row_bytes <= 64 * (int64_t)vb) {
         int lanes = 1;
         while ((int64_t)lanes * vb < row_bytes) lanes <<= 1;
-        done = ctx->dtype == BLS_FP16 ? dispatch_rows<BLS_FP16>(ctx, vb, lanes, ridx, rw, segoff, nnz, Y, to_slot, st)
-                                      : dispatch_rows<BLS_FP32>(ctx, vb, lanes, ridx, rw, segoff, nnz, Y, to_slot, st);
+        done = ctx->dtype == BLS_FP16 ? dispatch_rows<BLS_FP16>(ctx, vb, lanes, ridx, rw, segoff, nnz, Y, to_slot, q0, qn, st)
+                                      : dispatch_rows<BLS_FP32>(ctx, vb, lanes, ridx, rw, segoff, nnz, Y, to_slot, q0, qn, st);
     }
     if (!done) {
-        dim3 grid((unsigned)((ctx->B + kThreads / 64 - 1) / (kThreads / 64)), ctx->Q);
-        if (ctx->dtype == BLS_FP16) pool_rows_generic<BLS_FP16><<<grid, kThreads, 0, st>>>(ctx->desc, ridx, rw, segoff, nnz, Y, to_slot);
-        else pool_rows_generic<BLS_FP32><<<grid, kThreads, 0, st>>>(ctx->desc, ridx, rw, segoff, nnz, Y, to_slot);
+        dim3 grid((unsigned)((ctx->B + kThreads / 64 - 1) / (kThreads / 64)), qn);
+        if (ctx->dtype == BLS_FP16) pool_rows_generic<BLS_FP16><<<grid, kThreads, 0, st>>>(ctx->desc, ridx, rw, segoff, nnz, Y, to_slot, q0);
+        else pool_rows_generic<BLS_FP32><<<grid, kThreads, 0, st>>>(ctx->desc, ridx, rw, segoff, nnz, Y, to_slot, q0);
     }
     BLS_HIP(ctx, hipGetLastError());
     return BLS_OK;

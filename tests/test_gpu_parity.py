@@ -367,3 +367,72 @@ def test_weighted_and_mean_pooling(w):
         pipe.complete(j, out, mean_offsets=d_off)
         assert np.array_equal(bits(out.cpu().numpy()), bits(refm)), fused
     pipe.ctx.bls_check()
+
+
+@pytest.mark.parametrize("k", [0, 2, 4])
+@pytest.mark.parametrize("cfg", [3, 4, 6])
+def test_per_rank_issue_and_completion(k, cfg):
+    """Every simulated rank on its own stream, ranks served in a scrambled order, stragglers
+    delayed on the device: whatever the interleaving within the bound, every iteration's
+    output is the oracle's, bit for bit; the ring refuses what the bound forbids."""
+    import paper_2512_19342_amd as B
+    from paper_2512_19342_amd.runner import Pipeline
+    w = synth.workload(cfg, "small")
+    w.k = k
+    w.values = "gauss"
+    dev = torch.device("cuda:0")
+    tabs_cpu = [synth.make_table(w, t) for t in range(w.T)]
+    pipe = Pipeline(w, [t.to(dev) for t in tabs_cpu], 1 << 21)
+    c, ctx, P, K = case_of(w), pipe.ctx, w.P, max(k, 1)
+    tabs_np = [t.numpy() for t in tabs_cpu]
+    N = 6
+    rng = np.random.default_rng(100 * cfg + k)
+    streams = [torch.cuda.Stream() for _ in range(P)]
+    plans, refs, outs = [], [], []
+    for it in range(N):                               # plans are prepared up front, one buffer set each
+        ix, off = synth.make_batch(w, it)
+        nnz = int(off[-1])
+        ctx.bls_plan(ix.to(dev), off.to(dev), nnz, pipe.sendcounts, pipe.sdispls, pipe.recvcounts, pipe.rdispls,
+                     pipe.ridx, pipe.segoff, None, pipe.ws)
+        plans.append((pipe.ridx[:max(nnz, 1)].clone(), pipe.segoff.clone(), nnz))
+        refs.append(oracle.pipeline(c, tabs_np, ix.numpy(), off.numpy())["Out"])
+        outs.append(pipe.new_out())
+    torch.cuda.synchronize()
+    with pytest.raises(B.BlsError) as e:
+        ctx.bls_rank_complete(0, 0, None, outs[0], streams[0])
+    assert e.value.code == B.BLS_ERING_EMPTY
+    done = [0] * P
+    for it in range(N):
+        if it >= K:                                   # the slot must be released by every requester first
+            with pytest.raises(B.BlsError) as e:
+                ctx.bls_rank_put(0, plans[it][0], None, plans[it][1], plans[it][2], it, streams[0])
+            assert e.value.code == B.BLS_ERING_FULL
+            for s in rng.permutation(P):
+                ctx.bls_rank_complete(int(s), it - K, None, outs[it - K], streams[s])
+                done[s] += 1
+        order = rng.permutation(P)
+        if it == 0:
+            ctx.bls_rank_put(int(order[0]), plans[0][0], None, plans[0][1], plans[0][2], 0, streams[order[0]])
+            with pytest.raises(B.BlsError) as e:      # not every owner has issued iteration 0 yet
+                ctx.bls_rank_complete(0, 0, None, outs[0], streams[0])
+            assert e.value.code == B.BLS_EORDER
+            with pytest.raises(B.BlsError) as e:      # an owner cannot skip ahead
+                ctx.bls_rank_put(int(order[0]), plans[0][0], None, plans[0][1], plans[0][2], 2, streams[order[0]])
+            assert e.value.code == B.BLS_EORDER
+            order = order[1:]
+        for d in order:
+            if rng.random() < 0.4:
+                ctx.bls_rank_delay(int(rng.integers(50, 400)), streams[d])
+            ctx.bls_rank_put(int(d), plans[it][0], None, plans[it][1], plans[it][2], it, streams[d])
+    for it in range(max(N - K, 0), N):
+        for s in rng.permutation(P):
+            ctx.bls_rank_complete(int(s), it, None, outs[it], streams[s])
+    torch.cuda.synchronize()
+    ctx.bls_check()
+    for it in range(N):
+        assert np.array_equal(bits(outs[it].cpu().numpy()), bits(refs[it])), (cfg, k, it)
+    # back to whole-batch calls on the same context once everything has drained
+    ix, off = synth.make_batch(w, 0)
+    out = pipe.new_out()
+    pipe.step(ix.to(dev), off.to(dev), int(off[-1]), out)
+    assert np.array_equal(bits(out.cpu().numpy()), bits(refs[0]))
