@@ -80,6 +80,77 @@ def cpu_baseline(w, tabs_gpu, batches, budget_s: float) -> dict:
                       f"unpack, all {w.T} tables at full size on the host"}
 
 
+def lag_demo(args) -> int:
+    """The paper's Setting 2 on one GPU: every simulated rank on its own stream, a uniformly random
+    delay before each rank's work in every iteration, bound k swept.  With k = 0 every iteration
+    costs the slowest rank's delay; with k > 0 ranks run ahead and the delays average out."""
+    import numpy as np
+    import torch
+
+    import synth
+    from paper_2512_19342_amd.runner import Pipeline
+    dev = torch.device("cuda:0")
+    base = synth.workload(args.config, args.size)
+    tabs = [synth.make_table(base, t, dev) for t in range(base.T)]
+    N, P = args.steps, base.P
+    batches = [synth.make_batch(base, it, dev) for it in range(N)]
+    nnzs = [int(off[-1].item()) for _, off in batches]
+    delays = np.random.default_rng(2512).integers(0, args.max_delay_us + 1, size=(N, P))
+    rows = []
+    for n_cfg, k in enumerate([args.bounds[0]] + list(args.bounds)):   # the first pass only warms the device up
+        w = synth.workload(args.config, args.size)
+        w.k = k
+        pipe = Pipeline(w, tabs, max(nnzs))
+        c, K = pipe.ctx, max(k, 1)
+        plans = []
+        for (ix, off), nnz in zip(batches, nnzs):          # data and plans are prepared before timing
+            c.bls_plan(ix, off, nnz, pipe.sendcounts, pipe.sdispls, pipe.recvcounts, pipe.rdispls,
+                       pipe.ridx, pipe.segoff, None, pipe.ws)
+            plans.append((pipe.ridx[:max(nnz, 1)].clone(), pipe.segoff.clone(), nnz))
+        outs = [pipe.new_out() for _ in range(K)]
+        streams = [torch.cuda.Stream() for _ in range(P)]
+        ev = [[torch.cuda.Event(enable_timing=True) for _ in range(2)] for _ in range(P)]
+        for with_delay in (None, False, True):           # None: an untimed warm-up pass without delays
+            torch.cuda.synchronize()
+            for r in range(P):
+                ev[r][0].record(streams[r])
+            t0 = time.perf_counter()
+            first = getattr(pipe, "_lag_iter", 0)       # per-rank iteration numbers keep counting
+            for j in range(N):
+                it = first + j
+                if j >= K:
+                    for s in range(P):
+                        c.bls_rank_complete(s, it - K, None, outs[(it - K) % K], streams[s])
+                for d in range(P):
+                    if with_delay and delays[j, d]:
+                        c.bls_rank_delay(int(delays[j, d]), streams[d])
+                    c.bls_rank_put(d, plans[j][0], None, plans[j][1], plans[j][2], it, streams[d])
+            for j in range(max(N - K, 0), N):
+                for s in range(P):
+                    c.bls_rank_complete(s, first + j, None, outs[(first + j) % K], streams[s])
+            t_host = time.perf_counter() - t0
+            for r in range(P):
+                ev[r][1].record(streams[r])
+            torch.cuda.synchronize()
+            pipe._lag_iter = first + N
+            c.bls_check()
+            per_rank = [ev[r][0].elapsed_time(ev[r][1]) / N for r in range(P)]
+            if with_delay is None or n_cfg == 0:
+                continue
+            rows.append({"k": k, "delays": with_delay, "latency_ms_per_iteration_mean_over_ranks": sum(per_rank) / P,
+                         "iterations_per_s_sum_over_ranks": sum(1e3 / x for x in per_rank),
+                         "host_enqueue_ms_per_iteration": t_host / N * 1e3})
+            print(f"[lag] k={k} delays={'U(0,%d us)' % args.max_delay_us if with_delay else 'none'}: "
+                  f"{rows[-1]['latency_ms_per_iteration_mean_over_ranks']:.4f} ms per iteration per rank "
+                  f"(host enqueue {rows[-1]['host_enqueue_ms_per_iteration']:.4f})", file=sys.stderr, flush=True)
+        del pipe
+    print(json.dumps({"experiment": "per-rank streams with injected delays (the paper's Setting 2 on one GPU)",
+                      "workload": WORKLOAD_TEXT[args.config], "iterations": N, "ranks": P,
+                      "max_delay_us": args.max_delay_us, "mean_delay_ms": args.max_delay_us / 2e3,
+                      "expected_max_of_P_delays_ms": args.max_delay_us * P / (P + 1) / 1e3, "results": rows}))
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -94,6 +165,12 @@ def main() -> int:
                     help="cache-defeating control: uniform indices instead of the workload's law")
     ap.add_argument("--timed-only", action="store_true",
                     help="only the warm-up and the timed staged steps (for profiler runs: no fused, ring or copy sections)")
+    ap.add_argument("--lag-demo", action="store_true",
+                    help="instead of the benchmark: per-rank streams with random delays, bound k swept "
+                         "(use a workload with P <= 4, e.g. --config 2: a process has 4 hardware queues here, "
+                         "more streams than that share queues and serialise)")
+    ap.add_argument("--max-delay-us", type=int, default=1000)
+    ap.add_argument("--bounds", type=int, nargs="+", default=[0, 1, 2, 4, 8])
     ap.add_argument("--bag-fixed", type=int, default=0, help="experiment: every bag has this many lookups")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -109,6 +186,8 @@ def main() -> int:
     if not torch.cuda.is_available():
         print("bench.py needs a GPU", file=sys.stderr)
         return 2
+    if args.lag_demo:
+        return lag_demo(args)
     dev = torch.device("cuda:0")
     w = synth.workload(args.config, args.size)
     if args.index_dist == "uniform":
