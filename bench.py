@@ -171,6 +171,7 @@ def main() -> int:
                          "more streams than that share queues and serialise)")
     ap.add_argument("--max-delay-us", type=int, default=1000)
     ap.add_argument("--bounds", type=int, nargs="+", default=[0, 1, 2, 4, 8])
+    ap.add_argument("--rows-cap", type=int, default=0, help="experiment: no table has more rows than this")
     ap.add_argument("--bag-fixed", type=int, default=0, help="experiment: every bag has this many lookups")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -194,6 +195,8 @@ def main() -> int:
         w.index_dist = ("uniform",)
     if args.bag_fixed:
         w.bag = ("fixed", args.bag_fixed)
+    if args.rows_cap:
+        w.rows = [min(r, args.rows_cap) for r in w.rows]
     def note(msg: str):
         print(f"[bench] {msg}", file=sys.stderr, flush=True)
 
@@ -327,7 +330,8 @@ def main() -> int:
         "dtype": "f32" if w.table_dtype == "fp32" else "f16 storage, f32 accumulate", "data": "synthetic",
         "config": {"workload": WORKLOAD_TEXT[args.config] + ("" if args.size == "full" else " [reduced twin]")
                    + (" [uniform-index control]" if args.index_dist else "")
-                   + (f" [every bag {args.bag_fixed} lookups]" if args.bag_fixed else ""),
+                   + (f" [every bag {args.bag_fixed} lookups]" if args.bag_fixed else "")
+                   + (f" [tables capped at {args.rows_cap} rows]" if args.rows_cap else ""),
                    "P": w.P, "T": w.T, "D": w.D, "B": w.B, "k": w.k, "lookups_per_step": mean_nnz,
                    "table_bytes": w.table_bytes(), "distinct_batches": len(batches)},
         "roofline": {"bound": "hbm", "kernel": "pool_stream (bls_embbag_pool)", "achieved": achieved,

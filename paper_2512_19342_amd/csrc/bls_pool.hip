@@ -261,27 +261,28 @@ __global__ __launch_bounds__(kThreads) void pool_stream(DevDesc dd, const int64_
     const int rel = (int)(seg - beg);                        // segment starts relative to the stream
     const int total = nb > 0 ? (int)(end - beg) : 0;
 
-    int cur = 0, pos = 0;                                    // segment being summed, rows consumed
+    int cur = 0;                                             // segment being summed
     int cur_end = nb > 0 ? (int)__shfl(rel, gbase + 1, 64) : -1;
     A acc;
     acc.zero();
 
-    // store finished segments (also empty ones); every lane of the wavefront takes part in the
-    // lane exchange, the updates are per group
-    auto flush = [&]() {
-        for (;;) {
-            const bool need = cur < nb && cur_end == pos;
-            if (!__any(need)) break;
+    // Store finished segments (also empty ones) once `pos` rows of the stream are consumed.  The
+    // test is one compare against a uniform value; the rest runs only when some group of the
+    // wavefront is at a boundary.  Every lane takes part in the lane exchange, the updates are
+    // per group.  cur_end is -1 when the group has no segment left, which no position equals.
+    auto flush = [&](int pos) {
+        if (!__any(cur_end == pos)) return;
+        do {
             const int nxt = __shfl(rel, gbase + (cur + 2 < G ? cur + 2 : G - 1), 64);
-            if (need) {
+            if (cur_end == pos) {
                 if (col_ok) acc.store(Y + (out0 + cur) * dd.D + li * A::NV);
                 acc.zero();
                 ++cur;
                 cur_end = cur < nb ? nxt : -1;
             }
-        }
+        } while (__any(cur_end == pos));
     };
-    flush();
+    flush(0);
 
     // this lane's row of block c0 as a position in the shard (all ones: none or out of range)
     using pos_t = typename std::conditional<WIDE, uint64_t, uint32_t>::type;
@@ -337,8 +338,7 @@ __global__ __launch_bounds__(kThreads) void pool_stream(DevDesc dd, const int64_
                     if constexpr (WGT) acc.add_weighted(v[u], wt[u]);
                     else acc.add(v[u]);
                 }
-                pos = at + u + 1 < total ? at + u + 1 : total;
-                flush();
+                flush(at + u + 1);                           // positions past the stream's end match nothing
             }
         }
         mine = ahead;
