@@ -65,7 +65,7 @@ def cpu_baseline(w, tabs_gpu, batches, budget_s: float) -> dict:
     (all tables at full size, copied to the host) until about `budget_s` seconds are spent."""
     import oracle
     tabs = [t.cpu().numpy() for t in tabs_gpu]
-    case = oracle.Case(w.P, w.T, w.D, w.B, w.part_kind, w.rows, w.table_owner, 1 if w.table_dtype == "fp16" else 0)
+    case = oracle.Case(w.P, w.T, w.D, w.B, w.part_kind, w.rows, w.table_owner, w.dtype_code)
     host = [(ix.cpu().numpy(), off.cpu().numpy()) for ix, off in batches]
     spent, nnz, n = 0.0, 0, 0
     while spent < budget_s and n < 64:

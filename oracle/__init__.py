@@ -59,7 +59,8 @@ def _chk(fn: str, rc: int):
 class Case:
     """Shape of one problem: P ranks, T tables, vector length D, global batch B,
     partition kind (0 table-wise with ``owner[t]``, 1 row-wise block), rows per table,
-    storage dtype (0 fp32, 1 fp16)."""
+    storage dtype (0 fp32, 1 fp16, 2 row-quantised 8-bit: ``rowq_stride(D)`` bytes per row,
+    D codes, fp32 scale, fp32 bias, padding)."""
     P: int
     T: int
     D: int
@@ -84,11 +85,17 @@ class Case:
         return self.F * self.T * self.B
 
 
+def rowq_stride(D: int) -> int:
+    """Bytes per row of a row-quantised table: D codes + scale + bias, padded to 16."""
+    return (D + 8 + 15) // 16 * 16
+
+
 def _table_ptrs(case: Case, tables: List[np.ndarray]):
-    want = np.float16 if case.dtype == 1 else np.float32
+    want = {0: np.float32, 1: np.float16, 2: np.uint8}[case.dtype]
+    width = rowq_stride(case.D) if case.dtype == 2 else case.D
     keep = []
     for t, a in enumerate(tables):
-        assert a.dtype == want and a.flags.c_contiguous and a.shape == (case.rows[t], case.D), (t, a.dtype, a.shape)
+        assert a.dtype == want and a.flags.c_contiguous and a.shape == (case.rows[t], width), (t, a.dtype, a.shape)
         keep.append(a)
     arr = (C.c_void_p * case.T)(*[a.ctypes.data for a in keep])
     return arr, keep

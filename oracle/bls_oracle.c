@@ -249,9 +249,25 @@ static float half_to_float(uint16_t h)
     return f;
 }
 
-static float elem(const void *table, int dtype, int64_t i)
+/* Bytes from one row of a row-quantised table (dtype 2) to the next: D one-byte codes, the
+ * row's fp32 scale, its fp32 bias, padded to a multiple of 16. */
+static int64_t rowq_stride(int D) { return ((int64_t)D + 8 + 15) / 16 * 16; }
+
+/* Element (row, c) of a table as the fp32 number it stands for.  dtype 0: fp32; 1: binary16
+ * (conversion exact); 2: 8-bit codes with one scale and one bias per row (an extension the
+ * paper does not describe; reading: value = code * scale + bias evaluated in fp32, the
+ * product rounded, then the sum rounded - the usual row-wise 8-bit embedding format). */
+static float elem(const void *table, int dtype, int D, int64_t row, int c)
 {
-    return dtype == 1 ? half_to_float(((const uint16_t *)table)[i]) : ((const float *)table)[i];
+    if (dtype == 2) {
+        const uint8_t *p = (const uint8_t *)table + row * rowq_stride(D);
+        float scale, bias, prod;
+        memcpy(&scale, p + D, 4);
+        memcpy(&bias, p + D + 4, 4);
+        prod = (float)p[c] * scale;
+        return prod + bias;
+    }
+    return dtype == 1 ? half_to_float(((const uint16_t *)table)[row * D + c]) : ((const float *)table)[row * D + c];
 }
 
 /*
@@ -259,7 +275,7 @@ static float elem(const void *table, int dtype, int64_t i)
  *   Out[b][t][c] = sum over l in bag (t,b) of W_t[indices[l]][c]
  * computed in double precision (out64, nullable) and with one fp32 accumulator that
  * starts at +0.0f and adds the terms in increasing l (out32, nullable).  tables[t] is
- * table t with global row numbering, dtype 0 = fp32, 1 = fp16 storage.
+ * table t with global row numbering, dtype 0 = fp32, 1 = fp16, 2 = row-quantised 8-bit storage.
  */
 int orc_embbag_plain_ex(int T, int D, int64_t B, int dtype, const int64_t *rows, const void *const *tables,
                         const int64_t *indices, const int64_t *offsets, const float *weights, int mean,
@@ -289,7 +305,7 @@ int orc_embbag_plain_ex(int T, int D, int64_t B, int dtype, const int64_t *rows,
                 double a64 = 0.0;
                 float a32 = 0.0f;
                 for (l = offsets[g]; l < offsets[g + 1]; ++l) {
-                    float x = elem(tables[t], dtype, indices[l] * D + c);
+                    float x = elem(tables[t], dtype, D, indices[l], c);
                     if (weights) {
                         float term = weights[l] * x;
                         a64 += (double)weights[l] * (double)x;
@@ -323,7 +339,7 @@ int orc_embbag_absmass(int T, int D, int64_t B, int dtype, const void *const *ta
                 int64_t g = (int64_t)t * B + b;
                 double a = 0.0;
                 for (l = offsets[g]; l < offsets[g + 1]; ++l) {
-                    double x = (double)elem(tables[t], dtype, indices[l] * D + c);
+                    double x = (double)elem(tables[t], dtype, D, indices[l], c);
                     a += x < 0 ? -x : x;
                 }
                 mass[((int64_t)b * T + t) * D + c] = a;
@@ -384,7 +400,7 @@ int orc_pool_weighted(int P, int T, int D, int64_t B, int part_kind, const int64
                     for (c = 0; c < D; ++c) {
                         float acc = 0.0f;
                         for (j = segoff[sg]; j < segoff[sg + 1]; ++j) {
-                            float x = elem(tables[t], dtype, (shard_first + ridx[j]) * D + c);
+                            float x = elem(tables[t], dtype, D, shard_first + ridx[j], c);
                             if (rweights) { float term = rweights[j] * x; acc += term; }
                             else acc += x;
                         }

@@ -97,7 +97,7 @@ class Workload:
     D: int
     k: int
     B: int
-    table_dtype: str            # "fp32" | "fp16"
+    table_dtype: str            # "fp32" | "fp16" | "u8rq" (8-bit codes, scale and bias per row)
     part_kind: int              # 0 table-wise, 1 row-wise block
     rows: List[int]
     table_owner: List[int]      # table-wise only (zeros for row-wise)
@@ -116,18 +116,36 @@ class Workload:
         return self.P if self.part_kind == 1 else 1
 
     @property
-    def elem_bytes(self) -> int:
-        return 2 if self.table_dtype == "fp16" else 4
+    def dtype_code(self) -> int:
+        """Storage code shared by the library's and the oracle's interfaces."""
+        return {"fp32": 0, "fp16": 1, "u8rq": 2}[self.table_dtype]
+
+    @property
+    def row_bytes(self) -> int:
+        """Bytes from one table row to the next."""
+        if self.table_dtype == "u8rq":
+            return rowq_stride(self.D)
+        return self.D * (2 if self.table_dtype == "fp16" else 4)
+
+    @property
+    def row_width(self) -> int:
+        """Second dimension of a table tensor (elements; bytes for row-quantised tables)."""
+        return rowq_stride(self.D) if self.table_dtype == "u8rq" else self.D
 
     @property
     def torch_dtype(self):
-        return torch.float16 if self.table_dtype == "fp16" else torch.float32
+        return {"fp32": torch.float32, "fp16": torch.float16, "u8rq": torch.uint8}[self.table_dtype]
 
     def mean_bag(self) -> float:
         return float(self.bag[1]) if self.bag[0] == "fixed" else 0.5 * (self.bag[1] + self.bag[2])
 
     def table_bytes(self) -> int:
-        return sum(self.rows) * self.D * self.elem_bytes
+        return sum(self.rows) * self.row_bytes
+
+
+def rowq_stride(D: int) -> int:
+    """Row-quantised storage: D one-byte codes, fp32 scale, fp32 bias, padded to 16 bytes."""
+    return (D + 8 + 15) // 16 * 16
 
 
 # ----------------------------------------------------------------------------- partitions
@@ -249,9 +267,47 @@ def grid_rows(w: Workload, t: int, row_ids: torch.Tensor) -> torch.Tensor:
     return s.to(torch.float32) * (2.0 ** -14)
 
 
+def rowq_rows(w: Workload, t: int, row_ids: torch.Tensor) -> torch.Tensor:
+    """Rows ``row_ids`` of row-quantised table t as stored: uint8 ``[n, rowq_stride(D)]``.
+
+    Codes are hash bytes.  "grid" values: scale in {2^-8, 2^-9, 2^-10} and bias a multiple of
+    2^-10 in [-1/16, 1/16), so every element and every sum of up to 2^10 of them is exact in
+    fp32 in any order.  Otherwise scale and bias are arbitrary floats (scale in (1e-4, 1e-2),
+    bias in (-0.5, 0.5)), which makes the roundings of the decoding and of the sum visible.
+    Padding bytes are zero.
+    """
+    dev = row_ids.device
+    n, stride = row_ids.numel(), rowq_stride(w.D)
+    key = stream_key(w.seed, _P_TABLE, t)
+    ids = row_ids.to(torch.int64)
+    out = torch.zeros((n, stride), dtype=torch.uint8, device=dev)
+    cols = torch.arange(w.D, dtype=torch.int64, device=dev)
+    out[:, :w.D] = (hash_u64(key, ids[:, None] * w.D + cols[None, :]) & 255).to(torch.uint8)
+    hk = stream_key(w.seed, _P_TABLE, t, 1)
+    if w.values == "grid":
+        h = hash_u64(hk, ids)
+        scale = torch.pow(2.0, -(8.0 + (h % 3).to(torch.float32))).to(torch.float32)
+        bias = (((h >> 8) & 127) - 64).to(torch.float32) * (2.0 ** -10)
+    else:
+        scale = (1e-4 + 9.9e-3 * uniform01(hk, 2 * ids)).to(torch.float32)
+        bias = (uniform01(hk, 2 * ids + 1) - 0.5).to(torch.float32)
+    out[:, w.D:w.D + 4] = scale.contiguous().view(torch.uint8).reshape(n, 4)
+    out[:, w.D + 4:w.D + 8] = bias.contiguous().view(torch.uint8).reshape(n, 4)
+    return out
+
+
 def make_table(w: Workload, t: int, device="cpu", chunk_rows: Optional[int] = None) -> torch.Tensor:
-    """Full table t as ``[rows_t, D]`` in the workload's storage dtype on ``device``."""
+    """Full table t in the workload's storage on ``device``: ``[rows_t, D]``, or uint8
+    ``[rows_t, rowq_stride(D)]`` for row-quantised storage."""
     rows = w.rows[t]
+    if w.table_dtype == "u8rq":
+        out = torch.empty((rows, rowq_stride(w.D)), dtype=torch.uint8, device=device)
+        if chunk_rows is None:
+            chunk_rows = max(1, (1 << 24) // w.D)
+        for r0 in range(0, rows, chunk_rows):
+            r1 = min(rows, r0 + chunk_rows)
+            out[r0:r1] = rowq_rows(w, t, torch.arange(r0, r1, dtype=torch.int64, device=device))
+        return out
     if w.values == "gauss":
         rng = np.random.Generator(np.random.PCG64([w.seed, _P_TABLE, t]))
         a = rng.normal(0.0, 0.01, size=(rows, w.D)).astype(np.float32)
@@ -267,7 +323,9 @@ def make_table(w: Workload, t: int, device="cpu", chunk_rows: Optional[int] = No
 
 
 def table_rows(w: Workload, t: int, row_ids: torch.Tensor, table: Optional[torch.Tensor] = None) -> torch.Tensor:
-    """Selected rows of table t as float32 on the CPU (recomputed for grid tables)."""
+    """Selected rows of table t as float32 on the CPU (recomputed for grid tables).
+    Not for row-quantised tables, whose stored rows come from ``rowq_rows``."""
+    assert w.table_dtype != "u8rq"
     if w.values == "grid":
         return grid_rows(w, t, row_ids.cpu()).to(w.torch_dtype).to(torch.float32)
     if table is None:

@@ -50,7 +50,7 @@ def test_full_size(cfg):
     print(f"  {nnz} lookups through the path; comparing the plan in full", flush=True)
 
     ix_h, off_h = ix.cpu().numpy(), off.cpu().numpy()
-    case = oracle.Case(w.P, w.T, w.D, w.B, w.part_kind, w.rows, w.table_owner, 1 if w.table_dtype == "fp16" else 0)
+    case = oracle.Case(w.P, w.T, w.D, w.B, w.part_kind, w.rows, w.table_owner, w.dtype_code)
     ref = oracle.plan(case, ix_h, off_h)
     assert ref["sendcounts"].sum() == nnz
     for name, got in (("sendcounts", pipe.sendcounts), ("sdispls", pipe.sdispls), ("recvcounts", pipe.recvcounts),

@@ -19,7 +19,7 @@ TOL = {"fp32": 1e-6, "fp16": 1e-3}
 
 
 def case_of(w):
-    return oracle.Case(w.P, w.T, w.D, w.B, w.part_kind, w.rows, w.table_owner, 1 if w.table_dtype == "fp16" else 0)
+    return oracle.Case(w.P, w.T, w.D, w.B, w.part_kind, w.rows, w.table_owner, w.dtype_code)
 
 
 def bits(a):

@@ -24,8 +24,8 @@ MUTATIONS = {
     "plain sum wrong sign": ("a32 += x;", "a32 -= x;"),
     "plain sum drops first term": ("for (l = offsets[g]; l < offsets[g + 1]; ++l) {\n                    float x",
                                    "for (l = offsets[g] + 1; l < offsets[g + 1]; ++l) {\n                    float x"),
-    "pool ignores shard base": ("float x = elem(tables[t], dtype, (shard_first + ridx[j]) * D + c);",
-                                "float x = elem(tables[t], dtype, (ridx[j]) * D + c);"),
+    "pool ignores shard base": ("float x = elem(tables[t], dtype, D, shard_first + ridx[j], c);",
+                                "float x = elem(tables[t], dtype, D, ridx[j], c);"),
     "weights not carried": ("rweights[rbase[d] + rdispls[d * P + s] + rank] = weights[l];",
                             "rweights[rbase[d] + rdispls[d * P + s] + rank] = weights[offsets[g]];"),
     "weighted term fused into double": ("float term = weights[l] * x;\n                        a64", "float term = (float)((double)weights[l] * 1.0000001 * x);\n                        a64"),
@@ -40,6 +40,12 @@ MUTATIONS = {
     "unpack reads local table index t": ("R + rbase + blk + ((int64_t)loc[t] * n + b_loc) * D;",
                                          "R + rbase + blk + ((int64_t)(part_kind ? loc[t] : 0) * n + b_loc) * D;"),
     "half exponent bias": ("bits = sign | ((e + 127 - 15) << 23) | (m << 13);", "bits = sign | ((e + 127 - 16) << 23) | (m << 13);"),
+    "row-quantised scale and bias swapped": ("memcpy(&scale, p + D, 4);\n        memcpy(&bias, p + D + 4, 4);",
+                                             "memcpy(&bias, p + D, 4);\n        memcpy(&scale, p + D + 4, 4);"),
+    "row-quantised stride not padded": ("return ((int64_t)D + 8 + 15) / 16 * 16;", "return (int64_t)D + 8;"),
+    "row-quantised codes read as signed": ("prod = (float)p[c] * scale;", "prod = (float)(int8_t)p[c] * scale;"),
+    "row-quantised decoding rounded once": ("prod = (float)p[c] * scale;\n        return prod + bias;",
+                                            "return (float)((double)p[c] * (double)scale + (double)bias);"),
     "half subnormals flushed": ("if (m == 0) bits = sign;\n        else {", "if (m >= 0) bits = sign;\n        else {"),
 }
 
@@ -57,6 +63,10 @@ PINS = [
     lambda: pins.test_weighted_and_mean_match_brute_force(pins.TINY[2]),
     lambda: pins.test_weighted_and_mean_against_torch(3),
     lambda: pins.test_weights_exact_cases(),
+    lambda: pins.test_rowq_worked_example(),
+    lambda: pins.test_rowq_stride_and_padding(),
+    lambda: pins.test_rowq_decoding_rounds_twice_in_fp32(),
+    lambda: pins.test_rowq_pipeline_against_decoded_fp32_tables(1),
 ]
 
 

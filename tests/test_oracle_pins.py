@@ -23,7 +23,7 @@ def np_tables(w, device="cpu"):
 
 
 def case_of(w):
-    return oracle.Case(w.P, w.T, w.D, w.B, w.part_kind, w.rows, w.table_owner, 1 if w.table_dtype == "fp16" else 0)
+    return oracle.Case(w.P, w.T, w.D, w.B, w.part_kind, w.rows, w.table_owner, w.dtype_code)
 
 
 def brute(w, tables, indices, offsets):
@@ -563,3 +563,105 @@ def test_weights_exact_cases():
     m = oracle.pipeline(c, [np.ones((r, 4), np.float32) for r in w.rows], ix, off, mean=True)["Out"]
     lens = np.diff(off).reshape(3, 9).T
     assert np.array_equal(m[:, :, 0], (lens > 0).astype(np.float32))
+
+
+# ----------------------------------------------------------------------------- row-quantised tables
+
+def _rowq_table(D, rows):
+    """Bytes of a row-quantised table written out by hand: rows = [(codes, scale, bias), ...]."""
+    import struct
+    stride = (D + 8 + 15) // 16 * 16
+    buf = bytearray(stride * len(rows))
+    for r, (codes, scale, bias) in enumerate(rows):
+        assert len(codes) == D
+        buf[r * stride:r * stride + D] = bytes(codes)
+        buf[r * stride + D:r * stride + D + 8] = struct.pack("<ff", scale, bias)
+    return np.frombuffer(bytes(buf), dtype=np.uint8).reshape(len(rows), stride).copy()
+
+
+def test_rowq_worked_example():
+    """Four rows written byte by byte, sums worked out by hand (all exact in fp32)."""
+    D = 4
+    tab = _rowq_table(D, [([0, 1, 2, 255], 0.5, -1.0),       # -1, -0.5, 0, 126.5
+                          ([10, 20, 30, 40], 0.25, 3.0),     # 5.5, 8, 10.5, 13
+                          ([1, 1, 1, 1], 2.0, 0.0),          # 2, 2, 2, 2
+                          ([128, 64, 32, 16], 0.125, -16.0)])  # 0, -8, -12, -14
+    assert tab.shape == (4, 16)
+    case = oracle.Case(1, 1, D, 3, 0, [4], [0], 2)
+    indices = np.array([0, 1, 3, 2, 2, 2], np.int64)         # bags: {0,1,3}, {}, {2,2,2}
+    offsets = np.array([0, 3, 3, 6], np.int64)
+    o64, o32 = oracle.embbag_plain(case, [tab], indices, offsets)
+    want = np.array([[[4.5, -0.5, -1.5, 125.5]], [[0, 0, 0, 0]], [[6, 6, 6, 6]]])
+    assert np.array_equal(o64, want) and np.array_equal(o32, want.astype(np.float32))
+    # the whole path moves these vectors unchanged (P = 1: one owner, one requester)
+    res = oracle.pipeline(case, [tab], indices, offsets)
+    assert np.array_equal(res["Out"], want.astype(np.float32))
+
+
+def test_rowq_stride_and_padding():
+    """Row r starts r * stride bytes in, stride = D + 8 rounded up to 16; padding is ignored."""
+    for D in (1, 7, 8, 9, 24, 40, 128):
+        stride = oracle.rowq_stride(D)
+        assert stride % 16 == 0 and D + 8 <= stride < D + 8 + 16 and stride == synth.rowq_stride(D)
+        rng = np.random.default_rng(D)
+        rows = [(list(rng.integers(0, 256, D)), float(2.0 ** -int(rng.integers(1, 6))), float(rng.integers(-8, 8)))
+                for _ in range(5)]
+        tab = _rowq_table(D, rows)
+        junk = tab.copy()
+        junk[:, D + 8:] = 0xA5                                # padding bytes must not matter
+        case = oracle.Case(1, 1, D, 5, 0, [5], [0], 2)
+        idx, off = np.arange(5, dtype=np.int64), np.arange(6, dtype=np.int64)
+        a64, _ = oracle.embbag_plain(case, [tab], idx, off)
+        b64, _ = oracle.embbag_plain(case, [junk], idx, off)
+        want = np.array([[np.array(c, np.float64) * s + b] for c, s, b in rows])
+        assert np.array_equal(a64, want) and np.array_equal(b64, want)
+
+
+def test_rowq_decoding_rounds_twice_in_fp32():
+    """value = fl32(fl32(code * scale) + bias): compared with numpy's float32 arithmetic, on
+    rows where a single rounding (as a fused multiply-add would do) gives other bits."""
+    D, n = 64, 400
+    w = synth.custom("rowq", P=1, T=1, D=D, B=n, k=0, part_kind=0, rows=[n], table_dtype="u8rq", values="gauss", seed=41)
+    tab = synth.make_table(w, 0).numpy()
+    codes = tab[:, :D].astype(np.float32)
+    scale = tab[:, D:D + 4].copy().view(np.float32)          # [n, 1]
+    bias = tab[:, D + 4:D + 8].copy().view(np.float32)
+    twice = (codes * scale).astype(np.float32) + bias         # numpy rounds each step to float32
+    once = (codes.astype(np.float64) * scale.astype(np.float64) + bias.astype(np.float64)).astype(np.float32)
+    assert twice.dtype == np.float32 and np.count_nonzero(twice != once) > 50
+    case = oracle.Case(1, 1, D, n, 0, [n], [0], 2)
+    idx, off = np.arange(n, dtype=np.int64), np.arange(n + 1, dtype=np.int64)
+    o64, o32 = oracle.embbag_plain(case, [tab], idx, off)
+    assert np.array_equal(o32[:, 0, :], twice) and np.array_equal(o64[:, 0, :], twice.astype(np.float64))
+
+
+@pytest.mark.parametrize("part_kind", [0, 1])
+def test_rowq_pipeline_against_decoded_fp32_tables(part_kind):
+    """The path over a row-quantised table equals the path over the fp32 table of its decoded
+    values (decoded here with numpy), step by step: only the element decoding differs."""
+    w = synth.custom("rowq", P=3, T=4, D=24, B=10, k=1, part_kind=part_kind, rows=[30, 7, 19, 64],
+                     table_dtype="u8rq", values="gauss", seed=43, bag=("uniform", 0, 6))
+    tabs = np_tables(w)
+    dec = []
+    for tab in tabs:
+        s = tab[:, w.D:w.D + 4].copy().view(np.float32)
+        b = tab[:, w.D + 4:w.D + 8].copy().view(np.float32)
+        dec.append(np.ascontiguousarray((tab[:, :w.D].astype(np.float32) * s).astype(np.float32) + b))
+    ix, off = synth.make_batch(w, 0)
+    ix, off = ix.numpy(), off.numpy()
+    q = oracle.pipeline(case_of(w), tabs, ix, off)
+    f = oracle.pipeline(oracle.Case(w.P, w.T, w.D, w.B, w.part_kind, w.rows, w.table_owner, 0), dec, ix, off)
+    for key in ("Y", "S", "R", "Out", "ridx", "segoff"):
+        assert np.array_equal(q[key], f[key]), key
+
+
+def test_rowq_grid_tables_are_exact():
+    """Grid-valued row-quantised tables: fp32 and fp64 bag sums agree bit for bit."""
+    w = synth.custom("rowq", P=2, T=3, D=16, B=32, k=0, part_kind=1, rows=[50, 11, 200],
+                     table_dtype="u8rq", values="grid", seed=47, bag=("uniform", 0, 40))
+    tabs = np_tables(w)
+    ix, off = synth.make_batch(w, 0)
+    o64, o32 = oracle.embbag_plain(case_of(w), tabs, ix.numpy(), off.numpy())
+    assert np.array_equal(o64, o32.astype(np.float64)) and np.abs(o64).max() > 1.0
+    res = oracle.pipeline(case_of(w), tabs, ix.numpy(), off.numpy())
+    assert np.array_equal(res["Out"], o32)
