@@ -43,7 +43,7 @@ def stage_bytes(w, nnz: int) -> dict:
     seg = 8 * nvec
     return {
         "plan": 8 * nnz + 8 * (w.T * w.B + 1) + 8 * nnz + seg,
-        "pool": 8 * nnz + seg + nnz * w.D * w.elem_bytes + pv,
+        "pool": 8 * nnz + seg + nnz * w.row_bytes + pv,
         "pack": 2 * pv,
         "exchange": 2 * pv,
         "unpack": pv + out,
@@ -171,6 +171,8 @@ def main() -> int:
                          "more streams than that share queues and serialise)")
     ap.add_argument("--max-delay-us", type=int, default=1000)
     ap.add_argument("--bounds", type=int, nargs="+", default=[0, 1, 2, 4, 8])
+    ap.add_argument("--table-dtype", default=None, choices=[None, "fp32", "fp16", "u8rq"],
+                    help="variant: store the tables this way instead of the workload's own dtype")
     ap.add_argument("--rows-cap", type=int, default=0, help="experiment: no table has more rows than this")
     ap.add_argument("--bag-fixed", type=int, default=0, help="experiment: every bag has this many lookups")
     args = ap.parse_args()
@@ -195,6 +197,8 @@ def main() -> int:
         w.index_dist = ("uniform",)
     if args.bag_fixed:
         w.bag = ("fixed", args.bag_fixed)
+    if args.table_dtype:
+        w.table_dtype = args.table_dtype
     if args.rows_cap:
         w.rows = [min(r, args.rows_cap) for r in w.rows]
     def note(msg: str):
@@ -327,11 +331,13 @@ def main() -> int:
         "metric": "embedding lookups/sec + achieved HBM GB/s (bucket+pool+pack), 1 MI355X",
         "value": lookups / dt, "unit": "lookups/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": dt / args.steps * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f32" if w.table_dtype == "fp32" else "f16 storage, f32 accumulate", "data": "synthetic",
+        "dtype": {"fp32": "f32", "fp16": "f16 storage, f32 accumulate",
+                  "u8rq": "u8 row-quantised storage, f32 accumulate"}[w.table_dtype], "data": "synthetic",
         "config": {"workload": WORKLOAD_TEXT[args.config] + ("" if args.size == "full" else " [reduced twin]")
                    + (" [uniform-index control]" if args.index_dist else "")
                    + (f" [every bag {args.bag_fixed} lookups]" if args.bag_fixed else "")
-                   + (f" [tables capped at {args.rows_cap} rows]" if args.rows_cap else ""),
+                   + (f" [tables capped at {args.rows_cap} rows]" if args.rows_cap else "")
+                   + (f" [tables stored as {args.table_dtype}]" if args.table_dtype else ""),
                    "P": w.P, "T": w.T, "D": w.D, "B": w.B, "k": w.k, "lookups_per_step": mean_nnz,
                    "table_bytes": w.table_bytes(), "distinct_batches": len(batches)},
         "roofline": {"bound": "hbm", "kernel": "pool_stream (bls_embbag_pool)", "achieved": achieved,

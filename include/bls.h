@@ -62,13 +62,19 @@ enum {
     BLS_EHIP = -7         /* a HIP runtime call failed; text in bls_last_error               */
 };
 
-enum { BLS_FP32 = 0, BLS_FP16 = 1 };          /* table storage; accumulation and output are fp32 */
+/* Table storage; accumulation and output are fp32.
+ * BLS_U8_ROWQ (an extension, not in the paper): a row is bls_row_bytes(D) = D + 8 rounded up
+ * to a multiple of 16 bytes: D unsigned 8-bit codes, the row's fp32 scale, its fp32 bias,
+ * padding (ignored).  Element c of the row stands for the fp32 number
+ * fl(fl((float)code[c] * scale) + bias) - product and sum rounded separately, no fused
+ * multiply-add - and the bag sum adds these numbers like any other fp32 row. */
+enum { BLS_FP32 = 0, BLS_FP16 = 1, BLS_U8_ROWQ = 2 };
 enum { BLS_TABLE_WISE = 0, BLS_ROW_WISE = 1 };
 
 typedef struct bls_config {
     int32_t P, T, D, k;          /* 1 <= P <= 64; k >= 0 is the paper's bound, K = max(k,1) slots   */
     int64_t B;                   /* global batch, B >= P                                             */
-    int32_t table_dtype;         /* BLS_FP32 | BLS_FP16                                              */
+    int32_t table_dtype;         /* BLS_FP32 | BLS_FP16 | BLS_U8_ROWQ                                */
     int32_t part_kind;           /* BLS_TABLE_WISE | BLS_ROW_WISE                                    */
     const int64_t *rows;         /* host [T], rows per table (global), each >= 1                     */
     const int32_t *table_owner;  /* host [T], owner rank of each table; read for table-wise only     */
@@ -80,7 +86,8 @@ int bls_create(const bls_config *cfg, bls_ctx **out);
 int bls_destroy(bls_ctx *ctx);
 
 /* Hand the library one table shard: row-major [rows_in_shard][D] in the configured
- * storage dtype, device memory, 16-byte aligned, borrowed until bls_destroy.
+ * storage dtype ([rows_in_shard][D + 8 rounded up to 16] bytes for BLS_U8_ROWQ), device
+ * memory, 16-byte aligned, borrowed until bls_destroy.
  * Table-wise: rank must be table_owner[t] and rows_in_shard = rows[t].  Row-wise: one
  * call per (t, rank), rows_in_shard = number of rows of table t that fall in the
  * rank's block (may be 0, then d_rows may be NULL). */

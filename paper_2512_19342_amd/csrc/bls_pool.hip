@@ -36,12 +36,27 @@ __device__ __forceinline__ float half_hi(uint32_t w) { return half_bits((unsigne
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef u32x2 u32x2_a4 __attribute__((aligned(4)));   // a row's scale and bias sit on a 4-byte boundary
+
+// Bytes of a row that hold its elements, and bytes from one row to the next.
+__host__ __device__ __forceinline__ int64_t payload_bytes(int dtype, int D)
+{
+    return dtype == BLS_U8_ROWQ ? (int64_t)D : (int64_t)D * (dtype == BLS_FP16 ? 2 : 4);
+}
+__host__ __device__ __forceinline__ int64_t stride_bytes(int dtype, int D)
+{
+    return dtype == BLS_U8_ROWQ ? ((int64_t)D + 8 + 15) / 16 * 16 : payload_bytes(dtype, D);
+}
 
 // Per-lane accumulator: VB bytes of table storage per lane and row, NV values in them.
+// Row-quantised rows also bring their scale and bias (8 bytes behind the codes, the same
+// address for every lane of the group), and a value is code * scale + bias with the product
+// and the sum each rounded to fp32.
 template <int DT, int VB> struct Acc {
     static constexpr int NW = VB / 4;                              // 32-bit words loaded per row
-    static constexpr int NV = DT == BLS_FP16 ? VB / 2 : VB / 4;   // fp32 values accumulated
-    struct Raw { uint32_t w[NW]; };
+    static constexpr int NV = DT == BLS_U8_ROWQ ? VB : DT == BLS_FP16 ? VB / 2 : VB / 4;   // fp32 values accumulated
+    static constexpr int NX = DT == BLS_U8_ROWQ ? 2 : 0;           // scale, bias
+    struct Raw { uint32_t w[NW + NX]; };
     float a[NV];
 
     __device__ __forceinline__ void zero()
@@ -53,13 +68,18 @@ template <int DT, int VB> struct Acc {
     {
         Raw r;
 #pragma unroll
-        for (int i = 0; i < NW; ++i) r.w[i] = 0u;
+        for (int i = 0; i < NW + NX; ++i) r.w[i] = 0u;
         return r;
     }
-    // tables live in global memory: say so, or the loads are emitted as flat accesses
-    static __device__ __forceinline__ Raw load(const char *p)
+    // tables live in global memory: say so, or the loads are emitted as flat accesses.
+    // p: this lane's bytes of the row; p + tail: the row's scale and bias (row-quantised only)
+    static __device__ __forceinline__ Raw load(const char *p, int tail)
     {
         Raw r;
+        if constexpr (NX == 2) {
+            const u32x2 sb = *(const __attribute__((address_space(1))) u32x2_a4 *)(p + tail);
+            r.w[NW] = sb.x; r.w[NW + 1] = sb.y;
+        }
         if constexpr (NW == 4) {
             const u32x4 v = *(const __attribute__((address_space(1))) u32x4 *)p;
             r.w[0] = v.x; r.w[1] = v.y; r.w[2] = v.z; r.w[3] = v.w;
@@ -71,11 +91,20 @@ template <int DT, int VB> struct Acc {
         }
         return r;
     }
+    static __device__ __forceinline__ float decode(uint32_t word, int k, float scale, float bias)
+    {
+        const float prod = (float)((word >> (8 * k)) & 0xffu) * scale;
+        return prod + bias;
+    }
     __device__ __forceinline__ void add(const Raw &r)
     {
 #pragma unroll
         for (int i = 0; i < NW; ++i) {
-            if constexpr (DT == BLS_FP16) { a[2 * i] += half_lo(r.w[i]); a[2 * i + 1] += half_hi(r.w[i]); }
+            if constexpr (DT == BLS_U8_ROWQ) {
+                const float sc = __uint_as_float(r.w[NW]), bi = __uint_as_float(r.w[NW + 1]);
+#pragma unroll
+                for (int k = 0; k < 4; ++k) a[4 * i + k] += decode(r.w[i], k, sc, bi);
+            } else if constexpr (DT == BLS_FP16) { a[2 * i] += half_lo(r.w[i]); a[2 * i + 1] += half_hi(r.w[i]); }
             else a[i] += __uint_as_float(r.w[i]);
         }
     }
@@ -84,7 +113,14 @@ template <int DT, int VB> struct Acc {
     {
 #pragma unroll
         for (int i = 0; i < NW; ++i) {
-            if constexpr (DT == BLS_FP16) {
+            if constexpr (DT == BLS_U8_ROWQ) {
+                const float sc = __uint_as_float(r.w[NW]), bi = __uint_as_float(r.w[NW + 1]);
+#pragma unroll
+                for (int k = 0; k < 4; ++k) {
+                    const float term = w * decode(r.w[i], k, sc, bi);
+                    a[4 * i + k] += term;
+                }
+            } else if constexpr (DT == BLS_FP16) {
                 const float p0 = w * half_lo(r.w[i]), p1 = w * half_hi(r.w[i]);
                 a[2 * i] += p0; a[2 * i + 1] += p1;
             } else {
@@ -145,9 +181,10 @@ __global__ __launch_bounds__(kThreads) void pool_rows(DevDesc dd, const int64_t 
     const int gbase = (threadIdx.x & 63) & ~(G - 1);
     const uint32_t b = blockIdx.x * (kThreads / G) + threadIdx.x / G;
     const bool live = b < (uint32_t)dd.B;
-    const uint32_t row_bytes = (uint32_t)dd.D * (DT == BLS_FP16 ? 2u : 4u);
+    const uint32_t row_bytes = (uint32_t)payload_bytes(DT, dd.D), row_stride = (uint32_t)stride_bytes(DT, dd.D);
     const bool col_ok = (uint32_t)li * VB < row_bytes;       // lanes past the row's end idle
     const char *__restrict__ base = (const char *)dd.q_base[q] + (uint32_t)li * VB;
+    const int tail = (int)row_bytes - li * VB;               // from this lane's bytes to the row's scale and bias
     const int64_t shard_rows = dd.q_rows[q];
 
     int64_t beg = 0, len = 0, out = 0;
@@ -187,7 +224,7 @@ __global__ __launch_bounds__(kThreads) void pool_rows(DevDesc dd, const int64_t 
 #pragma unroll
             for (int u = 0; u < U; ++u) {
                 v[u] = A::none();
-                if (j + u < rem && r[u] != kBadRow && col_ok) v[u] = A::load(base + (uint64_t)r[u] * row_bytes);
+                if (j + u < rem && r[u] != kBadRow && col_ok) v[u] = A::load(base + (uint64_t)r[u] * row_stride, tail);
                 else wt[u] = 0.f;
             }
 #pragma unroll
@@ -230,10 +267,11 @@ __global__ __launch_bounds__(kThreads) void pool_stream(DevDesc dd, const int64_
     const uint32_t gx = bx * (kThreads / G) + threadIdx.x / G;
     const uint32_t s = gx / chunks_per_s;
     const uint32_t chunk = gx - s * chunks_per_s;
-    const uint32_t row_bytes = (uint32_t)dd.D * (DT == BLS_FP16 ? 2u : 4u);
+    const uint32_t row_bytes = (uint32_t)payload_bytes(DT, dd.D), row_stride = (uint32_t)stride_bytes(DT, dd.D);
     const bool col_ok = (uint32_t)li * VB < row_bytes;       // lanes past the row's end idle:
     // idle lanes re-read the row's first bytes (in bounds, same cache line) and never store
     const char *__restrict__ base = (const char *)dd.q_base[q] + (col_ok ? (uint32_t)li * VB : 0u);
+    const int tail = (int)row_bytes - (col_ok ? li * VB : 0);   // to the row's scale and bias
     const int64_t shard_rows = dd.q_rows[q];
 
     // this group's segments: samples [b0, b0 + nb) of mini-batch s
@@ -287,7 +325,7 @@ __global__ __launch_bounds__(kThreads) void pool_stream(DevDesc dd, const int64_
     // this lane's row of block c0 as a position in the shard (all ones: none or out of range)
     using pos_t = typename std::conditional<WIDE, uint64_t, uint32_t>::type;
     constexpr pos_t kNone = (pos_t)~(pos_t)0;
-    const uint32_t row_units = WIDE ? row_bytes : row_bytes / VB;
+    const uint32_t row_units = WIDE ? row_stride : row_stride / VB;
     auto fetch = [&](int c0) -> pos_t {
         pos_t m = kNone;
         if (c0 + li < total) {
@@ -327,7 +365,7 @@ __global__ __launch_bounds__(kThreads) void pool_stream(DevDesc dd, const int64_
             // lanes without a row keep stale registers and skip the add: nothing to clear
 #pragma unroll
             for (int u = 0; u < U; ++u)
-                if (is_row(off[u])) v[u] = A::load(base + (WIDE ? (uint64_t)off[u] : (uint64_t)off[u] * VB));
+                if (is_row(off[u])) v[u] = A::load(base + (WIDE ? (uint64_t)off[u] : (uint64_t)off[u] * VB), tail);
             // every load of the batch has landed before the first add: said once, here, so that
             // no wait is placed between the conditional loads of the next batch
             __builtin_amdgcn_s_waitcnt(0x0f70);              // vmcnt(0)
@@ -371,8 +409,18 @@ __global__ __launch_bounds__(kThreads) void pool_rows_generic(DevDesc dd, const 
         for (int64_t j = beg; j < end; ++j) {
             const int64_t r = ridx[j];
             if (r < 0 || r >= shard_rows) { if (c == 0) flag_error(dd); continue; }
-            const int64_t e = r * dd.D + c;
-            const float x = DT == BLS_FP16 ? half_bits(((const unsigned short *)base)[e]) : ((const float *)base)[e];
+            float x;
+            if constexpr (DT == BLS_U8_ROWQ) {
+                const unsigned char *row = (const unsigned char *)base + r * stride_bytes(DT, dd.D);
+                float scale, bias;                              // any D: no alignment to rely on
+                __builtin_memcpy(&scale, row + dd.D, 4);
+                __builtin_memcpy(&bias, row + dd.D + 4, 4);
+                const float prod = (float)row[c] * scale;
+                x = prod + bias;
+            } else {
+                const int64_t e = r * dd.D + c;
+                x = DT == BLS_FP16 ? half_bits(((const unsigned short *)base)[e]) : ((const float *)base)[e];
+            }
             if (rw) { const float term = rw[j] * x; acc += term; }
             else acc += x;
         }
@@ -406,9 +454,9 @@ void launch_rows(const bls_ctx *ctx, const int64_t *ridx, const float *rw, const
         const dim3 grid = xcd ? dim3((unsigned)((uint64_t)((qn + 7) / 8) * 8u * wgx)) : dim3(wgx, qn);
         const uint32_t deal = xcd ? wgx : 0u;
         // 32-bit row positions unless some shard is too large for them
-        const int64_t row_bytes = (int64_t)ctx->D * (DT == BLS_FP16 ? 2 : 4);
+        const int64_t row_stride = stride_bytes(DT, ctx->D);
         bool wide = env_int("BLS_POOL_WIDE", 0) != 0;
-        for (int q = q0; q < q0 + qn; ++q) wide = wide || ctx->q_rows[q] * (row_bytes / VB) >= 0xffffffffLL;
+        for (int q = q0; q < q0 + qn; ++q) wide = wide || ctx->q_rows[q] * (row_stride / VB) >= 0xffffffffLL;
         if (rw) {
             if (wide) pool_stream<G, DT, VB, UU, true, true><<<grid, kThreads, 0, st>>>(ctx->desc, ridx, rw, segoff, nnz, Y, to_slot, nb, chunks, deal, q0, qn);
             else pool_stream<G, DT, VB, UU, false, true><<<grid, kThreads, 0, st>>>(ctx->desc, ridx, rw, segoff, nnz, Y, to_slot, nb, chunks, deal, q0, qn);
@@ -455,7 +503,7 @@ bool dispatch_rows(const bls_ctx *ctx, int vb, int lanes, const int64_t *ridx, c
 
 int bls_launch_pool(bls_ctx *ctx, const int64_t *ridx, const float *rw, const int64_t *segoff, int64_t nnz, float *Y, int to_slot, int q0, int qn, hipStream_t st)
 {
-    const int64_t row_bytes = (int64_t)ctx->D * (ctx->dtype == BLS_FP16 ? 2 : 4);
+    const int64_t row_bytes = payload_bytes(ctx->dtype, ctx->D);
     // bytes per lane and row: 16 when the row length allows; BLS_POOL_VB overrides (for tests)
     int vb = env_int("BLS_POOL_VB", 16);
     if (vb != 16 && vb != 8 && vb != 4) vb = 16;
@@ -465,12 +513,14 @@ int bls_launch_pool(bls_ctx *ctx, const int64_t *ridx, const float *rw, const in
     if (row_bytes % vb == 0 && row_bytes <= 64 * (int64_t)vb) {
         int lanes = 1;
         while ((int64_t)lanes * vb < row_bytes) lanes <<= 1;
-        done = ctx->dtype == BLS_FP16 ? dispatch_rows<BLS_FP16>(ctx, vb, lanes, ridx, rw, segoff, nnz, Y, to_slot, q0, qn, st)
-                                      : dispatch_rows<BLS_FP32>(ctx, vb, lanes, ridx, rw, segoff, nnz, Y, to_slot, q0, qn, st);
+        done = ctx->dtype == BLS_U8_ROWQ ? dispatch_rows<BLS_U8_ROWQ>(ctx, vb, lanes, ridx, rw, segoff, nnz, Y, to_slot, q0, qn, st)
+             : ctx->dtype == BLS_FP16  ? dispatch_rows<BLS_FP16>(ctx, vb, lanes, ridx, rw, segoff, nnz, Y, to_slot, q0, qn, st)
+                                       : dispatch_rows<BLS_FP32>(ctx, vb, lanes, ridx, rw, segoff, nnz, Y, to_slot, q0, qn, st);
     }
     if (!done) {
         dim3 grid((unsigned)((ctx->B + kThreads / 64 - 1) / (kThreads / 64)), qn);
-        if (ctx->dtype == BLS_FP16) pool_rows_generic<BLS_FP16><<<grid, kThreads, 0, st>>>(ctx->desc, ridx, rw, segoff, nnz, Y, to_slot, q0);
+        if (ctx->dtype == BLS_U8_ROWQ) pool_rows_generic<BLS_U8_ROWQ><<<grid, kThreads, 0, st>>>(ctx->desc, ridx, rw, segoff, nnz, Y, to_slot, q0);
+        else if (ctx->dtype == BLS_FP16) pool_rows_generic<BLS_FP16><<<grid, kThreads, 0, st>>>(ctx->desc, ridx, rw, segoff, nnz, Y, to_slot, q0);
         else pool_rows_generic<BLS_FP32><<<grid, kThreads, 0, st>>>(ctx->desc, ridx, rw, segoff, nnz, Y, to_slot, q0);
     }
     BLS_HIP(ctx, hipGetLastError());

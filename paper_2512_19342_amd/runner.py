@@ -13,7 +13,7 @@ from . import bls
 class Pipeline:
     """Device buffers + one Context for a fixed problem shape.
 
-    ``w`` is any object with P, T, D, k, B, rows, table_owner, table_dtype ("fp32"/"fp16")
+    ``w`` is any object with P, T, D, k, B, rows, table_owner, table_dtype ("fp32" / "fp16" / "u8rq")
     and part_kind; ``tables`` are the T full tables (global row numbering) on the GPU.
     Row-wise shards are views into those tables.
     """
@@ -22,11 +22,12 @@ class Pipeline:
         dev = tables[0].device
         assert dev.type == "cuda", "the hot path runs on the GPU only"
         self.w, self.dev, self.max_nnz = w, dev, int(max_nnz)
-        dt = bls.BLS_FP16 if w.table_dtype == "fp16" else bls.BLS_FP32
+        dt = {"fp32": bls.BLS_FP32, "fp16": bls.BLS_FP16, "u8rq": bls.BLS_U8_ROWQ}[w.table_dtype]
+        width = (w.D + 8 + 15) // 16 * 16 if dt == bls.BLS_U8_ROWQ else w.D   # bytes per row-quantised row
         self.ctx = bls.Context(w.P, w.T, w.D, w.k, w.B, w.rows, w.table_owner, dt, w.part_kind)
         c = self.ctx
         for t, tab in enumerate(tables):
-            assert tab.is_contiguous() and tab.shape == (w.rows[t], w.D)
+            assert tab.is_contiguous() and tab.shape == (w.rows[t], width)
             if w.part_kind == bls.BLS_TABLE_WISE:
                 c.bls_set_shard(t, w.table_owner[t], tab)
             else:

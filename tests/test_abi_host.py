@@ -52,7 +52,7 @@ def test_configuration_is_validated(B):
 def test_sizes_and_exchange_counts_match_oracle(B, cfg):
     w = synth.workload(cfg, "small" if cfg >= 3 else "full")
     c = B.Context(w.P, w.T, w.D, w.k, w.B, w.rows, w.table_owner,
-                  B.BLS_FP16 if w.table_dtype == "fp16" else B.BLS_FP32, w.part_kind)
+                  w.dtype_code, w.part_kind)
     sz = c.bls_sizes(12345)
     n_float = w.F * w.T * w.B * w.D
     assert sz["pooled_bytes"] == sz["send_bytes"] == sz["slot_bytes"] == 4 * n_float

@@ -31,10 +31,27 @@ def layout(w):
     return first, n_loc, loc, nsum
 
 
-@pytest.mark.parametrize("cfg", [3, 4, 5])
-def test_full_size(cfg):
+def bag_sum32(w, t, idx):
+    """fp32 sum, in order, of rows idx of table t: the rows are regenerated on the host and handed
+    to the oracle (as a little table of their own when the storage is row-quantised)."""
+    ids = torch.from_numpy(np.ascontiguousarray(idx))
+    if w.table_dtype == "u8rq":
+        n = len(idx)
+        if n == 0:
+            return np.zeros(w.D, np.float32)
+        mini = oracle.Case(1, 1, w.D, 1, 0, [n], [0], 2)
+        _, o32 = oracle.embbag_plain(mini, [synth.rowq_rows(w, t, ids).numpy()], np.arange(n, dtype=np.int64),
+                                     np.array([0, n], np.int64))
+        return o32.reshape(w.D)
+    return oracle.bag_sum(synth.table_rows(w, t, ids).numpy().reshape(-1, w.D))[0]
+
+
+@pytest.mark.parametrize("cfg,storage", [(3, None), (4, None), (5, None), (4, "u8rq")])
+def test_full_size(cfg, storage):
     from paper_2512_19342_amd.runner import Pipeline
     w = synth.workload(cfg, "full")
+    if storage:
+        w.table_dtype = storage
     dev = torch.device("cuda:0")
     print(f"full-size parity {w.name}: generating {w.table_bytes() / 1e9:.1f} GB of tables", flush=True)
     tabs = [synth.make_table(w, t, dev) for t in range(w.T)]
@@ -70,8 +87,7 @@ def test_full_size(cfg):
         idx = ix_h[off_h[g]:off_h[g + 1]]
         s = next(r for r in range(P) if b < first[r + 1])
         b_loc, n = b - first[s], first[s + 1] - first[s]
-        rows = synth.table_rows(w, t, torch.from_numpy(idx)).numpy()
-        whole32, _ = oracle.bag_sum(rows)
+        whole32 = bag_sum32(w, t, idx)
         assert np.array_equal(out[b, t].cpu().numpy().view(np.uint32), whole32.view(np.uint32)), (t, b)
         owners = [w.table_owner[t]] if w.part_kind == 0 else range(P)
         for d in owners:
@@ -79,7 +95,7 @@ def test_full_size(cfg):
                 part32 = whole32
             else:
                 rps = -(-w.rows[t] // P)
-                part32, _ = oracle.bag_sum(rows[idx // rps == d].reshape(-1, D))
+                part32 = bag_sum32(w, t, idx[idx // rps == d])
             q = int(nsum[d]) + loc[t]
             sigma = int(nsum[d]) * B + n_loc[d] * first[s] + loc[t] * n + b_loc
             rho = w.F * T * first[s] + q * n + b_loc

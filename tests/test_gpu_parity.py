@@ -4,7 +4,8 @@ Integer outputs (counts, displacements, ridx, segoff, perm) and every fp32 buffe
 send, receive slot, output) must equal the oracle's bit for bit: both sides add a segment's
 rows in segment order from +0 and, for row-wise partitions, the P partial vectors in
 increasing owner rank.  Against the plain float64 definition the bound is
-|x - exact| <= tol * sum|terms| with tol = 1e-6 for fp32 tables and 1e-3 for fp16 storage.
+|x - exact| <= tol * sum|terms| with tol = 1e-6 for fp32 tables and 1e-3 for fp16 storage; row-quantised 8-bit tables decode to
+fp32 numbers (the same two roundings on both sides) and are held to the fp32 bound.
 """
 import numpy as np
 import pytest
@@ -15,7 +16,7 @@ import synth
 
 pytestmark = pytest.mark.gpu
 
-TOL = {"fp32": 1e-6, "fp16": 1e-3}
+TOL = {"fp32": 1e-6, "fp16": 1e-3, "u8rq": 1e-6}
 
 
 def case_of(w):
@@ -106,7 +107,7 @@ EDGE = [
 
 
 @pytest.mark.parametrize("spec", EDGE)
-@pytest.mark.parametrize("dtype", ["fp32", "fp16"])
+@pytest.mark.parametrize("dtype", ["fp32", "fp16", "u8rq"])
 def test_edge_shapes(spec, dtype):
     w = synth.custom("edge", k=1, values="gauss", table_dtype=dtype, seed=23,
                      index_dist=("zipf", 1.1), **spec)
@@ -114,6 +115,33 @@ def test_edge_shapes(spec, dtype):
     batches = [synth.make_batch(w, it) for it in range(2)]
     got, _ = run_gpu(w, tabs, batches)
     check_against_oracle(w, tabs, batches, got)
+
+
+ROWQ = [
+    dict(P=2, T=3, D=16, B=90, part_kind=0, rows=[300, 17, 1000], bag=("uniform", 0, 40)),    # one lane per row
+    dict(P=3, T=2, D=32, B=100, part_kind=1, rows=[4000, 50], bag=("uniform", 0, 30)),        # two lanes
+    dict(P=4, T=4, D=64, B=257, part_kind=0, rows=[5000, 64, 900, 33], bag=("uniform", 0, 60)),   # four lanes, streams
+    dict(P=8, T=3, D=128, B=1000, part_kind=1, rows=[20000, 3000, 129], bag=("uniform", 1, 64)),  # the benchmark's row
+    dict(P=2, T=2, D=20, B=64, part_kind=0, rows=[100, 200], bag=("uniform", 0, 12)),         # 4 bytes per lane, 5 of 8 lanes
+    dict(P=2, T=2, D=1024, B=24, part_kind=1, rows=[300, 77], bag=("uniform", 0, 9)),         # a whole wavefront per row
+    dict(P=2, T=2, D=2048, B=12, part_kind=0, rows=[50, 60], bag=("uniform", 0, 5)),          # longer than 64 lanes cover
+]
+
+
+@pytest.mark.parametrize("spec", ROWQ, ids=lambda s: f"D{s['D']}-P{s['P']}-part{s['part_kind']}")
+@pytest.mark.parametrize("values", ["gauss", "grid"])
+def test_row_quantised_tables(spec, values):
+    """8-bit codes with a scale and a bias per row: decoding (two fp32 roundings) and the ordered
+    sum must give the oracle's bits for every row length the kernels treat differently."""
+    w = synth.custom("rowq", k=2, values=values, table_dtype="u8rq", seed=37, index_dist=("zipf", 1.05), **spec)
+    tabs = [synth.make_table(w, t) for t in range(w.T)]
+    batches = [synth.make_batch(w, it) for it in range(2)]
+    got, _ = run_gpu(w, tabs, batches)
+    check_against_oracle(w, tabs, batches, got)
+    if values == "grid":                                      # exact values: fp64 definition, bit for bit
+        o64, _ = oracle.embbag_plain(case_of(w), [t.numpy() for t in tabs], batches[0][0].numpy(),
+                                     batches[0][1].numpy(), want32=False)
+        assert np.array_equal(got[0]["Out"].astype(np.float64), o64)
 
 
 def test_all_bags_empty():
@@ -267,7 +295,9 @@ def test_pool_launch_variants(vb, nb, xcd, monkeypatch):
 FUSED = [synth.workload(1), synth.workload(2), synth.workload(3, "small"), synth.workload(4, "small"),
          synth.workload(5, "small")] + [
     synth.custom("edge", k=2, values="gauss", table_dtype=dt, seed=29, index_dist=("zipf", 1.1), **EDGE[i])
-    for i in (2, 4, 5, 6, 7, 8, 10) for dt in ("fp32", "fp16")]
+    for i in (2, 4, 5, 6, 7, 8, 10) for dt in ("fp32", "fp16")] + [
+    synth.custom("edge", k=2, values="gauss", table_dtype="u8rq", seed=29, index_dist=("zipf", 1.1), **EDGE[i])
+    for i in (5, 7, 9)]
 
 
 @pytest.mark.parametrize("w", FUSED, ids=lambda w: f"{w.name}-{w.table_dtype}-D{w.D}-P{w.P}")
@@ -325,7 +355,9 @@ def test_pool_put_needs_the_current_slot():
 WEIGHTED = [synth.workload(2), synth.workload(3, "small"), synth.workload(4, "small"), synth.workload(5, "small"),
             synth.workload(6, "small")] + [
     synth.custom("edge", k=1, values="gauss", table_dtype=dt, seed=31, index_dist=("zipf", 1.1), **EDGE[i])
-    for i in (1, 2, 4, 5, 6, 7, 8, 10) for dt in ("fp32", "fp16")]
+    for i in (1, 2, 4, 5, 6, 7, 8, 10) for dt in ("fp32", "fp16")] + [
+    synth.custom("edge", k=1, values="gauss", table_dtype="u8rq", seed=31, index_dist=("zipf", 1.1), **EDGE[i])
+    for i in (4, 6, 7, 9, 10)]
 
 
 @pytest.mark.parametrize("w", WEIGHTED, ids=lambda w: f"{w.name}-{w.table_dtype}-D{w.D}-P{w.P}-part{w.part_kind}")
