@@ -25,7 +25,7 @@ def build(force: bool = False) -> str:
     """Compile the C oracle with the host compiler (no fused multiply-add contraction)."""
     if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
         subprocess.check_call(["gcc", "-O2", "-ffp-contract=off", "-std=c99", "-Wall", "-Wextra",
-                               "-shared", "-fPIC", "-o", _LIB, _SRC])
+                               "-shared", "-fPIC", "-o", _LIB, _SRC, "-lm"])
     return _LIB
 
 
@@ -229,6 +229,57 @@ def pipeline(case: Case, tables: List[np.ndarray], indices, offsets, weights=Non
     r["R"] = exchange(case, r["S"])
     r["Out"] = unpack(case, r["R"], offsets if mean else None)
     return r
+
+
+# ----------------------------------------------------------------------------- dense layers
+
+def _f64(a) -> np.ndarray:
+    return np.ascontiguousarray(np.asarray(a, dtype=np.float64))
+
+
+def mlp_layer(x, W, bias, act: int, err_in=None, want_err: bool = True):
+    """act(x @ W.T + bias) in double; x [M, K] (any float dtype), W [N, K] fp32, bias [N] fp32 or None.
+    Returns (y [M, N] float64, err [M, N] float64 bound for an fp32 implementation, or None)."""
+    x = _f64(x)
+    W = np.ascontiguousarray(W, dtype=np.float32)
+    M, K = x.shape
+    N = W.shape[0]
+    assert W.shape == (N, K)
+    if bias is not None:
+        bias = np.ascontiguousarray(bias, dtype=np.float32)
+        assert bias.shape == (N,)
+    if err_in is not None:
+        err_in = _f64(err_in)
+        assert err_in.shape == x.shape
+    y = np.zeros((M, N), np.float64)
+    err = np.zeros((M, N), np.float64) if want_err else None
+    _chk("orc_mlp_layer", _load().orc_mlp_layer(C.c_int64(M), C.c_int(K), C.c_int(N), _p(x), _p(W), _p(bias),
+                                                C.c_int(act), _p(err_in), _p(y), _p(err)))
+    return y, err
+
+
+def mlp(x, layers, err_in=None):
+    """A stack of layers [(W, bias, act), ...]; returns the last output and its error bound."""
+    y, err = _f64(x), err_in
+    for W, bias, act in layers:
+        y, err = mlp_layer(y, W, bias, act, err)
+    return y, err
+
+
+def interact(x, emb, err_x=None, want_err: bool = True):
+    """x [B, D] (double), emb [B, T, D] fp32 -> z [B, D + T(T+1)/2] double and its error bound."""
+    x = _f64(x)
+    emb = np.ascontiguousarray(emb, dtype=np.float32)
+    B, T, D = emb.shape
+    assert x.shape == (B, D)
+    if err_x is not None:
+        err_x = _f64(err_x)
+    Wd = D + T * (T + 1) // 2
+    z = np.zeros((B, Wd), np.float64)
+    err = np.zeros((B, Wd), np.float64) if want_err else None
+    _chk("orc_interact", _load().orc_interact(C.c_int64(B), C.c_int(T), C.c_int(D), _p(x), _p(emb), _p(err_x),
+                                              _p(z), _p(err)))
+    return z, err
 
 
 # ----------------------------------------------------------------------------- ring model

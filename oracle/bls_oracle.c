@@ -569,3 +569,87 @@ int orc_bag_sum(int D, int64_t n, const float *rows_nd, float *out32, double *ou
     }
     return ORC_OK;
 }
+
+/* ---- dense part of the model around the lookup ------------------------------------- */
+
+#include <math.h>
+
+#define ORC_U32 5.9604644775390625e-08 /* 2^-24, unit roundoff of fp32 */
+
+/*
+ * One layer of apply_mlp (Listings 1 and 2; the model overview in the Introduction: a
+ * bottom MLP on the dense features, a top MLP that produces the prediction):
+ *   y[m][n] = act( bias[n] + sum_k x[m][k] * W[n][k] ),  W stored [N][K] as a linear layer's
+ * weight, act 0 = identity, 1 = ReLU, 2 = logistic sigmoid.  Everything in double.
+ * The paper does not give layer sizes or activations; reading: the reference model's ReLU
+ * layers with a sigmoid on the last top layer.
+ *
+ * err_in (nullable, [M][K]) bounds how far an fp32 implementation's input may be from x;
+ * err_out (nullable, [M][N]) receives a bound for its output: the input error carried
+ * through |W|, plus (K + 3) roundings of relative size 2^-24 on the sum of magnitudes, plus
+ * a few units for the activation (ReLU and the sigmoid do not amplify).
+ */
+int orc_mlp_layer(int64_t M, int K, int N, const double *x, const float *W, const float *bias, int act,
+                  const double *err_in, double *y, double *err_out)
+{
+    int64_t m;
+    int n, k;
+    if (M < 0 || K < 1 || N < 1 || act < 0 || act > 2) return ORC_EINVAL;
+    for (m = 0; m < M; ++m)
+        for (n = 0; n < N; ++n) {
+            double acc = bias ? (double)bias[n] : 0.0;
+            double mass = bias ? fabs((double)bias[n]) : 0.0, carried = 0.0, v, e;
+            for (k = 0; k < K; ++k) {
+                double w = (double)W[(int64_t)n * K + k], xv = x[m * K + k];
+                acc += xv * w;
+                mass += fabs(xv * w);
+                if (err_in) { carried += fabs(w) * err_in[m * K + k]; mass += fabs(w) * err_in[m * K + k]; }
+            }
+            e = carried + (double)(K + 3) * ORC_U32 * mass;
+            if (act == 1) v = acc > 0.0 ? acc : 0.0;
+            else if (act == 2) { v = 1.0 / (1.0 + exp(-acc)); e = 0.25 * e + 8.0 * ORC_U32; }
+            else v = acc;
+            y[m * N + n] = v;
+            if (err_out) err_out[m * N + n] = e;
+        }
+    return ORC_OK;
+}
+
+/*
+ * interact_features (Listings 1 and 2; Introduction: "an explicit dot-interaction layer"):
+ * per sample the D-vector x from the bottom MLP and the T pooled embedding vectors form
+ * Z = [x; e_0; ...; e_{T-1}] ((T+1) x D); the output is x followed by the dot products
+ * Z_i . Z_j for every pair i > j, ordered by i, then j (the reference model's order; the
+ * diagonal is left out).  z is [B][D + T(T+1)/2], everything in double.
+ * err_x / err_z as in orc_mlp_layer; the embedding vectors are taken as exact.
+ */
+int orc_interact(int64_t B, int T, int D, const double *x, const float *emb, const double *err_x,
+                 double *z, double *err_z)
+{
+    int64_t b, W = (int64_t)D + (int64_t)T * (T + 1) / 2;
+    int i, j, c;
+    if (B < 0 || T < 1 || D < 1) return ORC_EINVAL;
+    for (b = 0; b < B; ++b) {
+        int64_t at = D;
+        for (c = 0; c < D; ++c) {
+            z[b * W + c] = x[b * D + c];
+            if (err_z) err_z[b * W + c] = err_x ? err_x[b * D + c] : 0.0;
+        }
+        for (i = 1; i <= T; ++i)
+            for (j = 0; j < i; ++j) {
+                const float *ei = emb + (b * T + (i - 1)) * D;
+                double dot = 0.0, mass = 0.0, carried = 0.0;
+                for (c = 0; c < D; ++c) {
+                    double u = (double)ei[c];
+                    double v = j == 0 ? x[b * D + c] : (double)emb[(b * T + (j - 1)) * D + c];
+                    dot += u * v;
+                    mass += fabs(u * v);
+                    if (j == 0 && err_x) { carried += fabs(u) * err_x[b * D + c]; mass += fabs(u) * err_x[b * D + c]; }
+                }
+                z[b * W + at] = dot;
+                if (err_z) err_z[b * W + at] = carried + (double)(D + 2) * ORC_U32 * mass;
+                ++at;
+            }
+    }
+    return ORC_OK;
+}

@@ -387,3 +387,44 @@ def make_batch(w: Workload, it: int, device="cpu") -> Tuple[torch.Tensor, torch.
     torch.cumsum(torch.cat(lens), 0, out=offsets[1:])
     indices = torch.cat(idx) if idx else torch.zeros(0, dtype=torch.int64, device=device)
     return indices, offsets
+
+
+# ----------------------------------------------------------------------------- dense part of the model
+
+_P_DENSE, _P_MLP = 5, 6
+N_DENSE = 13                      # dense features per sample of the click-log datasets the paper uses
+
+
+def _bell(key: int, n: int, device="cpu") -> torch.Tensor:
+    """n values with mean 0 and variance 1, bell-shaped: a centred, scaled sum of four hash bytes."""
+    h = hash_u64(key, torch.arange(n, dtype=torch.int64, device=device))
+    s = (h & 255) + ((h >> 8) & 255) + ((h >> 16) & 255) + ((h >> 24) & 255) - 510
+    return s.to(torch.float32) * (1.0 / 147.8)               # sd of a uniform byte is 73.9; four of them: 147.8
+
+
+def dense_features(w: Workload, it: int, device="cpu") -> torch.Tensor:
+    """Dense inputs of iteration ``it``: ``[B, N_DENSE]`` fp32 uniforms in [0, 1)."""
+    u = uniform01(stream_key(w.seed, _P_DENSE, it), torch.arange(w.B * N_DENSE, dtype=torch.int64, device=device))
+    return u.to(torch.float32).reshape(w.B, N_DENSE)
+
+
+def mlp_sizes(w: Workload, size: str = "full") -> Tuple[List[int], List[int]]:
+    """Layer widths (bottom, top).  The paper builds on the reference recommendation model and
+    gives no widths; "full" takes that model's large configuration around the workload's D and T
+    (bottom 13-512-256-D, top z-1024-1024-512-256-1 with z = D + T(T+1)/2), "small" a narrow
+    stack for tests the CPU oracle finishes quickly."""
+    zdim = w.D + w.T * (w.T + 1) // 2
+    if size == "full":
+        return [N_DENSE, 512, 256, w.D], [zdim, 1024, 1024, 512, 256, 1]
+    return [N_DENSE, 40, w.D], [zdim, 72, 24, 1]
+
+
+def mlp_weights(w: Workload, sizes: List[int], which: int, device="cpu"):
+    """Seeded layers ``[(W [N, K], bias [N]), ...]`` for widths ``sizes``: W ~ N(0, 2/(K+N)),
+    bias ~ N(0, 1/N) (the reference model's initialisation), values from the hash."""
+    layers = []
+    for i, (K, N) in enumerate(zip(sizes[:-1], sizes[1:])):
+        W = _bell(stream_key(w.seed, _P_MLP, which, i, 0), N * K, device).reshape(N, K) * math.sqrt(2.0 / (K + N))
+        b = _bell(stream_key(w.seed, _P_MLP, which, i, 1), N, device) * math.sqrt(1.0 / N)
+        layers.append((W.contiguous(), b.contiguous()))
+    return layers

@@ -46,6 +46,15 @@ MUTATIONS = {
     "row-quantised codes read as signed": ("prod = (float)p[c] * scale;", "prod = (float)(int8_t)p[c] * scale;"),
     "row-quantised decoding rounded once": ("prod = (float)p[c] * scale;\n        return prod + bias;",
                                             "return (float)((double)p[c] * (double)scale + (double)bias);"),
+    "layer weight read transposed": ("double w = (double)W[(int64_t)n * K + k], xv = x[m * K + k];",
+                                     "double w = (double)W[(int64_t)k * N + n], xv = x[m * K + k];"),
+    "layer bias dropped": ("double acc = bias ? (double)bias[n] : 0.0;", "double acc = 0.0;"),
+    "relu lets negatives through": ("if (act == 1) v = acc > 0.0 ? acc : 0.0;", "if (act == 1) v = acc;"),
+    "sigmoid of the wrong sign": ("v = 1.0 / (1.0 + exp(-acc));", "v = 1.0 / (1.0 + exp(acc));"),
+    "interaction pairs ordered by j": ("for (i = 1; i <= T; ++i)\n            for (j = 0; j < i; ++j) {\n                const float *ei",
+                                       "for (j = 0; j < T; ++j)\n            for (i = j + 1; i <= T; ++i) {\n                const float *ei"),
+    "interaction keeps the diagonal": ("for (j = 0; j < i; ++j) {\n                const float *ei", "for (j = 1; j <= i; ++j) {\n                const float *ei"),
+    "interaction pairs the wrong embedding": ("(double)emb[(b * T + (j - 1)) * D + c]", "(double)emb[(b * T + j) * D + c]"),
     "half subnormals flushed": ("if (m == 0) bits = sign;\n        else {", "if (m >= 0) bits = sign;\n        else {"),
 }
 
@@ -67,6 +76,9 @@ PINS = [
     lambda: pins.test_rowq_stride_and_padding(),
     lambda: pins.test_rowq_decoding_rounds_twice_in_fp32(),
     lambda: pins.test_rowq_pipeline_against_decoded_fp32_tables(1),
+    lambda: pins.test_mlp_layer_brute_force_and_closed_forms(),
+    lambda: pins.test_mlp_layer_against_torch_linear(2),
+    lambda: pins.test_interact_brute_force_order_and_torch(),
 ]
 
 
@@ -78,7 +90,7 @@ def test_planted_mistake_is_caught(name, tmp_path, monkeypatch):
     mutated = tmp_path / "mut.c"
     mutated.write_text(src.replace(old, new, 1))
     lib = tmp_path / "libmut.so"
-    subprocess.check_call(["gcc", "-O1", "-ffp-contract=off", "-std=c99", "-shared", "-fPIC", "-o", str(lib), str(mutated)])
+    subprocess.check_call(["gcc", "-O1", "-ffp-contract=off", "-std=c99", "-shared", "-fPIC", "-o", str(lib), str(mutated), "-lm"])
     monkeypatch.setattr(oracle, "_lib", ctypes.CDLL(str(lib)))
     caught = 0
     for pin in PINS:

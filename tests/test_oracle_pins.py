@@ -665,3 +665,108 @@ def test_rowq_grid_tables_are_exact():
     assert np.array_equal(o64, o32.astype(np.float64)) and np.abs(o64).max() > 1.0
     res = oracle.pipeline(case_of(w), tabs, ix.numpy(), off.numpy())
     assert np.array_equal(res["Out"], o32)
+
+
+# ----------------------------------------------------------------------------- dense layers and interaction
+
+def test_mlp_layer_brute_force_and_closed_forms():
+    rng = np.random.default_rng(5)
+    M, K, N = 4, 6, 3
+    x = rng.normal(size=(M, K))
+    W = rng.normal(size=(N, K)).astype(np.float32)
+    b = rng.normal(size=N).astype(np.float32)
+    for act in (0, 1, 2):
+        y, _ = oracle.mlp_layer(x, W, b, act)
+        for m in range(M):
+            for n in range(N):
+                v = float(b[n]) + sum(x[m, k] * float(W[n, k]) for k in range(K))
+                want = v if act == 0 else max(v, 0.0) if act == 1 else 1.0 / (1.0 + np.exp(-v))
+                assert abs(y[m, n] - want) <= 1e-14 * max(1.0, abs(want)), (act, m, n)
+    # identity weights: the layer is act(x + b); a one-hot row of W picks a column of x
+    eye = np.eye(K, dtype=np.float32)
+    bb = np.arange(K, dtype=np.float32) - 2
+    y, _ = oracle.mlp_layer(x, eye, bb, 1)
+    assert np.array_equal(y, np.maximum(x + bb, 0.0))
+    pick = np.zeros((2, K), np.float32)
+    pick[0, 4], pick[1, 1] = 1.0, -2.0
+    y, _ = oracle.mlp_layer(x, pick, None, 0)
+    assert np.array_equal(y[:, 0], x[:, 4]) and np.array_equal(y[:, 1], -2.0 * x[:, 1])
+    assert oracle.mlp_layer(np.zeros((3, K)), W, b, 2)[0][0, 0] == 1.0 / (1.0 + np.exp(-float(b[0])))
+
+
+@pytest.mark.parametrize("act", [0, 1, 2])
+def test_mlp_layer_against_torch_linear(act):
+    rng = np.random.default_rng(6)
+    M, K, N = 33, 29, 17
+    x = rng.normal(size=(M, K))
+    W = rng.normal(size=(N, K)).astype(np.float32)
+    b = rng.normal(size=N).astype(np.float32)
+    y, _ = oracle.mlp_layer(x, W, b, act)
+    ref = torch.nn.functional.linear(torch.from_numpy(x), torch.from_numpy(W).double(), torch.from_numpy(b).double())
+    ref = ref if act == 0 else torch.relu(ref) if act == 1 else torch.sigmoid(ref)
+    assert np.allclose(y, ref.numpy(), rtol=1e-13, atol=1e-13)
+
+
+def test_interact_brute_force_order_and_torch():
+    rng = np.random.default_rng(7)
+    B, T, D = 3, 5, 4
+    x = rng.normal(size=(B, D))
+    emb = rng.normal(size=(B, T, D)).astype(np.float32)
+    z, _ = oracle.interact(x, emb)
+    assert z.shape == (B, D + T * (T + 1) // 2)
+    for b in range(B):
+        Z = [x[b]] + [emb[b, t].astype(np.float64) for t in range(T)]
+        want = list(x[b])
+        for i in range(T + 1):
+            for j in range(i):                                # i > j, ordered by i then j, no diagonal
+                want.append(float(np.dot(Z[i], Z[j])))
+        assert np.allclose(z[b], want, rtol=1e-14, atol=1e-14)
+    # library route: batched Gram matrix and the strictly lower triangle in row-major order
+    Zt = torch.cat([torch.from_numpy(x)[:, None, :], torch.from_numpy(emb).double()], dim=1)
+    G = torch.bmm(Zt, Zt.transpose(1, 2))
+    li, lj = torch.tril_indices(T + 1, T + 1, offset=-1)
+    ref = torch.cat([torch.from_numpy(x), G[:, li, lj]], dim=1)
+    assert np.allclose(z, ref.numpy(), rtol=1e-13, atol=1e-13)
+    # every pair is told apart: Z_i = a_i * e_0 with a = 1 and distinct primes, so Z_i . Z_j = a_i a_j
+    a = [1.0, 2.0, 3.0, 5.0, 7.0, 11.0, 13.0]
+    Zc = np.zeros((len(a), 3))
+    Zc[:, 0] = a
+    zz, _ = oracle.interact(Zc[None, 0], Zc[None, 1:].astype(np.float32))
+    want = [a[i] * a[j] for i in range(1, len(a)) for j in range(i)]
+    assert len(set(want)) == len(want) and list(zz[0, 3:]) == want
+
+
+def test_dense_error_bounds_hold_for_an_fp32_implementation():
+    """The bound the GPU tests rely on: a plain fp32 evaluation (numpy, any summation order numpy
+    picks) stays inside it, through a chain of layers and the interaction; and it is not vacuous."""
+    w = synth.custom("dense", P=2, T=5, D=16, B=48, k=1, part_kind=0, rows=[10] * 5, seed=3)
+    bot, top = synth.mlp_sizes(w, "small")
+    Lb = [(W.numpy(), b.numpy(), 1) for W, b in synth.mlp_weights(w, bot, 0)]
+    Lt = [(W.numpy(), b.numpy(), 1) for W, b in synth.mlp_weights(w, top, 1)]
+    Lt[-1] = (Lt[-1][0], Lt[-1][1], 2)
+    dense = synth.dense_features(w, 0).numpy()
+    emb = np.random.default_rng(1).normal(0, 0.3, size=(w.B, w.T, w.D)).astype(np.float32)
+    x, ex = oracle.mlp(dense, Lb)
+    z, ez = oracle.interact(x, emb, ex)
+    p, ep = oracle.mlp(z, Lt, ez)
+
+    def f32_layer(a, W, b, act):
+        v = (a.astype(np.float32) @ W.T.astype(np.float32) + b).astype(np.float32)
+        return np.maximum(v, 0) if act == 1 else (1 / (1 + np.exp(-v))).astype(np.float32) if act == 2 else v
+    a = dense
+    for W, b, act in Lb:
+        a = f32_layer(a, W, b, act)
+    assert np.all(np.abs(a - x) <= ex) and ex.max() < 1e-4 * max(1.0, np.abs(x).max())
+    Z = np.concatenate([a[:, None, :], emb], axis=1)
+    G = np.einsum("bid,bjd->bij", Z, Z).astype(np.float32)
+    li, lj = np.tril_indices(w.T + 1, -1)
+    zf = np.concatenate([a, G[:, li, lj]], axis=1)
+    assert np.all(np.abs(zf - z) <= ez)
+    for W, b, act in Lt:
+        zf = f32_layer(zf, W, b, act)
+    assert np.all(np.abs(zf - p) <= ep) and ep.max() < 2e-3      # worst case carried through six layers
+    # one layer on exact inputs: the bound is (K + 3) roundings on the sum of magnitudes, a few 1e-6
+    y1, e1 = oracle.mlp_layer(z, Lt[0][0], Lt[0][1], 1)
+    assert np.all(np.abs(f32_layer(z.astype(np.float32), *Lt[0]) - oracle.mlp_layer(z.astype(np.float32), Lt[0][0], Lt[0][1], 1)[0]) <= e1)
+    assert e1.max() < 2e-5 * max(1.0, np.abs(y1).max())
+    assert p.shape == (w.B, 1) and np.all((p > 0) & (p < 1)) and p.std() > 1e-3
