@@ -223,6 +223,28 @@ int bls_rank_complete(bls_ctx *ctx, int32_t rank, int64_t iter, const int64_t *d
                       void *hip_stream);
 int bls_rank_delay(bls_ctx *ctx, uint32_t microseconds, void *hip_stream);
 
+/*
+ * The dense part of the model around the lookup (Introduction: dense features go through the
+ * bottom MLP, the pooled vectors and its output through an explicit dot-interaction layer and
+ * the top MLP; Listings 1 and 2: apply_mlp, interact_features).  fp32 in, fp32 out, products
+ * accumulated in fp32 on the matrix cores; the summation order is the hardware's, so results
+ * match a double-precision evaluation to within (K + 3) * 2^-24 * (|bias| + sum |x||w|).
+ *
+ * bls_mlp_layer: d_y[M][N] = act(d_x[M][K] * d_W[N][K]^T + d_bias[N]); d_bias may be NULL;
+ *   act is BLS_ACT_NONE, BLS_ACT_RELU or BLS_ACT_SIGMOID.  All arrays row-major device memory,
+ *   d_y must not overlap the inputs.  M >= 0, 1 <= K, N < 2^31 / 128.
+ * bls_interact: for samples b0 .. b0+bn-1 (b0 + bn <= B), with Z = [d_x[b]; d_emb[b][0..T-1]]
+ *   ((T+1) vectors of length D): d_z[b] = d_x[b] followed by Z_i . Z_j for all pairs i > j in
+ *   the order i = 1..T, j = 0..i-1.  d_x is [B][D], d_emb is [B][T][D] (the output of
+ *   bls_unpack), d_z is [B][D + T(T+1)/2].  BLS_EINVAL if the T vectors of a sample do not
+ *   fit in 64 KB of LDS (about T * D <= 16000).
+ */
+enum { BLS_ACT_NONE = 0, BLS_ACT_RELU = 1, BLS_ACT_SIGMOID = 2 };
+int bls_mlp_layer(bls_ctx *ctx, const float *d_x, int64_t M, int32_t K, const float *d_W, const float *d_bias,
+                  int32_t N, int32_t act, float *d_y, void *hip_stream);
+int bls_interact(bls_ctx *ctx, const float *d_x, const float *d_emb, float *d_z, int64_t b0, int64_t bn,
+                 void *hip_stream);
+
 /* Ring state for callers and tests: next iteration number, oldest in flight, K. */
 int bls_ring_state(const bls_ctx *ctx, int64_t *head, int64_t *tail, int32_t *K);
 

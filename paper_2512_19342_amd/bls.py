@@ -16,13 +16,14 @@ import torch
 BLS_OK, BLS_EINVAL, BLS_ERANGE, BLS_ENOSPC = 0, -1, -2, -3
 BLS_ERING_FULL, BLS_ERING_EMPTY, BLS_EORDER, BLS_EHIP = -4, -5, -6, -7
 BLS_FP32, BLS_FP16, BLS_U8_ROWQ = 0, 1, 2
+BLS_ACT_NONE, BLS_ACT_RELU, BLS_ACT_SIGMOID = 0, 1, 2
 BLS_TABLE_WISE, BLS_ROW_WISE = 0, 1
 
 EXPORTS = [
     "bls_create", "bls_destroy", "bls_set_shard", "bls_sizes", "bls_pooled_counts", "bls_plan", "bls_plan_weighted",
     "bls_embbag_pool", "bls_embbag_pool_weighted", "bls_embbag_pool_put", "bls_embbag_pool_put_weighted", "bls_pack",
     "bls_set_ring", "bls_ring_advance", "bls_alltoallv_local", "bls_unpack", "bls_unpack_mean", "bls_ring_state",
-    "bls_rank_put", "bls_rank_complete", "bls_rank_delay", "bls_check", "bls_last_error",
+    "bls_rank_put", "bls_rank_complete", "bls_rank_delay", "bls_mlp_layer", "bls_interact", "bls_check", "bls_last_error",
 ]
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
@@ -71,6 +72,8 @@ def lib() -> C.CDLL:
         L.bls_alltoallv_local.argtypes = [vp, vp, C.c_int32, vp]
         L.bls_unpack.argtypes = [vp, C.c_int64, vp, vp]
         L.bls_ring_state.argtypes = [vp, C.POINTER(C.c_int64), C.POINTER(C.c_int64), C.POINTER(C.c_int32)]
+        L.bls_mlp_layer.argtypes = [vp, vp, C.c_int64, C.c_int32, vp, vp, C.c_int32, C.c_int32, vp, vp]
+        L.bls_interact.argtypes = [vp, vp, vp, vp, C.c_int64, C.c_int64, vp]
         L.bls_check.argtypes = [vp, vp]
         L.bls_last_error.argtypes = [vp]
         L.bls_last_error.restype = C.c_char_p
@@ -212,6 +215,18 @@ class Context:
 
     def bls_rank_delay(self, microseconds, stream=None):
         self._call("bls_rank_delay", int(microseconds), _stream(stream))
+
+    def bls_mlp_layer(self, x, W, bias, act, y, stream=None):
+        """y[M, N] = act(x[M, K] @ W[N, K].T + bias); shapes are taken from the tensors."""
+        M, K = x.shape
+        N = W.shape[0]
+        assert W.shape == (N, K) and y.shape == (M, N) and x.is_contiguous() and W.is_contiguous() and y.is_contiguous()
+        assert x.dtype == W.dtype == y.dtype == torch.float32 and (bias is None or bias.shape == (N,))
+        self._call("bls_mlp_layer", _ptr(x), int(M), int(K), _ptr(W), _ptr(bias), int(N), int(act), _ptr(y), _stream(stream))
+
+    def bls_interact(self, x, emb, z, b0=0, bn=None, stream=None):
+        self._call("bls_interact", _ptr(x), _ptr(emb), _ptr(z), int(b0), int(self.B - b0 if bn is None else bn),
+                   _stream(stream))
 
     def bls_ring_state(self):
         h, t, k = C.c_int64(), C.c_int64(), C.c_int32()

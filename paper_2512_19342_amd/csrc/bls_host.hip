@@ -509,6 +509,29 @@ extern "C" int bls_rank_delay(bls_ctx *ctx, uint32_t microseconds, void *hip_str
     return bls_launch_delay(ctx, microseconds, (hipStream_t)hip_stream);
 }
 
+extern "C" int bls_mlp_layer(bls_ctx *ctx, const float *d_x, int64_t M, int32_t K, const float *d_W, const float *d_bias,
+                             int32_t N, int32_t act, float *d_y, void *hip_stream)
+{
+    if (!ctx) return BLS_EINVAL;
+    if (M < 0 || K < 1 || N < 1 || K > 0x7fffffff / 128 || N > 0x7fffffff / 128)
+        return bls_fail(ctx, BLS_EINVAL, "bls_mlp_layer: bad shape");
+    if (act != BLS_ACT_NONE && act != BLS_ACT_RELU && act != BLS_ACT_SIGMOID)
+        return bls_fail(ctx, BLS_EINVAL, "bls_mlp_layer: unknown activation");
+    if (M > 0 && (!d_x || !d_W || !d_y)) return bls_fail(ctx, BLS_EINVAL, "bls_mlp_layer: NULL array");
+    return bls_launch_mlp_layer(ctx, d_x, M, K, d_W, d_bias, N, act, d_y, (hipStream_t)hip_stream);
+}
+
+extern "C" int bls_interact(bls_ctx *ctx, const float *d_x, const float *d_emb, float *d_z, int64_t b0, int64_t bn,
+                            void *hip_stream)
+{
+    if (!ctx) return BLS_EINVAL;
+    if (b0 < 0 || bn < 0 || b0 + bn > ctx->B) return bls_fail(ctx, BLS_EINVAL, "bls_interact: samples outside the batch");
+    if (bls_interact_lds_bytes(ctx->T, ctx->D) > 64 * 1024)
+        return bls_fail(ctx, BLS_EINVAL, "bls_interact: the pooled vectors of one sample do not fit in 64 KB of LDS");
+    if (bn > 0 && (!d_x || !d_emb || !d_z)) return bls_fail(ctx, BLS_EINVAL, "bls_interact: NULL array");
+    return bls_launch_interact(ctx, d_x, d_emb, d_z, (uint32_t)b0, (uint32_t)bn, (hipStream_t)hip_stream);
+}
+
 extern "C" int bls_check(bls_ctx *ctx, void *hip_stream)
 {
     if (!ctx) return BLS_EINVAL;

@@ -113,3 +113,41 @@ class Pipeline:
 
     def slot_view(self, slot: int) -> torch.Tensor:
         return self.slots[slot * self.n_floats:(slot + 1) * self.n_floats]
+
+
+class DenseModel:
+    """Bottom MLP, dot interaction and top MLP around a Pipeline's lookups (Listings 1 and 2:
+    apply_mlp, interact_features): layer weights and activation buffers on the GPU, every
+    step a call into the library.  ``bottom`` / ``top`` are lists of (W [N, K], bias [N])
+    float32 tensors; ReLU between layers, a sigmoid after the last top layer."""
+
+    def __init__(self, ctx: "bls.Context", bottom, top, batch: int):
+        self.ctx, self.B = ctx, int(batch)
+        dev = bottom[0][0].device
+        assert dev.type == "cuda", "the dense layers run on the GPU only"
+        self.bottom = [(W.contiguous(), b.contiguous()) for W, b in bottom]
+        self.top = [(W.contiguous(), b.contiguous()) for W, b in top]
+        zdim = ctx.D + ctx.T * (ctx.T + 1) // 2
+        assert self.bottom[-1][0].shape[0] == ctx.D and self.top[0][0].shape[1] == zdim
+        f32 = dict(dtype=torch.float32, device=dev)
+        self.bot_act = [torch.empty((self.B, W.shape[0]), **f32) for W, _ in self.bottom]
+        self.z = torch.empty((self.B, zdim), **f32)
+        self.top_act = [torch.empty((self.B, W.shape[0]), **f32) for W, _ in self.top]
+
+    def apply_bottom(self, dense: torch.Tensor, stream=None) -> torch.Tensor:
+        """x = bottom MLP of the dense features ``[B, n_dense]``; returns the [B, D] buffer."""
+        a = dense
+        for (W, b), y in zip(self.bottom, self.bot_act):
+            self.ctx.bls_mlp_layer(a, W, b, bls.BLS_ACT_RELU, y, stream)
+            a = y
+        return a
+
+    def compute_ctr(self, x: torch.Tensor, emb: torch.Tensor, stream=None) -> torch.Tensor:
+        """The prediction from the bottom MLP's output and the completed lookup [B, T, D]."""
+        self.ctx.bls_interact(x, emb, self.z, 0, self.B, stream)
+        a = self.z
+        for i, ((W, b), y) in enumerate(zip(self.top, self.top_act)):
+            last = i == len(self.top) - 1
+            self.ctx.bls_mlp_layer(a, W, b, bls.BLS_ACT_SIGMOID if last else bls.BLS_ACT_RELU, y, stream)
+            a = y
+        return a

@@ -1,0 +1,162 @@
+"""Parity of the dense kernels (bls_mlp_layer, bls_interact) against the CPU oracle, through the
+C ABI.  The oracle evaluates in double; the fp32 matrix-core result must lie within the bound
+the oracle derives from the arithmetic for the same fp32 inputs: (K + 3) roundings of 2^-24 on
+|bias| + sum |x||w| for a layer (a few more for the sigmoid), (D + 2) on sum |u||v| for a dot
+product of the interaction.  Each kernel is checked on the inputs it really received; the whole
+chain is also compared with the oracle's chain under the bound carried from layer to layer."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import synth
+
+pytestmark = pytest.mark.gpu
+
+DEV = "cuda:0"
+
+
+def ctx_for(T=2, D=4, B=4):
+    import paper_2512_19342_amd as A
+    return A.Context(1, T, D, 0, B, [4] * T, [0] * T)
+
+
+LAYERS = [
+    # M, K, N, act, bias
+    (1, 1, 1, 0, True), (5, 13, 7, 1, True), (130, 13, 512, 1, True), (257, 512, 256, 1, True),
+    (128, 256, 128, 0, False), (300, 276, 100, 1, True), (64, 100, 1, 2, True), (200, 17, 33, 2, True),
+    (384, 64, 1024, 1, True), (129, 130, 129, 1, False), (1000, 16, 16, 0, True), (3, 2208, 40, 1, True),
+]
+
+
+@pytest.mark.parametrize("M,K,N,act,has_bias", LAYERS)
+def test_mlp_layer_matches_oracle(M, K, N, act, has_bias):
+    c = ctx_for()
+    rng = np.random.default_rng(M * 7 + K * 3 + N)
+    x = rng.normal(0, 1, size=(M, K)).astype(np.float32)
+    W = (rng.normal(0, 1, size=(N, K)) / np.sqrt(K)).astype(np.float32)
+    b = rng.normal(0, 1, size=N).astype(np.float32) if has_bias else None
+    y = torch.full((M, N), float("nan"), device=DEV)
+    c.bls_mlp_layer(torch.from_numpy(x).to(DEV), torch.from_numpy(W).to(DEV),
+                    None if b is None else torch.from_numpy(b).to(DEV), act, y)
+    c.bls_check()
+    ref, err = oracle.mlp_layer(x, W, b, act)
+    got = y.cpu().numpy().astype(np.float64)
+    assert np.all(np.isfinite(got)) and np.all(np.abs(got - ref) <= err)
+    # the worst case grows with K; rounding errors behave like a random walk, so in practice the
+    # result is within a few sqrt(K) roundings (the sigmoid's own few units included)
+    assert np.all(np.abs(got - ref) <= 4.0 * err / np.sqrt(K + 3) + (8 * 2.0 ** -24 if act == 2 else 0.0))
+    assert err.max() <= 2e-3 * max(1.0, np.abs(ref).max())
+
+
+def test_mlp_layer_unaligned_rows_and_empty():
+    """A view that starts 4 bytes into an allocation takes the scalar-load path; M = 0 is a no-op."""
+    c = ctx_for()
+    rng = np.random.default_rng(9)
+    M, K, N = 70, 24, 50
+    x = rng.normal(size=(M, K)).astype(np.float32)
+    W = rng.normal(size=(N, K)).astype(np.float32)
+    xb = torch.zeros(M * K + 1, device=DEV)
+    xb[1:] = torch.from_numpy(x).reshape(-1).to(DEV)
+    xv = xb[1:].view(M, K)
+    assert xv.data_ptr() % 16 == 4
+    y = torch.empty((M, N), device=DEV)
+    c.bls_mlp_layer(xv, torch.from_numpy(W).to(DEV), None, 1, y)
+    ref, err = oracle.mlp_layer(x, W, None, 1)
+    assert np.all(np.abs(y.cpu().numpy() - ref) <= err)
+    c.bls_mlp_layer(torch.empty((0, K), device=DEV), torch.from_numpy(W).to(DEV), None, 1, torch.empty((0, N), device=DEV))
+    c.bls_check()
+
+
+INTERACT = [(1, 4, 3), (3, 5, 6), (8, 16, 9), (26, 64, 20), (64, 128, 12), (33, 20, 7), (70, 32, 5), (32, 7, 4), (2, 1, 3)]
+
+
+@pytest.mark.parametrize("T,D,B", INTERACT)
+def test_interact_matches_oracle(T, D, B):
+    c = ctx_for(T, D, B)
+    rng = np.random.default_rng(T * 5 + D)
+    x = rng.normal(size=(B, D)).astype(np.float32)
+    emb = rng.normal(size=(B, T, D)).astype(np.float32)
+    Wz = D + T * (T + 1) // 2
+    z = torch.full((B, Wz), float("nan"), device=DEV)
+    c.bls_interact(torch.from_numpy(x).to(DEV), torch.from_numpy(emb).to(DEV), z)
+    c.bls_check()
+    ref, err = oracle.interact(x, emb)
+    got = z.cpu().numpy()
+    assert np.array_equal(got[:, :D], x)                      # the dense vector is copied
+    assert np.all(np.abs(got - ref) <= err)
+    # a range of samples leaves the others alone
+    if B >= 3:
+        z2 = torch.full((B, Wz), -7.0, device=DEV)
+        c.bls_interact(torch.from_numpy(x).to(DEV), torch.from_numpy(emb).to(DEV), z2, 1, B - 2)
+        g2 = z2.cpu().numpy()
+        assert np.all(g2[0] == -7.0) and np.all(g2[-1] == -7.0) and np.array_equal(g2[1:-1], got[1:-1])
+
+
+def test_dense_bad_arguments():
+    import paper_2512_19342_amd as A
+    c = ctx_for(2, 4, 4)
+    t = torch.zeros((4, 4), device=DEV)
+    with pytest.raises(A.BlsError) as e:
+        c.bls_mlp_layer(t, t, None, 7, torch.zeros((4, 4), device=DEV))
+    assert e.value.code == A.BLS_EINVAL
+    with pytest.raises(A.BlsError):
+        c.bls_interact(t, torch.zeros((4, 2, 4), device=DEV), torch.zeros((4, 7), device=DEV), 2, 3)   # 2 + 3 > B
+    big = ctx_for(64, 512, 4)                                  # 64 vectors of 512 floats: 128 KB
+    with pytest.raises(A.BlsError) as e:
+        big.bls_interact(torch.zeros((4, 512), device=DEV), torch.zeros((4, 64, 512), device=DEV),
+                         torch.zeros((4, 512 + 2080), device=DEV))
+    assert e.value.code == A.BLS_EINVAL
+
+
+@pytest.mark.parametrize("cfg", [2, 4])
+def test_model_around_the_lookup(cfg):
+    """Bottom MLP, the lookup through the path, interaction, top MLP -> prediction, on a workload's
+    reduced twin: every kernel against the oracle on the inputs it received, and the prediction
+    against the oracle's own chain."""
+    from paper_2512_19342_amd.runner import DenseModel, Pipeline
+    w = synth.workload(cfg, "small") if cfg != 2 else synth.workload(2)
+    tabs = [synth.make_table(w, t) for t in range(w.T)]
+    ix, off = synth.make_batch(w, 1)
+    nnz = int(off[-1])
+    pipe = Pipeline(w, [t.to(DEV) for t in tabs], nnz)
+    bot_sizes, top_sizes = synth.mlp_sizes(w, "small")
+    bot, top = synth.mlp_weights(w, bot_sizes, 0), synth.mlp_weights(w, top_sizes, 1)
+    model = DenseModel(pipe.ctx, [(W.to(DEV), b.to(DEV)) for W, b in bot], [(W.to(DEV), b.to(DEV)) for W, b in top], w.B)
+    dense = synth.dense_features(w, 1)
+
+    out = pipe.new_out()
+    it, _ = pipe.issue_fused(ix.to(DEV), off.to(DEV), nnz)
+    x = model.apply_bottom(dense.to(DEV))
+    pipe.complete(it, out)
+    p = model.compute_ctr(x, out)
+    pipe.ctx.bls_check()
+
+    case = oracle.Case(w.P, w.T, w.D, w.B, w.part_kind, w.rows, w.table_owner, w.dtype_code)
+    emb = oracle.pipeline(case, [t.numpy() for t in tabs], ix.numpy(), off.numpy())["Out"]
+    assert np.array_equal(out.cpu().numpy(), emb)
+    # kernel by kernel, each on what it was given
+    a = dense.numpy()
+    for (W, b), y in zip(bot, model.bot_act):
+        ref, err = oracle.mlp_layer(a, W.numpy(), b.numpy(), 1)
+        a = y.cpu().numpy()
+        assert np.all(np.abs(a - ref) <= err)
+    ref, err = oracle.interact(a, emb)
+    a = model.z.cpu().numpy()
+    assert np.all(np.abs(a - ref) <= err)
+    for i, ((W, b), y) in enumerate(zip(top, model.top_act)):
+        ref, err = oracle.mlp_layer(a, W.numpy(), b.numpy(), 2 if i == len(top) - 1 else 1)
+        a = y.cpu().numpy()
+        assert np.all(np.abs(a - ref) <= err)
+    # the whole chain in double, with the bound carried along
+    Lb = [(W.numpy(), b.numpy(), 1) for W, b in bot]
+    Lt = [(W.numpy(), b.numpy(), 1) for W, b in top]
+    Lt[-1] = (Lt[-1][0], Lt[-1][1], 2)
+    x64, ex = oracle.mlp(dense.numpy(), Lb)
+    z64, ez = oracle.interact(x64, emb, ex)
+    p64, ep = oracle.mlp(z64, Lt, ez)
+    got = p.cpu().numpy()
+    assert got.shape == (w.B, 1) and np.all(np.abs(got - p64) <= ep)
+    # the carried worst case is loose after six layers (about 1e-2); the prediction, a probability,
+    # is in fact within a few fp32 units of the double-precision chain
+    assert np.abs(got - p64).max() < 1e-6
