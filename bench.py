@@ -80,6 +80,77 @@ def cpu_baseline(w, tabs_gpu, batches, budget_s: float) -> dict:
                       f"unpack, all {w.T} tables at full size on the host"}
 
 
+def dense_section(args, w, pipe, batches, nnzs, note) -> dict:
+    """The model around the lookup (bottom MLP, dot interaction, top MLP) at the workload's batch:
+    every kernel timed with events, then Listing 2's loop (lookup + model per iteration)."""
+    import torch
+
+    import synth
+    from paper_2512_19342_amd.runner import BlsDlrm, DenseModel
+    dev = pipe.dev
+    bs, ts = synth.mlp_sizes(w, "full")
+    bot = [(W.to(dev), b.to(dev)) for W, b in synth.mlp_weights(w, bs, 0)]
+    top = [(W.to(dev), b.to(dev)) for W, b in synth.mlp_weights(w, ts, 1)]
+    model = DenseModel(pipe.ctx, bot, top, w.B)
+    dense = [synth.dense_features(w, i, dev) for i in range(2)]
+    emb = pipe.new_out().normal_(0.0, 0.1)
+    c = pipe.ctx
+    names = [f"bottom {K}->{N}" for K, N in zip(bs[:-1], bs[1:])] + ["interact"] + [f"top {K}->{N}" for K, N in zip(ts[:-1], ts[1:])]
+    flops = [2.0 * w.B * K * N for K, N in zip(bs[:-1], bs[1:])] + [2.0 * w.B * w.D * w.T * (w.T + 1) / 2] + \
+            [2.0 * w.B * K * N for K, N in zip(ts[:-1], ts[1:])]
+
+    def model_step(i: int, ev=None):
+        a, k = dense[i % 2], 0
+        for (W, b), y in zip(model.bottom, model.bot_act):
+            if ev: ev[k].record()
+            c.bls_mlp_layer(a, W, b, 1, y)
+            a, k = y, k + 1
+        if ev: ev[k].record()
+        c.bls_interact(a, emb, model.z)
+        a, k = model.z, k + 1
+        for j, ((W, b), y) in enumerate(zip(model.top, model.top_act)):
+            if ev: ev[k].record()
+            c.bls_mlp_layer(a, W, b, 2 if j == len(model.top) - 1 else 1, y)
+            a, k = y, k + 1
+        if ev: ev[k].record()
+
+    for i in range(args.warmup):
+        model_step(i)
+    n = len(names)
+    events = [[torch.cuda.Event(enable_timing=True) for _ in range(n + 1)] for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    for i in range(args.steps):
+        model_step(i, events[i])
+    torch.cuda.synchronize()
+    ms = [sum(e[k].elapsed_time(e[k + 1]) for e in events) / args.steps for k in range(n)]
+    kernels = {nm: {"ms": m, "tflops": f / (m * 1e-3) / 1e12} for nm, m, f in zip(names, ms, flops)}
+    big = max(range(n), key=lambda k: flops[k] if names[k] != "interact" else 0.0)
+    note(f"dense model: {sum(ms):.3f} ms per batch; {names[big]}: {ms[big]:.3f} ms, {kernels[names[big]]['tflops']:.1f} TFLOP/s")
+
+    # Listing 2's loop: lookup (fused owner side) + bottom MLP per call, completion + prediction k calls later
+    loop = BlsDlrm(pipe, model)
+    torch.cuda.synchronize()
+    for i in range(args.warmup):
+        loop.forward(dense[i % 2], *batches[i % len(batches)], nnzs[i % len(batches)])
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    done = 0
+    for i in range(args.steps):
+        done += len(loop.forward(dense[i % 2], *batches[i % len(batches)], nnzs[i % len(batches)], last_batch=i == args.steps - 1))
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    c.bls_check()
+    note(f"{args.steps} iterations of the model loop: {dt / args.steps * 1e3:.3f} ms per iteration")
+    mm = [k for k in range(n) if names[k] != "interact"]
+    return {"layers": {"bottom": bs, "top": ts}, "kernels": kernels, "dense_ms_per_batch": sum(ms),
+            "mlp_tflops": sum(flops[k] for k in mm) / (sum(ms[k] for k in mm) * 1e-3) / 1e12,
+            "mfma_roofline": {"bound": "mfma", "kernel": f"mlp_gemm ({names[big]})", "achieved": kernels[names[big]]["tflops"],
+                              "peak": 157.3, "unit": "TFLOP/s", "frac": kernels[names[big]]["tflops"] / 157.3},
+            "loop": {"entry_points": "bls_plan + bls_embbag_pool_put + bls_mlp_layer x3 | bls_unpack + bls_interact + bls_mlp_layer x5",
+                     "bound": w.k, "ms_per_iteration": dt / args.steps * 1e3, "samples_per_s": w.B * args.steps / dt,
+                     "completed": done}}
+
+
 def lag_demo(args) -> int:
     """The paper's Setting 2 on one GPU: every simulated rank on its own stream, a uniformly random
     delay before each rank's work in every iteration, bound k swept.  With k = 0 every iteration
@@ -173,6 +244,7 @@ def main() -> int:
     ap.add_argument("--bounds", type=int, nargs="+", default=[0, 1, 2, 4, 8])
     ap.add_argument("--table-dtype", default=None, choices=[None, "fp32", "fp16", "u8rq"],
                     help="variant: store the tables this way instead of the workload's own dtype")
+    ap.add_argument("--dense", action="store_true", help="with --timed-only: also time the dense model around the lookup")
     ap.add_argument("--rows-cap", type=int, default=0, help="experiment: no table has more rows than this")
     ap.add_argument("--bag-fixed", type=int, default=0, help="experiment: every bag has this many lookups")
     args = ap.parse_args()
@@ -319,6 +391,10 @@ def main() -> int:
         c.bls_check()
         note(f"{args.steps} steps with up to {c.K} iterations in flight: {dtr / args.steps * 1e3:.3f} ms per step")
 
+    dlrm = None
+    if not args.timed_only or args.dense:
+        dlrm = dense_section(args, w, pipe, batches, nnzs, note)
+
     stage_ms = {n: sum(e[k].elapsed_time(e[k + 1]) for e in events) / args.steps for k, n in enumerate(names)}
     mean_nnz = lookups / args.steps
     sb = stage_bytes(w, int(mean_nnz))
@@ -354,6 +430,7 @@ def main() -> int:
         "ring_in_flight": None if dtr is None else {
             "K": c.K, "ms_per_step": dtr / args.steps * 1e3,
             "note": "staged path, completion deferred K-1 iterations on a second stream"},
+        "dlrm_model": dlrm,
         "bucket_pool_pack": {"ms": stage_ms["plan"] + stage_ms["pool"] + stage_ms["pack"],
                              "lookups_per_s": mean_nnz / ((stage_ms["plan"] + stage_ms["pool"] + stage_ms["pack"]) * 1e-3)},
         "plain_copy_gbps": copy_gbps,

@@ -15,11 +15,12 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 
 constexpr int kThreads = 256;
 
-__device__ __forceinline__ float activate(float v, int act)
+template <int ACT>
+__device__ __forceinline__ float activate(float v)
 {
-    if (act == BLS_ACT_RELU) return v > 0.f ? v : 0.f;
-    if (act == BLS_ACT_SIGMOID) return 1.f / (1.f + expf(-v));
-    return v;
+    if constexpr (ACT == BLS_ACT_RELU) return v > 0.f ? v : 0.f;
+    else if constexpr (ACT == BLS_ACT_SIGMOID) return 1.f / (1.f + expf(-v));
+    else return v;
 }
 
 // ---- one layer: Y[M][N] = act(X[M][K] * W[N][K]^T + bias[N]) ---------------------------------
@@ -32,10 +33,10 @@ __device__ __forceinline__ float activate(float v, int act)
 // (one L2), N-tile fastest.
 constexpr int BM = 128, BN = 128, BK = 16, LDT = BM + 4;
 
-template <bool VEC>
+template <bool VEC, int ACT>
 __global__ __launch_bounds__(kThreads) void mlp_gemm(const float *__restrict__ X, const float *__restrict__ W,
                                                      const float *__restrict__ bias, float *__restrict__ Y,
-                                                     int64_t M, int N, int K, int act, uint32_t n_tiles, uint32_t tiles)
+                                                     int64_t M, int N, int K, uint32_t n_tiles, uint32_t tiles)
 {
     __shared__ float As[2][BK][LDT];
     __shared__ float Bs[2][BK][LDT];
@@ -101,13 +102,7 @@ __global__ __launch_bounds__(kThreads) void mlp_gemm(const float *__restrict__ X
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
-    fetch(0);
-    stage(0);
-    __syncthreads();
-    int buf = 0;
-    for (int k0 = 0; k0 < K; k0 += BK) {
-        const bool more = k0 + BK < K;
-        if (more) fetch(k0 + BK);                             // in flight during the multiplies below
+    auto multiply = [&](int buf) {
 #pragma unroll
         for (int kk = 0; kk < BK; kk += 2) {
             const float a0 = As[buf][kk + half][wm + l32], a1 = As[buf][kk + half][wm + 32 + l32];
@@ -117,12 +112,21 @@ __global__ __launch_bounds__(kThreads) void mlp_gemm(const float *__restrict__ X
             acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b0, acc[1][0], 0, 0, 0);
             acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b1, acc[1][1], 0, 0, 0);
         }
-        if (more) {
-            stage(buf ^ 1);                                   // the other buffer: nobody reads it now
-            __syncthreads();
-            buf ^= 1;
-        }
+    };
+
+    fetch(0);
+    stage(0);
+    __syncthreads();
+    const int steps = (K + BK - 1) / BK;
+    int buf = 0;
+    for (int t = 1; t < steps; ++t) {
+        fetch(t * BK);                                        // in flight during the multiplies below
+        multiply(buf);
+        stage(buf ^ 1);                                       // the other buffer: nobody reads it now
+        __syncthreads();
+        buf ^= 1;
     }
+    multiply(buf);
 
 #pragma unroll
     for (int i = 0; i < 2; ++i)
@@ -134,7 +138,7 @@ __global__ __launch_bounds__(kThreads) void mlp_gemm(const float *__restrict__ X
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
                 const int64_t row = m0 + wm + i * 32 + 8 * (v >> 2) + 4 * half + (v & 3);
-                if (row < M) Y[row * N + col] = activate(acc[i][j][v] + bv, act);
+                if (row < M) Y[row * N + col] = activate<ACT>(acc[i][j][v] + bv);
             }
         }
 }
@@ -149,7 +153,7 @@ __global__ __launch_bounds__(kThreads) void mlp_gemm(const float *__restrict__ X
 // vector i-1 with x and with pooled vectors 0..i-2.
 __global__ __launch_bounds__(kThreads) void interact_gram(const float *__restrict__ x, const float *__restrict__ emb,
                                                           float *__restrict__ z, int T, int D, int TP, int LD,
-                                                          uint32_t b0)
+                                                          uint32_t b0, int vec4)
 {
     extern __shared__ float lds[];
     float *Es = lds;                                          // [TP][LD]
@@ -160,9 +164,47 @@ __global__ __launch_bounds__(kThreads) void interact_gram(const float *__restric
     const float *__restrict__ e = emb + b * T * D;
     float *__restrict__ zb = z + b * Wz;
 
-    for (int i = tid; i < TP * LD; i += kThreads) {
-        const int r = i / LD, c = i - r * LD;
-        Es[i] = (r < T && c < D) ? e[(int64_t)r * D + c] : 0.f;
+    // zeros: the padding columns behind every vector and the padding rows behind the last one
+    const int padc = LD - D;
+    for (int i = tid; i < T * padc; i += kThreads) Es[(i / padc) * LD + D + i % padc] = 0.f;
+    for (int i = T * LD + tid; i < TP * LD; i += kThreads) Es[i] = 0.f;
+    // the vectors themselves: eight independent loads per lane in flight, then the LDS writes
+    constexpr int kFill = 8;
+    if (vec4) {
+        const float4 *__restrict__ e4 = reinterpret_cast<const float4 *>(e);
+        const uint32_t n4 = (uint32_t)T * (uint32_t)D / 4u, c4n = (uint32_t)D / 4u;
+        for (uint32_t base = 0; base < n4; base += kThreads * kFill) {
+            float4 v[kFill];
+#pragma unroll
+            for (int u = 0; u < kFill; ++u) {
+                const uint32_t i = base + u * kThreads + tid;
+                v[u] = i < n4 ? e4[i] : make_float4(0.f, 0.f, 0.f, 0.f);
+            }
+#pragma unroll
+            for (int u = 0; u < kFill; ++u) {
+                const uint32_t i = base + u * kThreads + tid;
+                if (i < n4) {
+                    const uint32_t r = i / c4n, c = (i - r * c4n) * 4u;
+                    float *d = Es + r * LD + c;
+                    d[0] = v[u].x; d[1] = v[u].y; d[2] = v[u].z; d[3] = v[u].w;
+                }
+            }
+        }
+    } else {
+        const uint32_t n1 = (uint32_t)T * (uint32_t)D;
+        for (uint32_t base = 0; base < n1; base += kThreads * kFill) {
+            float v[kFill];
+#pragma unroll
+            for (int u = 0; u < kFill; ++u) {
+                const uint32_t i = base + u * kThreads + tid;
+                v[u] = i < n1 ? e[i] : 0.f;
+            }
+#pragma unroll
+            for (int u = 0; u < kFill; ++u) {
+                const uint32_t i = base + u * kThreads + tid;
+                if (i < n1) { const uint32_t r = i / (uint32_t)D; Es[r * LD + (i - r * (uint32_t)D)] = v[u]; }
+            }
+        }
     }
     for (int c = tid; c < D; c += kThreads) {
         const float v = x[b * D + c];
@@ -211,8 +253,17 @@ int bls_launch_mlp_layer(bls_ctx *ctx, const float *x, int64_t M, int K, const f
     const uint32_t tiles = (uint32_t)(m_tiles * n_tiles);
     const dim3 grid((tiles + 7u) / 8u * 8u);
     const bool vec = K % 4 == 0 && (((uintptr_t)x | (uintptr_t)W) & 15u) == 0;
-    if (vec) mlp_gemm<true><<<grid, kThreads, 0, st>>>(x, W, bias, y, M, N, K, act, (uint32_t)n_tiles, tiles);
-    else mlp_gemm<false><<<grid, kThreads, 0, st>>>(x, W, bias, y, M, N, K, act, (uint32_t)n_tiles, tiles);
+#define BLS_GEMM(V, A) mlp_gemm<V, A><<<grid, kThreads, 0, st>>>(x, W, bias, y, M, N, K, (uint32_t)n_tiles, tiles)
+    if (vec) {
+        if (act == BLS_ACT_RELU) BLS_GEMM(true, BLS_ACT_RELU);
+        else if (act == BLS_ACT_SIGMOID) BLS_GEMM(true, BLS_ACT_SIGMOID);
+        else BLS_GEMM(true, BLS_ACT_NONE);
+    } else {
+        if (act == BLS_ACT_RELU) BLS_GEMM(false, BLS_ACT_RELU);
+        else if (act == BLS_ACT_SIGMOID) BLS_GEMM(false, BLS_ACT_SIGMOID);
+        else BLS_GEMM(false, BLS_ACT_NONE);
+    }
+#undef BLS_GEMM
     BLS_HIP(ctx, hipGetLastError());
     return BLS_OK;
 }
@@ -228,7 +279,8 @@ int bls_launch_interact(bls_ctx *ctx, const float *x, const float *emb, float *z
     if (bn == 0) return BLS_OK;
     const int T = ctx->T, D = ctx->D;
     const int TP = (T + 31) / 32 * 32, LD = ((D + 1) & ~1) + 1;
-    interact_gram<<<dim3(bn), kThreads, bls_interact_lds_bytes(T, D), st>>>(x, emb, z, T, D, TP, LD, b0);
+    const int vec4 = D % 4 == 0 && ((uintptr_t)emb & 15u) == 0;   // every sample's T*D floats then start 16-byte aligned
+    interact_gram<<<dim3(bn), kThreads, bls_interact_lds_bytes(T, D), st>>>(x, emb, z, T, D, TP, LD, b0, vec4);
     BLS_HIP(ctx, hipGetLastError());
     return BLS_OK;
 }

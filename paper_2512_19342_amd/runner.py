@@ -134,20 +134,67 @@ class DenseModel:
         self.z = torch.empty((self.B, zdim), **f32)
         self.top_act = [torch.empty((self.B, W.shape[0]), **f32) for W, _ in self.top]
 
-    def apply_bottom(self, dense: torch.Tensor, stream=None) -> torch.Tensor:
-        """x = bottom MLP of the dense features ``[B, n_dense]``; returns the [B, D] buffer."""
+    def apply_bottom(self, dense: torch.Tensor, x_out: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+        """x = bottom MLP of the dense features ``[B, n_dense]``, written to ``x_out`` [B, D]
+        (default: the model's own buffer, overwritten by the next call)."""
         a = dense
-        for (W, b), y in zip(self.bottom, self.bot_act):
+        for i, ((W, b), y) in enumerate(zip(self.bottom, self.bot_act)):
+            if x_out is not None and i == len(self.bottom) - 1:
+                y = x_out
             self.ctx.bls_mlp_layer(a, W, b, bls.BLS_ACT_RELU, y, stream)
             a = y
         return a
 
-    def compute_ctr(self, x: torch.Tensor, emb: torch.Tensor, stream=None) -> torch.Tensor:
-        """The prediction from the bottom MLP's output and the completed lookup [B, T, D]."""
+    def compute_ctr(self, x: torch.Tensor, emb: torch.Tensor, p_out: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+        """The prediction [B, 1] from the bottom MLP's output and the completed lookup [B, T, D]."""
         self.ctx.bls_interact(x, emb, self.z, 0, self.B, stream)
         a = self.z
         for i, ((W, b), y) in enumerate(zip(self.top, self.top_act)):
             last = i == len(self.top) - 1
+            if last and p_out is not None:
+                y = p_out
             self.ctx.bls_mlp_layer(a, W, b, bls.BLS_ACT_SIGMOID if last else bls.BLS_ACT_RELU, y, stream)
             a = y
         return a
+
+
+class BlsDlrm:
+    """The forward loop of Listing 2 on one stream: every call issues one iteration's lookup
+    (plan, pool straight into the ring slot) and its bottom MLP, and completes the oldest
+    iteration (unpack, interaction, top MLP) once more than ``bound`` are unfinished; the last
+    batch drains the ring.  Results do not depend on the bound; only how far completion lags.
+
+    The ring has K = max(bound, 1) slots, so with bound >= 1 the oldest iteration is completed
+    before the one that would reuse its slot is issued (Fig. "bound": the process blocks on
+    iteration 0 before it may start iteration k)."""
+
+    def __init__(self, pipe: Pipeline, model: DenseModel):
+        self.pipe, self.model = pipe, model
+        self.bound = pipe.w.k
+        n = pipe.ctx.K + 1
+        f32 = dict(dtype=torch.float32, device=pipe.dev)
+        self.x_list = [torch.empty((pipe.w.B, pipe.w.D), **f32) for _ in range(n)]   # the listing's x-list
+        self.emb = pipe.new_out()
+        self.unfinished: List[int] = []
+
+    def _finish_tail(self, stream=None):
+        it = self.unfinished.pop(0)
+        self.pipe.complete(it, self.emb, stream)
+        p = torch.empty((self.pipe.w.B, 1), dtype=torch.float32, device=self.pipe.dev)
+        self.model.compute_ctr(self.x_list[it % len(self.x_list)], self.emb, p, stream)
+        return it, p
+
+    def forward(self, dense, indices, offsets, nnz: int, last_batch: bool = False, stream=None):
+        """Returns the (iteration, prediction) pairs completed by this call, oldest first."""
+        done = []
+        if self.bound > 0 and len(self.unfinished) == self.pipe.ctx.K:
+            done.append(self._finish_tail(stream))
+        it, _ = self.pipe.issue_fused(indices, offsets, nnz, stream)
+        self.unfinished.append(it)
+        self.model.apply_bottom(dense, self.x_list[it % len(self.x_list)], stream)
+        if len(self.unfinished) > self.bound:
+            done.append(self._finish_tail(stream))
+        if last_batch:
+            while self.unfinished:
+                done.append(self._finish_tail(stream))
+        return done

@@ -160,3 +160,50 @@ def test_model_around_the_lookup(cfg):
     # the carried worst case is loose after six layers (about 1e-2); the prediction, a probability,
     # is in fact within a few fp32 units of the double-precision chain
     assert np.abs(got - p64).max() < 1e-6
+
+
+@pytest.mark.parametrize("part_kind", [0, 1])
+def test_bls_dlrm_loop_does_not_depend_on_the_bound(part_kind):
+    """Listing 2's loop for bounds 0, 1 and 3: every iteration's prediction is the same bits
+    whatever the bound, arrives in order, lags by at most the bound, and matches the oracle."""
+    from paper_2512_19342_amd.runner import BlsDlrm, DenseModel, Pipeline
+    n_iter = 6
+    ref_bits, base = None, None
+    for k in (0, 1, 3):
+        w = synth.custom("loop", P=4, T=6, D=32, B=96, k=k, part_kind=part_kind, rows=[500, 64, 3000, 17, 256, 999],
+                         bag=("uniform", 0, 12), index_dist=("zipf", 1.1), values="gauss", seed=51)
+        tabs = [synth.make_table(w, t) for t in range(w.T)]
+        batches = [synth.make_batch(w, it) for it in range(n_iter)]
+        dense = [synth.dense_features(w, it) for it in range(n_iter)]
+        pipe = Pipeline(w, [t.to(DEV) for t in tabs], max(int(o[-1]) for _, o in batches))
+        bs, ts = synth.mlp_sizes(w, "small")
+        bot, top = synth.mlp_weights(w, bs, 0), synth.mlp_weights(w, ts, 1)
+        model = DenseModel(pipe.ctx, [(W.to(DEV), b.to(DEV)) for W, b in bot], [(W.to(DEV), b.to(DEV)) for W, b in top], w.B)
+        loop = BlsDlrm(pipe, model)
+        got = {}
+        for it in range(n_iter):
+            ix, off = batches[it]
+            for j, p in loop.forward(dense[it].to(DEV), ix.to(DEV), off.to(DEV), int(off[-1]), last_batch=it == n_iter - 1):
+                assert j == len(got) and it - j <= max(k, 0)  # FIFO, lag within the bound
+                got[j] = p.cpu().numpy()
+            if it < n_iter - 1:
+                assert len(loop.unfinished) == min(k, it + 1)
+        pipe.ctx.bls_check()
+        assert sorted(got) == list(range(n_iter))
+        bits = [got[j].view(np.uint32) for j in range(n_iter)]
+        if ref_bits is None:
+            ref_bits, base = bits, (w, tabs, batches, dense, bot, top)
+        else:
+            assert all(np.array_equal(a, b) for a, b in zip(bits, ref_bits)), k
+    w, tabs, batches, dense, bot, top = base
+    case = oracle.Case(w.P, w.T, w.D, w.B, w.part_kind, w.rows, w.table_owner, w.dtype_code)
+    Lb = [(W.numpy(), b.numpy(), 1) for W, b in bot]
+    Lt = [(W.numpy(), b.numpy(), 1) for W, b in top]
+    Lt[-1] = (Lt[-1][0], Lt[-1][1], 2)
+    for it in (0, n_iter - 1):
+        emb = oracle.pipeline(case, [t.numpy() for t in tabs], batches[it][0].numpy(), batches[it][1].numpy())["Out"]
+        x64, ex = oracle.mlp(dense[it].numpy(), Lb)
+        z64, ez = oracle.interact(x64, emb, ex)
+        p64, ep = oracle.mlp(z64, Lt, ez)
+        p = ref_bits[it].view(np.float32)
+        assert np.all(np.abs(p - p64) <= ep) and np.abs(p - p64).max() < 1e-6
