@@ -127,6 +127,21 @@ def dense_section(args, w, pipe, batches, nnzs, note) -> dict:
     big = max(range(n), key=lambda k: flops[k] if names[k] != "interact" else 0.0)
     note(f"dense model: {sum(ms):.3f} ms per batch; {names[big]}: {ms[big]:.3f} ms, {kernels[names[big]]['tflops']:.1f} TFLOP/s")
 
+    # the vendor library's fp32 GEMM on the largest layer's shape (no bias, no activation), for scale
+    Wb, xb = model.top[big - len(bs)][0] if big >= len(bs) else model.bottom[big][0], None
+    xb = model.z if big == len(bs) else (model.top_act[big - len(bs) - 1] if big > len(bs) else dense[0])
+    lib_ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+    yb = torch.empty((xb.shape[0], Wb.shape[0]), dtype=torch.float32, device=dev)
+    for _ in range(2):
+        torch.mm(xb, Wb.t(), out=yb)
+    lib_ev[0].record()
+    for _ in range(5):
+        torch.mm(xb, Wb.t(), out=yb)
+    lib_ev[1].record()
+    torch.cuda.synchronize()
+    lib_tflops = flops[big] / (lib_ev[0].elapsed_time(lib_ev[1]) / 5 * 1e-3) / 1e12
+    note(f"torch.mm (rocBLAS / hipBLASLt) on the same shape: {lib_tflops:.1f} TFLOP/s")
+
     # Listing 2's loop: lookup (fused owner side) + bottom MLP per call, completion + prediction k calls later
     loop = BlsDlrm(pipe, model)
     torch.cuda.synchronize()
@@ -143,6 +158,7 @@ def dense_section(args, w, pipe, batches, nnzs, note) -> dict:
     note(f"{args.steps} iterations of the model loop: {dt / args.steps * 1e3:.3f} ms per iteration")
     mm = [k for k in range(n) if names[k] != "interact"]
     return {"layers": {"bottom": bs, "top": ts}, "kernels": kernels, "dense_ms_per_batch": sum(ms),
+            "library_gemm_tflops_same_shape": lib_tflops,
             "mlp_tflops": sum(flops[k] for k in mm) / (sum(ms[k] for k in mm) * 1e-3) / 1e12,
             "mfma_roofline": {"bound": "mfma", "kernel": f"mlp_gemm ({names[big]})", "achieved": kernels[names[big]]["tflops"],
                               "peak": 157.3, "unit": "TFLOP/s", "frac": kernels[names[big]]["tflops"] / 157.3},

@@ -31,7 +31,10 @@ __device__ __forceinline__ float activate(float v)
 // double-buffered: the loads of the next tile are in flight while the current one is multiplied.
 // Workgroups are numbered so that the eight that share rows of X follow each other on one XCD
 // (one L2), N-tile fastest.
-constexpr int BM = 128, BN = 128, BK = 16, LDT = BM + 4;
+#ifndef BLS_GEMM_BK
+#define BLS_GEMM_BK 16
+#endif
+constexpr int BM = 128, BN = 128, BK = BLS_GEMM_BK, LDT = BM + 4;
 
 template <bool VEC, int ACT>
 __global__ __launch_bounds__(kThreads) void mlp_gemm(const float *__restrict__ X, const float *__restrict__ W,
@@ -53,23 +56,23 @@ __global__ __launch_bounds__(kThreads) void mlp_gemm(const float *__restrict__ X
     const int half = lane >> 5, l32 = lane & 31;
 
     // staging registers for one tile of X and one of W
-    constexpr int NLD = VEC ? 2 : 8;
-    float4 xa[VEC ? 2 : 1], wa[VEC ? 2 : 1];
-    float xs[VEC ? 1 : 8], ws[VEC ? 1 : 8];
+    constexpr int NLD = VEC ? BM * BK / 4 / kThreads : BM * BK / kThreads;
+    float4 xa[VEC ? NLD : 1], wa[VEC ? NLD : 1];
+    float xs[VEC ? 1 : NLD], ws[VEC ? 1 : NLD];
 
     auto fetch = [&](int k0) {
 #pragma unroll
         for (int i = 0; i < NLD; ++i) {
             const int idx = tid + i * kThreads;
             if constexpr (VEC) {
-                const int row = idx >> 2, kq = (idx & 3) * 4;
+                const int row = idx / (BK / 4), kq = (idx % (BK / 4)) * 4;
                 const bool kin = k0 + kq < K;                 // K % 4 == 0: a whole float4 is in or out
                 xa[i] = (kin && m0 + row < M) ? *reinterpret_cast<const float4 *>(X + (m0 + row) * K + k0 + kq)
                                               : make_float4(0.f, 0.f, 0.f, 0.f);
                 wa[i] = (kin && n0 + row < N) ? *reinterpret_cast<const float4 *>(W + (int64_t)(n0 + row) * K + k0 + kq)
                                               : make_float4(0.f, 0.f, 0.f, 0.f);
             } else {
-                const int row = idx >> 4, k = idx & 15;
+                const int row = idx / BK, k = idx % BK;
                 const bool kin = k0 + k < K;
                 xs[i] = (kin && m0 + row < M) ? X[(m0 + row) * K + k0 + k] : 0.f;
                 ws[i] = (kin && n0 + row < N) ? W[(int64_t)(n0 + row) * K + k0 + k] : 0.f;
@@ -81,13 +84,13 @@ __global__ __launch_bounds__(kThreads) void mlp_gemm(const float *__restrict__ X
         for (int i = 0; i < NLD; ++i) {
             const int idx = tid + i * kThreads;
             if constexpr (VEC) {
-                const int row = idx >> 2, kq = (idx & 3) * 4;
+                const int row = idx / (BK / 4), kq = (idx % (BK / 4)) * 4;
                 As[buf][kq + 0][row] = xa[i].x; As[buf][kq + 1][row] = xa[i].y;
                 As[buf][kq + 2][row] = xa[i].z; As[buf][kq + 3][row] = xa[i].w;
                 Bs[buf][kq + 0][row] = wa[i].x; Bs[buf][kq + 1][row] = wa[i].y;
                 Bs[buf][kq + 2][row] = wa[i].z; Bs[buf][kq + 3][row] = wa[i].w;
             } else {
-                const int row = idx >> 4, k = idx & 15;
+                const int row = idx / BK, k = idx % BK;
                 As[buf][k][row] = xs[i];
                 Bs[buf][k][row] = ws[i];
             }
@@ -102,15 +105,27 @@ __global__ __launch_bounds__(kThreads) void mlp_gemm(const float *__restrict__ X
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
+    // operands of the next pair of k are read from LDS before the four multiplies of the current
+    // pair are issued, so their latency passes while the matrix pipe is busy
     auto multiply = [&](int buf) {
+        const float *pa = &As[buf][half][wm + l32], *pb = &Bs[buf][half][wn + l32];
+        float a0 = pa[0], a1 = pa[32], b0 = pb[0], b1 = pb[32];
+        __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
 #pragma unroll
         for (int kk = 0; kk < BK; kk += 2) {
-            const float a0 = As[buf][kk + half][wm + l32], a1 = As[buf][kk + half][wm + 32 + l32];
-            const float b0 = Bs[buf][kk + half][wn + l32], b1 = Bs[buf][kk + half][wn + 32 + l32];
+            float na0 = 0.f, na1 = 0.f, nb0 = 0.f, nb1 = 0.f;
+            if (kk + 2 < BK) {
+                na0 = pa[(kk + 2) * LDT]; na1 = pa[(kk + 2) * LDT + 32];
+                nb0 = pb[(kk + 2) * LDT]; nb1 = pb[(kk + 2) * LDT + 32];
+            }
             acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b0, acc[0][0], 0, 0, 0);
             acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b1, acc[0][1], 0, 0, 0);
             acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b0, acc[1][0], 0, 0, 0);
             acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b1, acc[1][1], 0, 0, 0);
+            a0 = na0; a1 = na1; b0 = nb0; b1 = nb1;
+            // keep that order in the schedule: the LDS reads of the pair, then its four multiplies
+            if (kk + 2 < BK) __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+            __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);
         }
     };
 
