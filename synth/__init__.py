@@ -187,7 +187,8 @@ def _rows_loguniform(seed: int, T: int, lo_exp: float, hi_exp: float) -> List[in
 
 
 def workload(cfg: int, size: str = "full") -> Workload:
-    """The five benchmark workloads (1..5), the paper's own heterogeneous setting (6), (``size="full"``) or reduced twins (``size="small"``).
+    """The five benchmark workloads (1..5) and the paper's own heterogeneous setting (6), at
+    full size or as reduced twins (``size="small"``).
 
     The reduced twins keep every structural feature (partition kind, ragged last
     shard, bag-length law, index law, dtype, ring depth) at sizes a CPU oracle
