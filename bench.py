@@ -175,11 +175,16 @@ def lag_demo(args) -> int:
     import torch
 
     import synth
-    from paper_2512_19342_amd.runner import Pipeline
+    from paper_2512_19342_amd.runner import BlsDlrmRanks, DenseModel, Pipeline
     dev = torch.device("cuda:0")
     base = synth.workload(args.config, args.size)
     tabs = [synth.make_table(base, t, dev) for t in range(base.T)]
     N, P = args.steps, base.P
+    if args.with_model:                                    # the dense model around every rank's lookup
+        bs, ts = synth.mlp_sizes(base, "full")
+        bot = [(W.to(dev), b.to(dev)) for W, b in synth.mlp_weights(base, bs, 0)]
+        top = [(W.to(dev), b.to(dev)) for W, b in synth.mlp_weights(base, ts, 1)]
+        dense = [synth.dense_features(base, i, dev) for i in range(4)]
     batches = [synth.make_batch(base, it, dev) for it in range(N)]
     nnzs = [int(off[-1].item()) for _, off in batches]
     delays = np.random.default_rng(2512).integers(0, args.max_delay_us + 1, size=(N, P))
@@ -196,6 +201,7 @@ def lag_demo(args) -> int:
             plans.append((pipe.ridx[:max(nnz, 1)].clone(), pipe.segoff.clone(), nnz))
         outs = [pipe.new_out() for _ in range(K)]
         streams = [torch.cuda.Stream() for _ in range(P)]
+        ranks = BlsDlrmRanks(pipe, DenseModel(c, bot, top, w.B), streams) if args.with_model else None
         ev = [[torch.cuda.Event(enable_timing=True) for _ in range(2)] for _ in range(P)]
         for with_delay in (None, False, True):           # None: an untimed warm-up pass without delays
             torch.cuda.synchronize()
@@ -207,14 +213,20 @@ def lag_demo(args) -> int:
                 it = first + j
                 if j >= K:
                     for s in range(P):
-                        c.bls_rank_complete(s, it - K, None, outs[(it - K) % K], streams[s])
+                        if ranks: ranks.finish(s, it - K)
+                        else: c.bls_rank_complete(s, it - K, None, outs[(it - K) % K], streams[s])
                 for d in range(P):
-                    if with_delay and delays[j, d]:
-                        c.bls_rank_delay(int(delays[j, d]), streams[d])
+                    dly = int(delays[j, d]) if with_delay else 0
+                    if ranks:
+                        ranks.issue(d, it, *plans[j], dense[j % 4], delay_us=dly)
+                        continue
+                    if dly:
+                        c.bls_rank_delay(dly, streams[d])
                     c.bls_rank_put(d, plans[j][0], None, plans[j][1], plans[j][2], it, streams[d])
             for j in range(max(N - K, 0), N):
                 for s in range(P):
-                    c.bls_rank_complete(s, first + j, None, outs[(first + j) % K], streams[s])
+                    if ranks: ranks.finish(s, first + j)
+                    else: c.bls_rank_complete(s, first + j, None, outs[(first + j) % K], streams[s])
             t_host = time.perf_counter() - t0
             for r in range(P):
                 ev[r][1].record(streams[r])
@@ -233,6 +245,7 @@ def lag_demo(args) -> int:
         del pipe
     print(json.dumps({"experiment": "per-rank streams with injected delays (the paper's Setting 2 on one GPU)",
                       "workload": WORKLOAD_TEXT[args.config], "iterations": N, "ranks": P,
+                      "model": "bottom MLP, interaction and top MLP per rank (Listing 2)" if args.with_model else "lookup only",
                       "max_delay_us": args.max_delay_us, "mean_delay_ms": args.max_delay_us / 2e3,
                       "expected_max_of_P_delays_ms": args.max_delay_us * P / (P + 1) / 1e3, "results": rows}))
     return 0
@@ -256,6 +269,8 @@ def main() -> int:
                     help="instead of the benchmark: per-rank streams with random delays, bound k swept "
                          "(use a workload with P <= 4, e.g. --config 2: a process has 4 hardware queues here, "
                          "more streams than that share queues and serialise)")
+    ap.add_argument("--with-model", action="store_true",
+                    help="with --lag-demo: every rank also runs the bottom MLP, the interaction and the top MLP of its mini-batch")
     ap.add_argument("--max-delay-us", type=int, default=1000)
     ap.add_argument("--bounds", type=int, nargs="+", default=[0, 1, 2, 4, 8])
     ap.add_argument("--table-dtype", default=None, choices=[None, "fp32", "fp16", "u8rq"],

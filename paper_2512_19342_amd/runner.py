@@ -134,28 +134,33 @@ class DenseModel:
         self.z = torch.empty((self.B, zdim), **f32)
         self.top_act = [torch.empty((self.B, W.shape[0]), **f32) for W, _ in self.top]
 
-    def apply_bottom(self, dense: torch.Tensor, x_out: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    def apply_bottom(self, dense: torch.Tensor, x_out: Optional[torch.Tensor] = None, stream=None,
+                     rows: Optional[tuple] = None) -> torch.Tensor:
         """x = bottom MLP of the dense features ``[B, n_dense]``, written to ``x_out`` [B, D]
-        (default: the model's own buffer, overwritten by the next call)."""
-        a = dense
+        (default: the model's own buffer, overwritten by the next call).  ``rows = (b0, bn)``
+        restricts the work to those samples (one rank's mini-batch); every tensor is the full one."""
+        lo, hi = (0, self.B) if rows is None else (rows[0], rows[0] + rows[1])
+        a = dense[lo:hi]
         for i, ((W, b), y) in enumerate(zip(self.bottom, self.bot_act)):
             if x_out is not None and i == len(self.bottom) - 1:
                 y = x_out
-            self.ctx.bls_mlp_layer(a, W, b, bls.BLS_ACT_RELU, y, stream)
-            a = y
-        return a
+            self.ctx.bls_mlp_layer(a, W, b, bls.BLS_ACT_RELU, y[lo:hi], stream)
+            a = y[lo:hi]
+        return y
 
-    def compute_ctr(self, x: torch.Tensor, emb: torch.Tensor, p_out: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    def compute_ctr(self, x: torch.Tensor, emb: torch.Tensor, p_out: Optional[torch.Tensor] = None, stream=None,
+                    rows: Optional[tuple] = None) -> torch.Tensor:
         """The prediction [B, 1] from the bottom MLP's output and the completed lookup [B, T, D]."""
-        self.ctx.bls_interact(x, emb, self.z, 0, self.B, stream)
-        a = self.z
+        lo, hi = (0, self.B) if rows is None else (rows[0], rows[0] + rows[1])
+        self.ctx.bls_interact(x, emb, self.z, lo, hi - lo, stream)
+        a = self.z[lo:hi]
         for i, ((W, b), y) in enumerate(zip(self.top, self.top_act)):
             last = i == len(self.top) - 1
             if last and p_out is not None:
                 y = p_out
-            self.ctx.bls_mlp_layer(a, W, b, bls.BLS_ACT_SIGMOID if last else bls.BLS_ACT_RELU, y, stream)
-            a = y
-        return a
+            self.ctx.bls_mlp_layer(a, W, b, bls.BLS_ACT_SIGMOID if last else bls.BLS_ACT_RELU, y[lo:hi], stream)
+            a = y[lo:hi]
+        return y
 
 
 class BlsDlrm:
@@ -198,3 +203,40 @@ class BlsDlrm:
             while self.unfinished:
                 done.append(self._finish_tail(stream))
         return done
+
+
+class BlsDlrmRanks:
+    """Listing 2 run by every simulated rank on a stream of its own.  ``issue(rank, ...)`` is the
+    rank's part of an iteration's start - its puts into the ring slot (owner side) and the bottom
+    MLP of its mini-batch; ``finish(rank, it)`` completes the rank's oldest iteration - copy-out
+    of its samples, interaction, top MLP.  The caller keeps every rank within K iterations of its
+    own completions (the library refuses a put into a slot a requester has not been asked to
+    release) and may run the ranks in any order; ranks never wait for each other on the host."""
+
+    def __init__(self, pipe: Pipeline, model: DenseModel, streams):
+        assert len(streams) == pipe.w.P
+        self.pipe, self.model, self.streams = pipe, model, streams
+        K, w = pipe.ctx.K, pipe.w
+        f32 = dict(dtype=torch.float32, device=pipe.dev)
+        self.first = [s * (w.B // w.P) + min(s, w.B % w.P) for s in range(w.P + 1)]
+        self.x_list = [torch.empty((w.B, w.D), **f32) for _ in range(K + 1)]
+        self.emb = [pipe.new_out() for _ in range(K)]
+        self.pred = [torch.empty((w.B, 1), **f32) for _ in range(K)]
+
+    def rows(self, rank: int) -> tuple:
+        return self.first[rank], self.first[rank + 1] - self.first[rank]
+
+    def issue(self, rank: int, it: int, ridx, segoff, nnz: int, dense, delay_us: int = 0):
+        c, st = self.pipe.ctx, self.streams[rank]
+        if delay_us:
+            c.bls_rank_delay(int(delay_us), st)
+        c.bls_rank_put(rank, ridx, None, segoff, nnz, it, st)
+        self.model.apply_bottom(dense, self.x_list[it % len(self.x_list)], st, self.rows(rank))
+
+    def finish(self, rank: int, it: int) -> torch.Tensor:
+        """Returns the prediction buffer of iteration ``it`` (valid for this rank's samples once
+        its stream has run; reused K iterations later)."""
+        c, st, K = self.pipe.ctx, self.streams[rank], self.pipe.ctx.K
+        c.bls_rank_complete(rank, it, None, self.emb[it % K], st)
+        self.model.compute_ctr(self.x_list[it % len(self.x_list)], self.emb[it % K], self.pred[it % K], st, self.rows(rank))
+        return self.pred[it % K]

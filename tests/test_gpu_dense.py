@@ -207,3 +207,68 @@ def test_bls_dlrm_loop_does_not_depend_on_the_bound(part_kind):
         p64, ep = oracle.mlp(z64, Lt, ez)
         p = ref_bits[it].view(np.float32)
         assert np.all(np.abs(p - p64) <= ep) and np.abs(p - p64).max() < 1e-6
+
+
+@pytest.mark.parametrize("k", [1, 3])
+def test_per_rank_model_loop_matches_the_whole_batch_loop(k):
+    """Every simulated rank on its own stream (puts + bottom MLP of its mini-batch, later copy-out,
+    interaction and top MLP), ranks visited in a scrambled order with device-side delays: the
+    predictions are the bits the single-stream loop gives."""
+    from paper_2512_19342_amd.runner import BlsDlrm, BlsDlrmRanks, DenseModel, Pipeline
+    n_iter = 7
+    w = synth.custom("ranks", P=4, T=5, D=32, B=90, k=k, part_kind=0, rows=[400, 64, 3000, 17, 256],
+                     bag=("uniform", 0, 10), index_dist=("zipf", 1.1), values="gauss", seed=53)   # 90 = 23+23+22+22
+    tabs = [synth.make_table(w, t).to(DEV) for t in range(w.T)]
+    batches = [synth.make_batch(w, it) for it in range(n_iter)]
+    dense = [synth.dense_features(w, it).to(DEV) for it in range(n_iter)]
+    bs, ts = synth.mlp_sizes(w, "small")
+    bot = [(W.to(DEV), b.to(DEV)) for W, b in synth.mlp_weights(w, bs, 0)]
+    top = [(W.to(DEV), b.to(DEV)) for W, b in synth.mlp_weights(w, ts, 1)]
+    max_nnz = max(int(o[-1]) for _, o in batches)
+
+    pipe = Pipeline(w, tabs, max_nnz)
+    loop = BlsDlrm(pipe, DenseModel(pipe.ctx, bot, top, w.B))
+    want = {}
+    for it in range(n_iter):
+        ix, off = batches[it]
+        for j, p in loop.forward(dense[it], ix.to(DEV), off.to(DEV), int(off[-1]), last_batch=it == n_iter - 1):
+            want[j] = p.cpu().numpy()
+    pipe.ctx.bls_check()
+
+    pipe2 = Pipeline(w, tabs, max_nnz)
+    c, K, P = pipe2.ctx, pipe2.ctx.K, w.P
+    plans = []
+    for ix, off in batches:
+        nnz = int(off[-1])
+        c.bls_plan(ix.to(DEV), off.to(DEV), nnz, pipe2.sendcounts, pipe2.sdispls, pipe2.recvcounts, pipe2.rdispls,
+                   pipe2.ridx, pipe2.segoff, None, pipe2.ws)
+        plans.append((pipe2.ridx[:max(nnz, 1)].clone(), pipe2.segoff.clone(), nnz))
+    torch.cuda.synchronize()
+    streams = [torch.cuda.Stream() for _ in range(P)]
+    ranks = BlsDlrmRanks(pipe2, DenseModel(c, bot, top, w.B), streams)
+    rng = np.random.default_rng(k)
+    got = {}
+
+    def finish_all(it):
+        parts = []
+        for s in rng.permutation(P):
+            pred = ranks.finish(int(s), it)
+            lo, n = ranks.rows(int(s))
+            with torch.cuda.stream(streams[s]):
+                parts.append((lo, n, pred[lo:lo + n].clone()))       # the buffer is reused K iterations later
+        got[it] = parts
+
+    for it in range(n_iter):
+        if it >= K:
+            finish_all(it - K)
+        for d in rng.permutation(P):
+            ranks.issue(int(d), it, *plans[it], dense[it], delay_us=int(rng.integers(0, 300)))
+    for it in range(max(n_iter - K, 0), n_iter):
+        finish_all(it)
+    torch.cuda.synchronize()
+    c.bls_check()
+    for it in range(n_iter):
+        full = np.empty((w.B, 1), np.float32)
+        for lo, n, part in got[it]:
+            full[lo:lo + n] = part.cpu().numpy()
+        assert np.array_equal(full.view(np.uint32), want[it].view(np.uint32)), it
