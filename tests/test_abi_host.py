@@ -93,3 +93,24 @@ def test_ring_bookkeeping_without_gpu(B):
 def test_bench_refuses_more_than_one_gpu():
     r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
     assert r.returncode != 0 and "one GPU" in r.stderr
+
+
+def test_missing_library_fails_loudly(B, monkeypatch, tmp_path):
+    """No built library, no path: the binding raises instead of computing anything elsewhere."""
+    import paper_2512_19342_amd.bls as mod
+    monkeypatch.setattr(mod, "_lib", None)
+    monkeypatch.setattr(mod, "lib_path", lambda: str(tmp_path / "libbls.so"))
+    with pytest.raises(RuntimeError, match="no fallback"):
+        mod.Context(2, 2, 4, 1, 4, [5, 5], [0, 1])
+
+
+def test_product_never_imports_the_oracle():
+    """The oracle is test infrastructure: nothing under the package or the generators names it."""
+    import re
+    for folder in ("paper_2512_19342_amd", "synth"):
+        for dirpath, _, files in os.walk(os.path.join(ROOT, folder)):
+            for f in files:
+                if f.endswith((".py", ".hip", ".h", ".c", ".cpp")):
+                    text = open(os.path.join(dirpath, f)).read()
+                    assert not re.search(r"^\s*(import|from)\s+oracle\b", text, re.M), f
+                    assert "bls_oracle" not in text and "orc_" not in text, f
