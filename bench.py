@@ -167,6 +167,77 @@ def dense_section(args, w, pipe, batches, nnzs, note) -> dict:
                      "completed": done}}
 
 
+def alltoallv_demo(args) -> int:
+    """The paper's two alltoallv microbenchmarks (Results, Alltoallv benchmarks) for the device-local
+    exchange with k = 0: (a) one collective (slot acquire, exchange, completion copy-out) for equal
+    message sizes per rank from 32 B to 256 MiB, (b) 1 .. 100 000 collectives in sequence at 32 KiB per
+    rank.  P = 8 ranks, one table per rank, so a rank sends B*D*4 bytes in all."""
+    import torch
+
+    import paper_2512_19342_amd as A
+    dev = torch.device("cuda:0")
+    P = 8
+
+    def make(per_rank_bytes: int):
+        D = 128 if per_rank_bytes >= 4096 else 1
+        B = max(P, per_rank_bytes // (4 * D))
+        c = A.Context(P, P, D, 0, B, [1] * P, list(range(P)))
+        tabs = [torch.zeros((1, D), dtype=torch.float32, device=dev) for _ in range(P)]
+        for t in range(P):
+            c.bls_set_shard(t, t, tabs[t])
+        n = P * B * D
+        send = torch.rand(n, dtype=torch.float32, device=dev)
+        slot = torch.empty(n, dtype=torch.float32, device=dev)
+        out = torch.empty((B, P, D), dtype=torch.float32, device=dev)
+        c.bls_set_ring(slot)
+        return c, send, out, B * D * 4, tabs
+
+    def collective(c, send, out):
+        it, slot = c.bls_ring_advance()
+        c.bls_alltoallv_local(send, slot)
+        c.bls_unpack(it, out)
+
+    sizes, rows_a = [32 << i for i in range(0, 24)], []          # 32 B .. 256 MiB per rank
+    for sz in sizes:
+        c, send, out, actual, _keep = make(sz)
+        for _ in range(3):
+            collective(c, send, out)
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+        reps = 20
+        torch.cuda.synchronize()
+        ev[0].record()
+        for _ in range(reps):
+            collective(c, send, out)
+        ev[1].record()
+        torch.cuda.synchronize()
+        c.bls_check()
+        us = ev[0].elapsed_time(ev[1]) / reps * 1e3
+        # bytes moved: exchange reads and writes all P messages, the copy-out reads and writes them again
+        rows_a.append({"bytes_per_rank": actual, "us_per_collective": us, "GBps_moved": 4 * P * actual / (us * 1e-6) / 1e9})
+        print(f"[a2a] {actual:>10d} B per rank: {us:9.2f} us", file=sys.stderr, flush=True)
+        del c, send, out, _keep
+
+    rows_b = []
+    c, send, out, actual, _keep = make(32 * 1024)
+    for _ in range(10):
+        collective(c, send, out)
+    torch.cuda.synchronize()
+    for reps in (1, 10, 100, 1000, 10000, 100000):
+        t0 = time.perf_counter()
+        for _ in range(reps):
+            collective(c, send, out)
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+        c.bls_check()
+        rows_b.append({"collectives": reps, "seconds": dt, "us_per_collective": dt / reps * 1e6})
+        print(f"[a2a] {reps:>6d} collectives of {actual} B per rank: {dt:.4f} s ({dt / reps * 1e6:.2f} us each)",
+              file=sys.stderr, flush=True)
+    print(json.dumps({"experiment": "device-local alltoallv microbenchmarks, k = 0 (the paper's message-size and repetition sweeps)",
+                      "ranks": P, "entry_points": "bls_ring_advance + bls_alltoallv_local + bls_unpack",
+                      "message_size_sweep": rows_a, "repetition_sweep_32KiB_per_rank": rows_b}))
+    return 0
+
+
 def lag_demo(args) -> int:
     """The paper's Setting 2 on one GPU: every simulated rank on its own stream, a uniformly random
     delay before each rank's work in every iteration, bound k swept.  With k = 0 every iteration
@@ -269,6 +340,8 @@ def main() -> int:
                     help="instead of the benchmark: per-rank streams with random delays, bound k swept "
                          "(use a workload with P <= 4, e.g. --config 2: a process has 4 hardware queues here, "
                          "more streams than that share queues and serialise)")
+    ap.add_argument("--alltoallv-demo", action="store_true",
+                    help="instead of the benchmark: the paper's alltoallv microbenchmarks for the device-local exchange")
     ap.add_argument("--with-model", action="store_true",
                     help="with --lag-demo: every rank also runs the bottom MLP, the interaction and the top MLP of its mini-batch")
     ap.add_argument("--max-delay-us", type=int, default=1000)
@@ -294,6 +367,8 @@ def main() -> int:
         return 2
     if args.lag_demo:
         return lag_demo(args)
+    if args.alltoallv_demo:
+        return alltoallv_demo(args)
     dev = torch.device("cuda:0")
     w = synth.workload(args.config, args.size)
     if args.index_dist == "uniform":
