@@ -313,7 +313,7 @@ extern "C" int bls_ring_advance(bls_ctx *ctx, int64_t *iter_out, int32_t *slot_o
     const int64_t j = ctx->head;
     const int slot = (int)(j % ctx->K);
     RingSlot &r = ctx->ring[slot];
-    if (r.has_released)   // the stream that refills the slot must see the earlier copy-out finished
+    if (r.has_released && r.released_on != (hipStream_t)hip_stream)   // the stream that refills the slot must see the earlier copy-out finished
         BLS_HIP(ctx, hipStreamWaitEvent((hipStream_t)hip_stream, r.released, 0));
     r.state = 1;
     r.iter = j;
@@ -359,6 +359,7 @@ extern "C" int bls_alltoallv_local(bls_ctx *ctx, const float *d_send, int32_t sl
     rc = bls_launch_exchange(ctx, d_send, (float *)(ctx->slots + (size_t)slot * ctx->slot_bytes), (hipStream_t)hip_stream);
     if (rc) return rc;
     BLS_HIP(ctx, hipEventRecord(r->filled, (hipStream_t)hip_stream));
+    r->filled_on = (hipStream_t)hip_stream;
     r->state = 2;
     return BLS_OK;
 }
@@ -374,6 +375,7 @@ static int put_common(bls_ctx *ctx, const int64_t *d_ridx, const float *d_rweigh
                          0, ctx->Q, (hipStream_t)hip_stream);
     if (rc) return rc;
     BLS_HIP(ctx, hipEventRecord(r->filled, (hipStream_t)hip_stream));
+    r->filled_on = (hipStream_t)hip_stream;
     r->state = 2;
     return BLS_OK;
 }
@@ -403,11 +405,12 @@ static int unpack_common(bls_ctx *ctx, int64_t iter, const int64_t *mean_off, fl
     if (r.state != 2) return bls_fail(ctx, BLS_EORDER, "bls_unpack: the iteration's exchange has not been issued");
     int rc = bls_commit(ctx);
     if (rc) return rc;
-    BLS_HIP(ctx, hipStreamWaitEvent((hipStream_t)hip_stream, r.filled, 0));
+    if (r.filled_on != (hipStream_t)hip_stream) BLS_HIP(ctx, hipStreamWaitEvent((hipStream_t)hip_stream, r.filled, 0));
     rc = bls_launch_unpack(ctx, (const float *)(ctx->slots + (size_t)slot * ctx->slot_bytes), d_out, mean_off, 0u,
                            (uint32_t)ctx->B, (hipStream_t)hip_stream);
     if (rc) return rc;
     BLS_HIP(ctx, hipEventRecord(r.released, (hipStream_t)hip_stream));
+    r.released_on = (hipStream_t)hip_stream;
     r.has_released = true;
     r.state = 0;
     ctx->tail = iter + 1;
@@ -440,6 +443,8 @@ static int rank_ring_init(bls_ctx *ctx)
     rr.released.assign(n, nullptr);
     rr.has_arrived.assign(n, 0);
     rr.has_released.assign(n, 0);
+    rr.arrived_on.assign(n, nullptr);
+    rr.released_on.assign(n, nullptr);
     for (size_t i = 0; i < n; ++i) {
         BLS_HIP(ctx, hipEventCreateWithFlags(&rr.arrived[i], hipEventDisableTiming));
         BLS_HIP(ctx, hipEventCreateWithFlags(&rr.released[i], hipEventDisableTiming));
@@ -467,12 +472,14 @@ extern "C" int bls_rank_put(bls_ctx *ctx, int32_t rank, const int64_t *d_ridx, c
     const int slot = (int)(iter % ctx->K);
     hipStream_t st = (hipStream_t)hip_stream;
     for (int s = 0; s < ctx->P; ++s)
-        if (rr.has_released[(size_t)slot * ctx->P + s]) BLS_HIP(ctx, hipStreamWaitEvent(st, rr.released[(size_t)slot * ctx->P + s], 0));
+        if (rr.has_released[(size_t)slot * ctx->P + s] && rr.released_on[(size_t)slot * ctx->P + s] != st)
+            BLS_HIP(ctx, hipStreamWaitEvent(st, rr.released[(size_t)slot * ctx->P + s], 0));
     rc = bls_launch_pool(ctx, d_ridx, nnz > 0 ? d_rweights : nullptr, d_segoff, nnz,
                          (float *)(ctx->slots + (size_t)slot * ctx->slot_bytes), 1, ctx->nsum[rank], ctx->n_loc[rank], st);
     if (rc) return rc;
     BLS_HIP(ctx, hipEventRecord(rr.arrived[(size_t)slot * ctx->P + rank], st));
     rr.has_arrived[(size_t)slot * ctx->P + rank] = 1;
+    rr.arrived_on[(size_t)slot * ctx->P + rank] = st;
     rr.put_next[rank] = iter + 1;
     return BLS_OK;
 }
@@ -492,12 +499,14 @@ extern "C" int bls_rank_complete(bls_ctx *ctx, int32_t rank, int64_t iter, const
     const int slot = (int)(iter % ctx->K);
     hipStream_t st = (hipStream_t)hip_stream;
     // completion = the blocks of all P owners have arrived (the paper polls a tag counter for this)
-    for (int d = 0; d < ctx->P; ++d) BLS_HIP(ctx, hipStreamWaitEvent(st, rr.arrived[(size_t)slot * ctx->P + d], 0));
+    for (int d = 0; d < ctx->P; ++d)
+        if (rr.arrived_on[(size_t)slot * ctx->P + d] != st) BLS_HIP(ctx, hipStreamWaitEvent(st, rr.arrived[(size_t)slot * ctx->P + d], 0));
     int rc = bls_launch_unpack(ctx, (const float *)(ctx->slots + (size_t)slot * ctx->slot_bytes), d_out, d_mean_offsets,
                                (uint32_t)ctx->first[rank], (uint32_t)(ctx->first[rank + 1] - ctx->first[rank]), st);
     if (rc) return rc;
     BLS_HIP(ctx, hipEventRecord(rr.released[(size_t)slot * ctx->P + rank], st));
     rr.has_released[(size_t)slot * ctx->P + rank] = 1;
+    rr.released_on[(size_t)slot * ctx->P + rank] = st;
     rr.done_next[rank] = iter + 1;
     return BLS_OK;
 }

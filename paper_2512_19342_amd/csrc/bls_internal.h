@@ -44,6 +44,7 @@ struct RankRing {
     std::vector<int64_t> put_next, done_next;     // [P] next iteration rank r puts / completes
     std::vector<hipEvent_t> arrived, released;    // [K*P] slot-major
     std::vector<uint8_t> has_arrived, has_released;
+    std::vector<hipStream_t> arrived_on, released_on;   // stream of the last record: same-stream waits are skipped
 };
 
 struct RingSlot {
@@ -52,6 +53,9 @@ struct RingSlot {
     hipEvent_t filled = nullptr;   // recorded after the exchange into the slot
     hipEvent_t released = nullptr; // recorded after the slot was copied out
     bool has_released = false;
+    // streams the two events were last recorded on: a wait from the same stream is implied by
+    // stream order and is not enqueued
+    hipStream_t filled_on = nullptr, released_on = nullptr;
 };
 
 struct bls_ctx {
