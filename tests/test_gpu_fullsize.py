@@ -102,3 +102,43 @@ def test_full_size(cfg, storage):
             for name, buf, at in (("Y", Yv, q * B + b), ("S", Sv, sigma), ("R", Rv, rho)):
                 assert np.array_equal(buf[at].cpu().numpy().view(np.uint32), part32.view(np.uint32)), (name, t, b, d)
     print(f"  {n_samples} sampled bags match in Y, S, R and Out", flush=True)
+
+
+def test_dense_model_full_size():
+    """The dense model at the benchmark's batch (16384 samples, D = 128, T = 64; layer widths as
+    bench.py times them): every kernel runs on the whole batch, the oracle recomputes sampled
+    samples of every kernel's output from the inputs that kernel received."""
+    import paper_2512_19342_amd as A
+    from paper_2512_19342_amd.runner import DenseModel
+    w = synth.workload(4, "full")
+    dev = torch.device("cuda:0")
+    c = A.Context(w.P, w.T, w.D, w.k, w.B, w.rows, w.table_owner)
+    bs, ts = synth.mlp_sizes(w, "full")
+    bot, top = synth.mlp_weights(w, bs, 0), synth.mlp_weights(w, ts, 1)
+    model = DenseModel(c, [(W.to(dev), b.to(dev)) for W, b in bot], [(W.to(dev), b.to(dev)) for W, b in top], w.B)
+    dense = synth.dense_features(w, 2, dev)
+    gen = torch.Generator(device="cpu").manual_seed(11)
+    emb = (torch.randn((w.B, w.T, w.D), generator=gen) * 0.05).to(dev)       # stands in for the completed lookup
+    print(f"dense model at full size: batch {w.B}, bottom {bs}, top {ts}", flush=True)
+    x = model.apply_bottom(dense)
+    p = model.compute_ctr(x, emb)
+    c.bls_check()
+
+    rng = np.random.default_rng(4)
+    rows = np.unique(np.concatenate([[0, 127, 128, w.B - 1], rng.integers(0, w.B, 44)]))   # tile edges and random samples
+    pick = torch.from_numpy(rows).to(dev)
+    a = dense[pick].cpu().numpy()
+    for (W, b), y in zip(bot, model.bot_act):
+        ref, err = oracle.mlp_layer(a, W.numpy(), b.numpy(), 1)
+        a = y[pick].cpu().numpy()
+        assert np.all(np.abs(a - ref) <= err), ("bottom", W.shape)
+    ref, err = oracle.interact(a, emb[pick].cpu().numpy())
+    a = model.z[pick].cpu().numpy()
+    assert np.all(np.abs(a - ref) <= err), "interaction"
+    for i, ((W, b), y) in enumerate(zip(top, model.top_act)):
+        ref, err = oracle.mlp_layer(a, W.numpy(), b.numpy(), 2 if i == len(top) - 1 else 1)
+        a = y[pick].cpu().numpy()
+        assert np.all(np.abs(a - ref) <= err), ("top", W.shape)
+    got = p[pick].cpu().numpy()
+    assert np.array_equal(got, a) and np.all((got > 0) & (got < 1))
+    print(f"  {len(rows)} sampled samples match through {len(bot) + len(top)} layers and the interaction", flush=True)
