@@ -143,28 +143,33 @@ def dense_section(args, w, pipe, batches, nnzs, note) -> dict:
     note(f"torch.mm (rocBLAS / hipBLASLt) on the same shape: {lib_tflops:.1f} TFLOP/s")
 
     # Listing 2's loop: lookup (fused owner side) + bottom MLP per call, completion + prediction k calls later
-    loop = BlsDlrm(pipe, model)
-    torch.cuda.synchronize()
-    for i in range(args.warmup):
-        loop.forward(dense[i % 2], *batches[i % len(batches)], nnzs[i % len(batches)])
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    done = 0
-    for i in range(args.steps):
-        done += len(loop.forward(dense[i % 2], *batches[i % len(batches)], nnzs[i % len(batches)], last_batch=i == args.steps - 1))
-    torch.cuda.synchronize()
-    dt = time.perf_counter() - t0
-    c.bls_check()
-    note(f"{args.steps} iterations of the model loop: {dt / args.steps * 1e3:.3f} ms per iteration")
+    loops = {}
+    for fused_completion in (False, True):
+        loop = BlsDlrm(pipe, model, fused_completion=fused_completion)
+        torch.cuda.synchronize()
+        for i in range(args.warmup):
+            loop.forward(dense[i % 2], *batches[i % len(batches)], nnzs[i % len(batches)], last_batch=i == args.warmup - 1)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        done = 0
+        for i in range(args.steps):
+            done += len(loop.forward(dense[i % 2], *batches[i % len(batches)], nnzs[i % len(batches)], last_batch=i == args.steps - 1))
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+        c.bls_check()
+        assert done == args.steps
+        what = "completion folded into the interaction" if fused_completion else "copy-out, then interaction"
+        note(f"{args.steps} iterations of the model loop ({what}): {dt / args.steps * 1e3:.3f} ms per iteration")
+        loops["folded_completion" if fused_completion else "staged_completion"] = {
+            "ms_per_iteration": dt / args.steps * 1e3, "samples_per_s": w.B * args.steps / dt}
     mm = [k for k in range(n) if names[k] != "interact"]
     return {"layers": {"bottom": bs, "top": ts}, "kernels": kernels, "dense_ms_per_batch": sum(ms),
             "library_gemm_tflops_same_shape": lib_tflops,
             "mlp_tflops": sum(flops[k] for k in mm) / (sum(ms[k] for k in mm) * 1e-3) / 1e12,
             "mfma_roofline": {"bound": "mfma", "kernel": f"mlp_gemm ({names[big]})", "achieved": kernels[names[big]]["tflops"],
                               "peak": 157.3, "unit": "TFLOP/s", "frac": kernels[names[big]]["tflops"] / 157.3},
-            "loop": {"entry_points": "bls_plan + bls_embbag_pool_put + bls_mlp_layer x3 | bls_unpack + bls_interact + bls_mlp_layer x5",
-                     "bound": w.k, "ms_per_iteration": dt / args.steps * 1e3, "samples_per_s": w.B * args.steps / dt,
-                     "completed": done}}
+            "loop": {"entry_points": "bls_plan + bls_embbag_pool_put + bls_mlp_layer x3 | bls_unpack + bls_interact "
+                                     "(or bls_unpack_interact) + bls_mlp_layer x5", "bound": w.k, **loops}}
 
 
 def alltoallv_demo(args) -> int:

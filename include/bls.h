@@ -238,12 +238,19 @@ int bls_rank_delay(bls_ctx *ctx, uint32_t microseconds, void *hip_stream);
  *   the order i = 1..T, j = 0..i-1.  d_x is [B][D], d_emb is [B][T][D] (the output of
  *   bls_unpack), d_z is [B][D + T(T+1)/2].  BLS_EINVAL if the T vectors of a sample do not
  *   fit in 64 KB of LDS (about T * D <= 16000).
+ * bls_unpack_interact: completion of iteration `iter` (the oldest in flight, as for bls_unpack)
+ *   folded into the interaction: the pooled vectors are read from the iteration's ring slot where
+ *   their owners put them (row-wise: the P partial vectors added in increasing owner rank, as
+ *   bls_unpack does) and d_z[B][D + T(T+1)/2] is written for the whole batch; no [B][T][D] output
+ *   is produced.  The slot is released as by bls_unpack.  Same results, bit for bit, as
+ *   bls_unpack followed by bls_interact.
  */
 enum { BLS_ACT_NONE = 0, BLS_ACT_RELU = 1, BLS_ACT_SIGMOID = 2 };
 int bls_mlp_layer(bls_ctx *ctx, const float *d_x, int64_t M, int32_t K, const float *d_W, const float *d_bias,
                   int32_t N, int32_t act, float *d_y, void *hip_stream);
 int bls_interact(bls_ctx *ctx, const float *d_x, const float *d_emb, float *d_z, int64_t b0, int64_t bn,
                  void *hip_stream);
+int bls_unpack_interact(bls_ctx *ctx, int64_t iter, const float *d_x, float *d_z, void *hip_stream);
 
 /* Ring state for callers and tests: next iteration number, oldest in flight, K. */
 int bls_ring_state(const bls_ctx *ctx, int64_t *head, int64_t *tail, int32_t *K);

@@ -23,7 +23,7 @@ EXPORTS = [
     "bls_create", "bls_destroy", "bls_set_shard", "bls_sizes", "bls_pooled_counts", "bls_plan", "bls_plan_weighted",
     "bls_embbag_pool", "bls_embbag_pool_weighted", "bls_embbag_pool_put", "bls_embbag_pool_put_weighted", "bls_pack",
     "bls_set_ring", "bls_ring_advance", "bls_alltoallv_local", "bls_unpack", "bls_unpack_mean", "bls_ring_state",
-    "bls_rank_put", "bls_rank_complete", "bls_rank_delay", "bls_mlp_layer", "bls_interact", "bls_check", "bls_last_error",
+    "bls_rank_put", "bls_rank_complete", "bls_rank_delay", "bls_mlp_layer", "bls_interact", "bls_unpack_interact", "bls_check", "bls_last_error",
 ]
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
@@ -74,6 +74,7 @@ def lib() -> C.CDLL:
         L.bls_ring_state.argtypes = [vp, C.POINTER(C.c_int64), C.POINTER(C.c_int64), C.POINTER(C.c_int32)]
         L.bls_mlp_layer.argtypes = [vp, vp, C.c_int64, C.c_int32, vp, vp, C.c_int32, C.c_int32, vp, vp]
         L.bls_interact.argtypes = [vp, vp, vp, vp, C.c_int64, C.c_int64, vp]
+        L.bls_unpack_interact.argtypes = [vp, C.c_int64, vp, vp, vp]
         L.bls_check.argtypes = [vp, vp]
         L.bls_last_error.argtypes = [vp]
         L.bls_last_error.restype = C.c_char_p
@@ -227,6 +228,9 @@ class Context:
     def bls_interact(self, x, emb, z, b0=0, bn=None, stream=None):
         self._call("bls_interact", _ptr(x), _ptr(emb), _ptr(z), int(b0), int(self.B - b0 if bn is None else bn),
                    _stream(stream))
+
+    def bls_unpack_interact(self, it, x, z, stream=None):
+        self._call("bls_unpack_interact", int(it), _ptr(x), _ptr(z), _stream(stream))
 
     def bls_ring_state(self):
         h, t, k = C.c_int64(), C.c_int64(), C.c_int32()

@@ -166,7 +166,12 @@ __global__ __launch_bounds__(kThreads) void mlp_gemm(const float *__restrict__ X
 // tile one accumulator over D / 2 matrix instructions; the last wavefront also takes the T
 // products with the dense vector x.  Output row: x, then for i = 1..T the products of pooled
 // vector i-1 with x and with pooled vectors 0..i-2.
-__global__ __launch_bounds__(kThreads) void interact_gram(const float *__restrict__ x, const float *__restrict__ emb,
+// SLOT = false: emb is the completed lookup [B][T][D].  SLOT = true: emb is a ring slot in receive
+// order and the copy to LDS is the completion itself - vector (b, t) is read where its owner put
+// it, and for a row-wise partition the P partial vectors are added in increasing owner rank from
+// +0, exactly as the copy-out kernel does.
+template <bool SLOT>
+__global__ __launch_bounds__(kThreads) void interact_gram(DevDesc dd, const float *__restrict__ x, const float *__restrict__ emb,
                                                           float *__restrict__ z, int T, int D, int TP, int LD,
                                                           uint32_t b0, int vec4)
 {
@@ -176,8 +181,19 @@ __global__ __launch_bounds__(kThreads) void interact_gram(const float *__restric
     const int64_t b = (int64_t)b0 + blockIdx.x;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int64_t Wz = (int64_t)D + (int64_t)T * (T + 1) / 2;
-    const float *__restrict__ e = emb + b * T * D;
+    const float *__restrict__ e = emb + b * T * D;               // SLOT = false only
     float *__restrict__ zb = z + b * Wz;
+    int64_t slot_base = 0, slot_step = 0;                        // vector (q, b) of the slot: slot_base + q * slot_step
+    if constexpr (SLOT) {
+        int s; uint32_t b_loc, n;
+        bls_split_sample(dd, (uint32_t)b, s, b_loc, n);
+        slot_base = (int64_t)dd.Q * dd.first[s] + b_loc;
+        slot_step = n;
+    }
+    // start of the d-th partial (d < F; F = 1 table-wise) of pooled vector t of this sample
+    auto partial = [&](uint32_t t, int d) -> const float * {
+        return emb + (slot_base + (int64_t)(dd.t_q[t] + d * dd.T) * slot_step) * D;
+    };
 
     // zeros: the padding columns behind every vector and the padding rows behind the last one
     const int padc = LD - D;
@@ -193,7 +209,18 @@ __global__ __launch_bounds__(kThreads) void interact_gram(const float *__restric
 #pragma unroll
             for (int u = 0; u < kFill; ++u) {
                 const uint32_t i = base + u * kThreads + tid;
-                v[u] = i < n4 ? e4[i] : make_float4(0.f, 0.f, 0.f, 0.f);
+                v[u] = make_float4(0.f, 0.f, 0.f, 0.f);
+                if constexpr (SLOT) {
+                    if (i < n4) {
+                        const uint32_t r = i / c4n, c = (i - r * c4n) * 4u;
+                        for (int d = 0; d < dd.F; ++d) {
+                            const float4 part = *reinterpret_cast<const float4 *>(partial(r, d) + c);
+                            v[u].x += part.x; v[u].y += part.y; v[u].z += part.z; v[u].w += part.w;
+                        }
+                    }
+                } else if (i < n4) {
+                    v[u] = e4[i];
+                }
             }
 #pragma unroll
             for (int u = 0; u < kFill; ++u) {
@@ -212,7 +239,15 @@ __global__ __launch_bounds__(kThreads) void interact_gram(const float *__restric
 #pragma unroll
             for (int u = 0; u < kFill; ++u) {
                 const uint32_t i = base + u * kThreads + tid;
-                v[u] = i < n1 ? e[i] : 0.f;
+                v[u] = 0.f;
+                if constexpr (SLOT) {
+                    if (i < n1) {
+                        const uint32_t r = i / (uint32_t)D, c = i - r * (uint32_t)D;
+                        for (int d = 0; d < dd.F; ++d) v[u] += partial(r, d)[c];
+                    }
+                } else if (i < n1) {
+                    v[u] = e[i];
+                }
             }
 #pragma unroll
             for (int u = 0; u < kFill; ++u) {
@@ -289,13 +324,16 @@ size_t bls_interact_lds_bytes(int T, int D)
     return ((size_t)TP * LD + (size_t)D) * sizeof(float);
 }
 
-int bls_launch_interact(bls_ctx *ctx, const float *x, const float *emb, float *z, uint32_t b0, uint32_t bn, hipStream_t st)
+int bls_launch_interact(bls_ctx *ctx, const float *x, const float *emb, int from_slot, float *z, uint32_t b0, uint32_t bn,
+                        hipStream_t st)
 {
     if (bn == 0) return BLS_OK;
     const int T = ctx->T, D = ctx->D;
     const int TP = (T + 31) / 32 * 32, LD = ((D + 1) & ~1) + 1;
-    const int vec4 = D % 4 == 0 && ((uintptr_t)emb & 15u) == 0;   // every sample's T*D floats then start 16-byte aligned
-    interact_gram<<<dim3(bn), kThreads, bls_interact_lds_bytes(T, D), st>>>(x, emb, z, T, D, TP, LD, b0, vec4);
+    const int vec4 = D % 4 == 0 && ((uintptr_t)emb & 15u) == 0;   // every vector then starts 16-byte aligned
+    const size_t lds = bls_interact_lds_bytes(T, D);
+    if (from_slot) interact_gram<true><<<dim3(bn), kThreads, lds, st>>>(ctx->desc, x, emb, z, T, D, TP, LD, b0, vec4);
+    else interact_gram<false><<<dim3(bn), kThreads, lds, st>>>(ctx->desc, x, emb, z, T, D, TP, LD, b0, vec4);
     BLS_HIP(ctx, hipGetLastError());
     return BLS_OK;
 }

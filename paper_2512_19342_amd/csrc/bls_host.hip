@@ -538,7 +538,32 @@ extern "C" int bls_interact(bls_ctx *ctx, const float *d_x, const float *d_emb, 
     if (bls_interact_lds_bytes(ctx->T, ctx->D) > 64 * 1024)
         return bls_fail(ctx, BLS_EINVAL, "bls_interact: the pooled vectors of one sample do not fit in 64 KB of LDS");
     if (bn > 0 && (!d_x || !d_emb || !d_z)) return bls_fail(ctx, BLS_EINVAL, "bls_interact: NULL array");
-    return bls_launch_interact(ctx, d_x, d_emb, d_z, (uint32_t)b0, (uint32_t)bn, (hipStream_t)hip_stream);
+    return bls_launch_interact(ctx, d_x, d_emb, 0, d_z, (uint32_t)b0, (uint32_t)bn, (hipStream_t)hip_stream);
+}
+
+extern "C" int bls_unpack_interact(bls_ctx *ctx, int64_t iter, const float *d_x, float *d_z, void *hip_stream)
+{
+    if (!ctx) return BLS_EINVAL;
+    if (ctx->head == ctx->tail) return bls_fail(ctx, BLS_ERING_EMPTY, "bls_unpack_interact: nothing in flight");
+    if (iter != ctx->tail) return bls_fail(ctx, BLS_EORDER, "bls_unpack_interact: not the oldest iteration in flight");
+    if (!d_x || !d_z) return bls_fail(ctx, BLS_EINVAL, "bls_unpack_interact: NULL array");
+    if (bls_interact_lds_bytes(ctx->T, ctx->D) > 64 * 1024)
+        return bls_fail(ctx, BLS_EINVAL, "bls_unpack_interact: the pooled vectors of one sample do not fit in 64 KB of LDS");
+    const int slot = (int)(iter % ctx->K);
+    RingSlot &r = ctx->ring[slot];
+    if (r.state != 2) return bls_fail(ctx, BLS_EORDER, "bls_unpack_interact: the iteration's exchange has not been issued");
+    int rc = bls_commit(ctx);
+    if (rc) return rc;
+    if (r.filled_on != (hipStream_t)hip_stream) BLS_HIP(ctx, hipStreamWaitEvent((hipStream_t)hip_stream, r.filled, 0));
+    rc = bls_launch_interact(ctx, d_x, (const float *)(ctx->slots + (size_t)slot * ctx->slot_bytes), 1, d_z, 0u, (uint32_t)ctx->B,
+                             (hipStream_t)hip_stream);
+    if (rc) return rc;
+    BLS_HIP(ctx, hipEventRecord(r.released, (hipStream_t)hip_stream));
+    r.released_on = (hipStream_t)hip_stream;
+    r.has_released = true;
+    r.state = 0;
+    ctx->tail = iter + 1;
+    return BLS_OK;
 }
 
 extern "C" int bls_check(bls_ctx *ctx, void *hip_stream)

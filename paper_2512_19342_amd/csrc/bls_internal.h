@@ -114,7 +114,9 @@ int bls_launch_delay(bls_ctx *ctx, uint32_t microseconds, hipStream_t st);
 int bls_launch_mlp_layer(bls_ctx *ctx, const float *x, int64_t M, int K, const float *W, const float *bias, int N,
                          int act, float *y, hipStream_t st);
 size_t bls_interact_lds_bytes(int T, int D);
-int bls_launch_interact(bls_ctx *ctx, const float *x, const float *emb, float *z, uint32_t b0, uint32_t bn, hipStream_t st);
+// from_slot = 0: emb is [B][T][D]; 1: emb is a ring slot in receive order (the copy-out is folded in)
+int bls_launch_interact(bls_ctx *ctx, const float *x, const float *emb, int from_slot, float *z, uint32_t b0, uint32_t bn,
+                        hipStream_t st);
 
 // ---- device helpers ----------------------------------------------------------------
 #ifdef __HIPCC__

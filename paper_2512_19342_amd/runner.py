@@ -148,11 +148,17 @@ class DenseModel:
             a = y[lo:hi]
         return y
 
-    def compute_ctr(self, x: torch.Tensor, emb: torch.Tensor, p_out: Optional[torch.Tensor] = None, stream=None,
+    def compute_ctr(self, x: torch.Tensor, emb, p_out: Optional[torch.Tensor] = None, stream=None,
                     rows: Optional[tuple] = None) -> torch.Tensor:
-        """The prediction [B, 1] from the bottom MLP's output and the completed lookup [B, T, D]."""
+        """The prediction [B, 1] from the bottom MLP's output and the completed lookup [B, T, D].
+        ``emb`` may instead be the number of the oldest iteration in flight: its completion is then
+        folded into the interaction (bls_unpack_interact; whole batch only)."""
         lo, hi = (0, self.B) if rows is None else (rows[0], rows[0] + rows[1])
-        self.ctx.bls_interact(x, emb, self.z, lo, hi - lo, stream)
+        if isinstance(emb, int):
+            assert rows is None
+            self.ctx.bls_unpack_interact(emb, x, self.z, stream)
+        else:
+            self.ctx.bls_interact(x, emb, self.z, lo, hi - lo, stream)
         a = self.z[lo:hi]
         for i, ((W, b), y) in enumerate(zip(self.top, self.top_act)):
             last = i == len(self.top) - 1
@@ -173,8 +179,8 @@ class BlsDlrm:
     before the one that would reuse its slot is issued (Fig. "bound": the process blocks on
     iteration 0 before it may start iteration k)."""
 
-    def __init__(self, pipe: Pipeline, model: DenseModel):
-        self.pipe, self.model = pipe, model
+    def __init__(self, pipe: Pipeline, model: DenseModel, fused_completion: bool = False):
+        self.pipe, self.model, self.fused_completion = pipe, model, fused_completion
         self.bound = pipe.w.k
         n = pipe.ctx.K + 1
         f32 = dict(dtype=torch.float32, device=pipe.dev)
@@ -184,9 +190,12 @@ class BlsDlrm:
 
     def _finish_tail(self, stream=None):
         it = self.unfinished.pop(0)
-        self.pipe.complete(it, self.emb, stream)
         p = torch.empty((self.pipe.w.B, 1), dtype=torch.float32, device=self.pipe.dev)
-        self.model.compute_ctr(self.x_list[it % len(self.x_list)], self.emb, p, stream)
+        if self.fused_completion:                               # no [B, T, D] copy-out: the interaction reads the slot
+            self.model.compute_ctr(self.x_list[it % len(self.x_list)], it, p, stream)
+        else:
+            self.pipe.complete(it, self.emb, stream)
+            self.model.compute_ctr(self.x_list[it % len(self.x_list)], self.emb, p, stream)
         return it, p
 
     def forward(self, dense, indices, offsets, nnz: int, last_batch: bool = False, stream=None):

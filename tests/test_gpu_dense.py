@@ -272,3 +272,51 @@ def test_per_rank_model_loop_matches_the_whole_batch_loop(k):
         for lo, n, part in got[it]:
             full[lo:lo + n] = part.cpu().numpy()
         assert np.array_equal(full.view(np.uint32), want[it].view(np.uint32)), it
+
+
+FOLDED = [
+    dict(P=3, T=5, D=32, B=50, part_kind=0, rows=[400, 64, 3000, 17, 256]),        # table-wise, P does not divide B
+    dict(P=4, T=6, D=24, B=37, part_kind=1, rows=[500, 64, 3000, 17, 256, 999]),   # row-wise: partial vectors summed on the way
+    dict(P=2, T=33, D=7, B=9, part_kind=1, rows=[40] * 33),                       # odd D (scalar copies), two tile rows
+    dict(P=8, T=64, D=128, B=64, part_kind=0, rows=[300] * 64),                   # the benchmark's shape
+]
+
+
+@pytest.mark.parametrize("spec", FOLDED, ids=lambda s: f"T{s['T']}-D{s['D']}-P{s['P']}-part{s['part_kind']}")
+def test_completion_folded_into_the_interaction(spec):
+    """bls_unpack_interact gives the bits of bls_unpack followed by bls_interact, retires the slot,
+    and keeps the ring's FIFO rule."""
+    import paper_2512_19342_amd as A
+    from paper_2512_19342_amd.runner import Pipeline
+    w = synth.custom("folded", k=2, values="gauss", bag=("uniform", 0, 9), index_dist=("zipf", 1.1), seed=57, **spec)
+    tabs = [synth.make_table(w, t).to(DEV) for t in range(w.T)]
+    batches = [synth.make_batch(w, it) for it in range(3)]
+    pipe = Pipeline(w, tabs, max(int(o[-1]) for _, o in batches))
+    c = pipe.ctx
+    Wz = w.D + w.T * (w.T + 1) // 2
+    xs = [torch.randn((w.B, w.D), device=DEV) for _ in range(3)]
+    want = []
+    for (ix, off), x in zip(batches, xs):                       # staged: copy-out, then interaction
+        out, z = pipe.new_out(), torch.empty((w.B, Wz), device=DEV)
+        it, _ = pipe.issue_fused(ix.to(DEV), off.to(DEV), int(off[-1]))
+        pipe.complete(it, out)
+        c.bls_interact(x, out, z)
+        want.append(z.cpu().numpy())
+    its = []
+    for ix, off in batches[:2]:                                 # two iterations in flight
+        its.append(pipe.issue_fused(ix.to(DEV), off.to(DEV), int(off[-1]))[0])
+    z = torch.full((w.B, Wz), float("nan"), device=DEV)
+    with pytest.raises(A.BlsError) as e:
+        c.bls_unpack_interact(its[1], xs[1], z)                 # not the oldest
+    assert e.value.code == A.BLS_EORDER
+    c.bls_unpack_interact(its[0], xs[0], z)
+    assert np.array_equal(z.cpu().numpy().view(np.uint32), want[0].view(np.uint32))
+    it2, _ = pipe.issue_fused(batches[2][0].to(DEV), batches[2][1].to(DEV), int(batches[2][1][-1]))   # the slot is free again
+    for it, k in ((its[1], 1), (it2, 2)):
+        c.bls_unpack_interact(it, xs[k], z)
+        assert np.array_equal(z.cpu().numpy().view(np.uint32), want[k].view(np.uint32)), k
+    assert c.bls_ring_state()[0] == c.bls_ring_state()[1]       # nothing left in flight
+    with pytest.raises(A.BlsError) as e:
+        c.bls_unpack_interact(it2 + 1, xs[0], z)
+    assert e.value.code == A.BLS_ERING_EMPTY
+    c.bls_check()
