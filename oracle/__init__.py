@@ -59,8 +59,8 @@ def _chk(fn: str, rc: int):
 class Case:
     """Shape of one problem: P ranks, T tables, vector length D, global batch B,
     partition kind (0 table-wise with ``owner[t]``, 1 row-wise block), rows per table,
-    storage dtype (0 fp32, 1 fp16, 2 row-quantised 8-bit: ``rowq_stride(D)`` bytes per row,
-    D codes, fp32 scale, fp32 bias, padding)."""
+    storage dtype (0 fp32, 1 fp16, 2 / 3 row-quantised 8-bit with integer / E4M3 codes:
+    ``rowq_stride(D)`` bytes per row, D codes, fp32 scale, fp32 bias, padding)."""
     P: int
     T: int
     D: int
@@ -90,9 +90,16 @@ def rowq_stride(D: int) -> int:
     return (D + 8 + 15) // 16 * 16
 
 
+def e4m3_table() -> np.ndarray:
+    """The 256 E4M3 codes decoded to float32."""
+    out = np.zeros(256, np.float32)
+    _chk("orc_e4m3_table", _load().orc_e4m3_table(_p(out)))
+    return out
+
+
 def _table_ptrs(case: Case, tables: List[np.ndarray]):
-    want = {0: np.float32, 1: np.float16, 2: np.uint8}[case.dtype]
-    width = rowq_stride(case.D) if case.dtype == 2 else case.D
+    want = {0: np.float32, 1: np.float16, 2: np.uint8, 3: np.uint8}[case.dtype]
+    width = rowq_stride(case.D) if case.dtype in (2, 3) else case.D
     keep = []
     for t, a in enumerate(tables):
         assert a.dtype == want and a.flags.c_contiguous and a.shape == (case.rows[t], width), (t, a.dtype, a.shape)

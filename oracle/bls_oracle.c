@@ -253,18 +253,34 @@ static float half_to_float(uint16_t h)
  * row's fp32 scale, its fp32 bias, padded to a multiple of 16. */
 static int64_t rowq_stride(int D) { return ((int64_t)D + 8 + 15) / 16 * 16; }
 
+/* 8-bit float E4M3 (1 sign, 4 exponent bits with bias 7, 3 mantissa bits; no infinities, the
+ * all-ones exponent-and-mantissa pattern is NaN, subnormals at exponent 0) -> binary32, exact. */
+static float e4m3_to_float(uint8_t v)
+{
+    int e = (v >> 3) & 15, m = v & 7;
+    float mag;
+    if (e == 15 && m == 7) { uint32_t nan = 0x7FC00000u | ((uint32_t)(v & 0x80u) << 24); float f; memcpy(&f, &nan, 4); return f; }
+    if (e == 0) mag = (float)m * 0.001953125f;                      /* m * 2^-9 */
+    else {
+        uint32_t bits = ((uint32_t)(e + 120) << 23) | ((uint32_t)m << 20);   /* 2^(e-7) * (1 + m/8) */
+        memcpy(&mag, &bits, 4);
+    }
+    return (v & 0x80u) ? -mag : mag;
+}
+
 /* Element (row, c) of a table as the fp32 number it stands for.  dtype 0: fp32; 1: binary16
- * (conversion exact); 2: 8-bit codes with one scale and one bias per row (an extension the
- * paper does not describe; reading: value = code * scale + bias evaluated in fp32, the
- * product rounded, then the sum rounded - the usual row-wise 8-bit embedding format). */
+ * (conversion exact); 2 and 3: 8-bit codes with one scale and one bias per row (an extension
+ * the paper does not describe; reading: value = code * scale + bias evaluated in fp32, the
+ * product rounded, then the sum rounded - the usual row-wise 8-bit embedding format), the code
+ * an unsigned integer (2) or an E4M3 float (3). */
 static float elem(const void *table, int dtype, int D, int64_t row, int c)
 {
-    if (dtype == 2) {
+    if (dtype == 2 || dtype == 3) {
         const uint8_t *p = (const uint8_t *)table + row * rowq_stride(D);
         float scale, bias, prod;
         memcpy(&scale, p + D, 4);
         memcpy(&bias, p + D + 4, 4);
-        prod = (float)p[c] * scale;
+        prod = (dtype == 2 ? (float)p[c] : e4m3_to_float(p[c])) * scale;
         return prod + bias;
     }
     return dtype == 1 ? half_to_float(((const uint16_t *)table)[row * D + c]) : ((const float *)table)[row * D + c];
@@ -275,7 +291,8 @@ static float elem(const void *table, int dtype, int D, int64_t row, int c)
  *   Out[b][t][c] = sum over l in bag (t,b) of W_t[indices[l]][c]
  * computed in double precision (out64, nullable) and with one fp32 accumulator that
  * starts at +0.0f and adds the terms in increasing l (out32, nullable).  tables[t] is
- * table t with global row numbering, dtype 0 = fp32, 1 = fp16, 2 = row-quantised 8-bit storage.
+ * table t with global row numbering, dtype 0 = fp32, 1 = fp16, 2 / 3 = row-quantised 8-bit storage
+ * (integer / E4M3 codes).
  */
 int orc_embbag_plain_ex(int T, int D, int64_t B, int dtype, const int64_t *rows, const void *const *tables,
                         const int64_t *indices, const int64_t *offsets, const float *weights, int mean,
@@ -651,5 +668,14 @@ int orc_interact(int64_t B, int T, int D, const double *x, const float *emb, con
                 ++at;
             }
     }
+    return ORC_OK;
+}
+
+
+/* The 256 E4M3 codes as binary32 (for pinning the decoder on its own). */
+int orc_e4m3_table(float *out256)
+{
+    int v;
+    for (v = 0; v < 256; ++v) out256[v] = e4m3_to_float((uint8_t)v);
     return ORC_OK;
 }

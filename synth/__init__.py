@@ -97,7 +97,7 @@ class Workload:
     D: int
     k: int
     B: int
-    table_dtype: str            # "fp32" | "fp16" | "u8rq" (8-bit codes, scale and bias per row)
+    table_dtype: str            # "fp32" | "fp16" | "u8rq" / "f8rq" (8-bit integer / E4M3 codes, scale and bias per row)
     part_kind: int              # 0 table-wise, 1 row-wise block
     rows: List[int]
     table_owner: List[int]      # table-wise only (zeros for row-wise)
@@ -118,23 +118,23 @@ class Workload:
     @property
     def dtype_code(self) -> int:
         """Storage code shared by the library's and the oracle's interfaces."""
-        return {"fp32": 0, "fp16": 1, "u8rq": 2}[self.table_dtype]
+        return {"fp32": 0, "fp16": 1, "u8rq": 2, "f8rq": 3}[self.table_dtype]
 
     @property
     def row_bytes(self) -> int:
         """Bytes from one table row to the next."""
-        if self.table_dtype == "u8rq":
+        if self.table_dtype in ("u8rq", "f8rq"):
             return rowq_stride(self.D)
         return self.D * (2 if self.table_dtype == "fp16" else 4)
 
     @property
     def row_width(self) -> int:
         """Second dimension of a table tensor (elements; bytes for row-quantised tables)."""
-        return rowq_stride(self.D) if self.table_dtype == "u8rq" else self.D
+        return rowq_stride(self.D) if self.table_dtype in ("u8rq", "f8rq") else self.D
 
     @property
     def torch_dtype(self):
-        return {"fp32": torch.float32, "fp16": torch.float16, "u8rq": torch.uint8}[self.table_dtype]
+        return {"fp32": torch.float32, "fp16": torch.float16, "u8rq": torch.uint8, "f8rq": torch.uint8}[self.table_dtype]
 
     def mean_bag(self) -> float:
         return float(self.bag[1]) if self.bag[0] == "fixed" else 0.5 * (self.bag[1] + self.bag[2])
@@ -271,7 +271,9 @@ def grid_rows(w: Workload, t: int, row_ids: torch.Tensor) -> torch.Tensor:
 def rowq_rows(w: Workload, t: int, row_ids: torch.Tensor) -> torch.Tensor:
     """Rows ``row_ids`` of row-quantised table t as stored: uint8 ``[n, rowq_stride(D)]``.
 
-    Codes are hash bytes.  "grid" values: scale in {2^-8, 2^-9, 2^-10} and bias a multiple of
+    Codes are hash bytes; for E4M3 codes ("f8rq") the two NaN patterns are replaced by the
+    largest finite code of the same sign, and "grid" tables keep the exponent field below 8
+    (|value| < 2, a multiple of 2^-9).  "grid" values: scale in {2^-8, 2^-9, 2^-10} and bias a multiple of
     2^-10 in [-1/16, 1/16), so every element and every sum of up to 2^10 of them is exact in
     fp32 in any order.  Otherwise scale and bias are arbitrary floats (scale in (1e-4, 1e-2),
     bias in (-0.5, 0.5)), which makes the roundings of the decoding and of the sum visible.
@@ -283,7 +285,12 @@ def rowq_rows(w: Workload, t: int, row_ids: torch.Tensor) -> torch.Tensor:
     ids = row_ids.to(torch.int64)
     out = torch.zeros((n, stride), dtype=torch.uint8, device=dev)
     cols = torch.arange(w.D, dtype=torch.int64, device=dev)
-    out[:, :w.D] = (hash_u64(key, ids[:, None] * w.D + cols[None, :]) & 255).to(torch.uint8)
+    codes = hash_u64(key, ids[:, None] * w.D + cols[None, :]) & 255
+    if w.table_dtype == "f8rq":
+        if w.values == "grid":
+            codes = codes & 0xBF                                  # exponent field 0..7
+        codes = torch.where((codes & 0x7F) == 0x7F, codes - 1, codes)
+    out[:, :w.D] = codes.to(torch.uint8)
     hk = stream_key(w.seed, _P_TABLE, t, 1)
     if w.values == "grid":
         h = hash_u64(hk, ids)
@@ -301,7 +308,7 @@ def make_table(w: Workload, t: int, device="cpu", chunk_rows: Optional[int] = No
     """Full table t in the workload's storage on ``device``: ``[rows_t, D]``, or uint8
     ``[rows_t, rowq_stride(D)]`` for row-quantised storage."""
     rows = w.rows[t]
-    if w.table_dtype == "u8rq":
+    if w.table_dtype in ("u8rq", "f8rq"):
         out = torch.empty((rows, rowq_stride(w.D)), dtype=torch.uint8, device=device)
         if chunk_rows is None:
             chunk_rows = max(1, (1 << 24) // w.D)
@@ -326,7 +333,7 @@ def make_table(w: Workload, t: int, device="cpu", chunk_rows: Optional[int] = No
 def table_rows(w: Workload, t: int, row_ids: torch.Tensor, table: Optional[torch.Tensor] = None) -> torch.Tensor:
     """Selected rows of table t as float32 on the CPU (recomputed for grid tables).
     Not for row-quantised tables, whose stored rows come from ``rowq_rows``."""
-    assert w.table_dtype != "u8rq"
+    assert w.table_dtype not in ("u8rq", "f8rq")
     if w.values == "grid":
         return grid_rows(w, t, row_ids.cpu()).to(w.torch_dtype).to(torch.float32)
     if table is None:

@@ -55,6 +55,9 @@ MUTATIONS = {
                                        "for (j = 0; j < T; ++j)\n            for (i = j + 1; i <= T; ++i) {\n                const float *ei"),
     "interaction keeps the diagonal": ("for (j = 0; j < i; ++j) {\n                const float *ei", "for (j = 1; j <= i; ++j) {\n                const float *ei"),
     "interaction pairs the wrong embedding": ("(double)emb[(b * T + (j - 1)) * D + c]", "(double)emb[(b * T + j) * D + c]"),
+    "e4m3 exponent bias": ("uint32_t bits = ((uint32_t)(e + 120) << 23) | ((uint32_t)m << 20);", "uint32_t bits = ((uint32_t)(e + 119) << 23) | ((uint32_t)m << 20);"),
+    "e4m3 subnormals flushed": ("if (e == 0) mag = (float)m * 0.001953125f;", "if (e == 0) mag = 0.0f;"),
+    "e4m3 sign dropped": ("return (v & 0x80u) ? -mag : mag;", "return mag;"),
     "half subnormals flushed": ("if (m == 0) bits = sign;\n        else {", "if (m >= 0) bits = sign;\n        else {"),
 }
 
@@ -76,6 +79,8 @@ PINS = [
     lambda: pins.test_rowq_stride_and_padding(),
     lambda: pins.test_rowq_decoding_rounds_twice_in_fp32(),
     lambda: pins.test_rowq_pipeline_against_decoded_fp32_tables(1),
+    lambda: pins.test_e4m3_decoder_all_codes(),
+    lambda: pins.test_f8rq_worked_example_and_decoded_tables(),
     lambda: pins.test_mlp_layer_brute_force_and_closed_forms(),
     lambda: pins.test_mlp_layer_against_torch_linear(2),
     lambda: pins.test_interact_brute_force_order_and_torch(),

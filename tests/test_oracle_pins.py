@@ -770,3 +770,57 @@ def test_dense_error_bounds_hold_for_an_fp32_implementation():
     assert np.all(np.abs(f32_layer(z.astype(np.float32), *Lt[0]) - oracle.mlp_layer(z.astype(np.float32), Lt[0][0], Lt[0][1], 1)[0]) <= e1)
     assert e1.max() < 2e-5 * max(1.0, np.abs(y1).max())
     assert p.shape == (w.B, 1) and np.all((p > 0) & (p < 1)) and p.std() > 1e-3
+
+
+# ----------------------------------------------------------------------------- E4M3 codes
+
+def test_e4m3_decoder_all_codes():
+    """All 256 codes against torch's float8_e4m3fn conversion and against the format's definition
+    (sign, 4 exponent bits with bias 7, 3 mantissa bits, subnormals, NaN only at 0x7f / 0xff)."""
+    got = oracle.e4m3_table()
+    ref = torch.arange(256, dtype=torch.uint8).view(torch.float8_e4m3fn).to(torch.float32).numpy()
+    nan = np.isnan(ref)
+    assert list(np.flatnonzero(nan)) == [0x7F, 0xFF] and np.array_equal(np.isnan(got), nan)
+    assert np.array_equal(got[~nan].view(np.uint32), ref[~nan].view(np.uint32))
+    for v in range(256):
+        e, m, sgn = (v >> 3) & 15, v & 7, -1.0 if v & 0x80 else 1.0
+        if e == 15 and m == 7:
+            continue
+        want = sgn * (m * 2.0 ** -9 if e == 0 else (1 + m / 8) * 2.0 ** (e - 7))
+        assert got[v] == want and np.signbit(got[v]) == bool(v & 0x80), v
+    assert got[0x7E] == 448.0 and got[0x08] == 2.0 ** -6 and got[0x01] == 2.0 ** -9
+
+
+def test_f8rq_worked_example_and_decoded_tables():
+    """A row written by hand, and the path over an E4M3-coded table against the path over the fp32
+    table of its decoded values (decoded here through torch's float8 type and numpy float32)."""
+    D = 4
+    tab = _rowq_table(D, [([0x38, 0x40, 0xB8, 0x01], 2.0, 1.0),      # codes 1, 2, -1, 2^-9 -> 3, 5, -1, 1 + 2^-8
+                          ([0x30, 0x34, 0x00, 0x7E], 4.0, 0.0)])     # 0.5, 0.75, 0, 448 -> 2, 3, 0, 1792
+    case = oracle.Case(1, 1, D, 2, 0, [2], [0], 3)
+    o64, o32 = oracle.embbag_plain(case, [tab], np.array([0, 1, 1], np.int64), np.array([0, 1, 3], np.int64))
+    want = np.array([[[3.0, 5.0, -1.0, 1.0 + 2.0 ** -8]], [[4.0, 6.0, 0.0, 3584.0]]])
+    assert np.array_equal(o64, want) and np.array_equal(o32, want.astype(np.float32))
+
+    w = synth.custom("f8", P=3, T=3, D=24, B=11, k=1, part_kind=1, rows=[30, 7, 64],
+                     table_dtype="f8rq", values="gauss", seed=59, bag=("uniform", 0, 6))
+    tabs = np_tables(w)
+    dec = []
+    for t in tabs:
+        codes = torch.from_numpy(t[:, :w.D].copy()).view(torch.float8_e4m3fn).to(torch.float32).numpy()
+        assert np.all(np.isfinite(codes))
+        s = t[:, w.D:w.D + 4].copy().view(np.float32)
+        b = t[:, w.D + 4:w.D + 8].copy().view(np.float32)
+        dec.append(np.ascontiguousarray((codes * s).astype(np.float32) + b))
+    ix, off = synth.make_batch(w, 0)
+    q = oracle.pipeline(case_of(w), tabs, ix.numpy(), off.numpy())
+    f = oracle.pipeline(oracle.Case(w.P, w.T, w.D, w.B, w.part_kind, w.rows, w.table_owner, 0), dec, ix.numpy(), off.numpy())
+    for key in ("Y", "S", "R", "Out"):
+        assert np.array_equal(q[key], f[key]), key
+    # grid tables are exact
+    wg = synth.custom("f8", P=2, T=2, D=16, B=20, k=0, part_kind=0, rows=[50, 200], table_dtype="f8rq", values="grid",
+                      seed=61, bag=("uniform", 0, 40))
+    tg = np_tables(wg)
+    ix, off = synth.make_batch(wg, 0)
+    o64, o32 = oracle.embbag_plain(case_of(wg), tg, ix.numpy(), off.numpy())
+    assert np.array_equal(o64, o32.astype(np.float64)) and np.abs(o64).max() > 0.1
