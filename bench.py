@@ -351,7 +351,7 @@ def main() -> int:
                     help="with --lag-demo: every rank also runs the bottom MLP, the interaction and the top MLP of its mini-batch")
     ap.add_argument("--max-delay-us", type=int, default=1000)
     ap.add_argument("--bounds", type=int, nargs="+", default=[0, 1, 2, 4, 8])
-    ap.add_argument("--table-dtype", default=None, choices=[None, "fp32", "fp16", "u8rq"],
+    ap.add_argument("--table-dtype", default=None, choices=[None, "fp32", "fp16", "u8rq", "f8rq"],
                     help="variant: store the tables this way instead of the workload's own dtype")
     ap.add_argument("--dense", action="store_true", help="with --timed-only: also time the dense model around the lookup")
     ap.add_argument("--rows-cap", type=int, default=0, help="experiment: no table has more rows than this")
@@ -519,7 +519,8 @@ def main() -> int:
         "value": lookups / dt, "unit": "lookups/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": dt / args.steps * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": {"fp32": "f32", "fp16": "f16 storage, f32 accumulate",
-                  "u8rq": "u8 row-quantised storage, f32 accumulate"}[w.table_dtype], "data": "synthetic",
+                  "u8rq": "u8 row-quantised storage, f32 accumulate",
+                  "f8rq": "e4m3 row-quantised storage, f32 accumulate"}[w.table_dtype], "data": "synthetic",
         "config": {"workload": WORKLOAD_TEXT[args.config] + ("" if args.size == "full" else " [reduced twin]")
                    + (" [uniform-index control]" if args.index_dist else "")
                    + (f" [every bag {args.bag_fixed} lookups]" if args.bag_fixed else "")

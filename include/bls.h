@@ -67,14 +67,16 @@ enum {
  * to a multiple of 16 bytes: D unsigned 8-bit codes, the row's fp32 scale, its fp32 bias,
  * padding (ignored).  Element c of the row stands for the fp32 number
  * fl(fl((float)code[c] * scale) + bias) - product and sum rounded separately, no fused
- * multiply-add - and the bag sum adds these numbers like any other fp32 row. */
-enum { BLS_FP32 = 0, BLS_FP16 = 1, BLS_U8_ROWQ = 2 };
+ * multiply-add - and the bag sum adds these numbers like any other fp32 row.
+ * BLS_F8_ROWQ: the same row layout with 8-bit float codes (E4M3: 1 sign, 4 exponent bits with
+ * bias 7, 3 mantissa bits, no infinities; NaN codes give NaN) in place of the integers. */
+enum { BLS_FP32 = 0, BLS_FP16 = 1, BLS_U8_ROWQ = 2, BLS_F8_ROWQ = 3 };
 enum { BLS_TABLE_WISE = 0, BLS_ROW_WISE = 1 };
 
 typedef struct bls_config {
     int32_t P, T, D, k;          /* 1 <= P <= 64; k >= 0 is the paper's bound, K = max(k,1) slots   */
     int64_t B;                   /* global batch, B >= P                                             */
-    int32_t table_dtype;         /* BLS_FP32 | BLS_FP16 | BLS_U8_ROWQ                                */
+    int32_t table_dtype;         /* BLS_FP32 | BLS_FP16 | BLS_U8_ROWQ | BLS_F8_ROWQ                  */
     int32_t part_kind;           /* BLS_TABLE_WISE | BLS_ROW_WISE                                    */
     const int64_t *rows;         /* host [T], rows per table (global), each >= 1                     */
     const int32_t *table_owner;  /* host [T], owner rank of each table; read for table-wise only     */
@@ -86,7 +88,7 @@ int bls_create(const bls_config *cfg, bls_ctx **out);
 int bls_destroy(bls_ctx *ctx);
 
 /* Hand the library one table shard: row-major [rows_in_shard][D] in the configured
- * storage dtype ([rows_in_shard][D + 8 rounded up to 16] bytes for BLS_U8_ROWQ), device
+ * storage dtype ([rows_in_shard][D + 8 rounded up to 16] bytes for the row-quantised ones), device
  * memory, 16-byte aligned, borrowed until bls_destroy.
  * Table-wise: rank must be table_owner[t] and rows_in_shard = rows[t].  Row-wise: one
  * call per (t, rank), rows_in_shard = number of rows of table t that fall in the

@@ -15,7 +15,7 @@ import torch
 
 BLS_OK, BLS_EINVAL, BLS_ERANGE, BLS_ENOSPC = 0, -1, -2, -3
 BLS_ERING_FULL, BLS_ERING_EMPTY, BLS_EORDER, BLS_EHIP = -4, -5, -6, -7
-BLS_FP32, BLS_FP16, BLS_U8_ROWQ = 0, 1, 2
+BLS_FP32, BLS_FP16, BLS_U8_ROWQ, BLS_F8_ROWQ = 0, 1, 2, 3
 BLS_ACT_NONE, BLS_ACT_RELU, BLS_ACT_SIGMOID = 0, 1, 2
 BLS_TABLE_WISE, BLS_ROW_WISE = 0, 1
 

@@ -32,7 +32,9 @@ extern "C" int bls_create(const bls_config *cfg, bls_ctx **out)
     *out = nullptr;
     if (cfg->P < 1 || cfg->P > 64 || cfg->T < 1 || cfg->D < 1 || cfg->k < 0) return BLS_EINVAL;
     if (cfg->B < cfg->P || cfg->B > 0x7fffffffLL) return BLS_EINVAL;
-    if (cfg->table_dtype != BLS_FP32 && cfg->table_dtype != BLS_FP16 && cfg->table_dtype != BLS_U8_ROWQ) return BLS_EINVAL;
+    if (cfg->table_dtype != BLS_FP32 && cfg->table_dtype != BLS_FP16 && cfg->table_dtype != BLS_U8_ROWQ &&
+        cfg->table_dtype != BLS_F8_ROWQ)
+        return BLS_EINVAL;
     if (cfg->part_kind != BLS_TABLE_WISE && cfg->part_kind != BLS_ROW_WISE) return BLS_EINVAL;
     if (!cfg->rows || (cfg->part_kind == BLS_TABLE_WISE && !cfg->table_owner)) return BLS_EINVAL;
     const int P = cfg->P, T = cfg->T;

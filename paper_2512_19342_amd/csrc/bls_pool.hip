@@ -39,13 +39,14 @@ typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 typedef u32x2 u32x2_a4 __attribute__((aligned(4)));   // a row's scale and bias sit on a 4-byte boundary
 
 // Bytes of a row that hold its elements, and bytes from one row to the next.
+__host__ __device__ constexpr bool is_rowq(int dtype) { return dtype == BLS_U8_ROWQ || dtype == BLS_F8_ROWQ; }
 __host__ __device__ __forceinline__ int64_t payload_bytes(int dtype, int D)
 {
-    return dtype == BLS_U8_ROWQ ? (int64_t)D : (int64_t)D * (dtype == BLS_FP16 ? 2 : 4);
+    return is_rowq(dtype) ? (int64_t)D : (int64_t)D * (dtype == BLS_FP16 ? 2 : 4);
 }
 __host__ __device__ __forceinline__ int64_t stride_bytes(int dtype, int D)
 {
-    return dtype == BLS_U8_ROWQ ? ((int64_t)D + 8 + 15) / 16 * 16 : payload_bytes(dtype, D);
+    return is_rowq(dtype) ? ((int64_t)D + 8 + 15) / 16 * 16 : payload_bytes(dtype, D);
 }
 
 // Per-lane accumulator: VB bytes of table storage per lane and row, NV values in them.
@@ -54,8 +55,8 @@ __host__ __device__ __forceinline__ int64_t stride_bytes(int dtype, int D)
 // and the sum each rounded to fp32.
 template <int DT, int VB> struct Acc {
     static constexpr int NW = VB / 4;                              // 32-bit words loaded per row
-    static constexpr int NV = DT == BLS_U8_ROWQ ? VB : DT == BLS_FP16 ? VB / 2 : VB / 4;   // fp32 values accumulated
-    static constexpr int NX = DT == BLS_U8_ROWQ ? 2 : 0;           // scale, bias
+    static constexpr int NV = is_rowq(DT) ? VB : DT == BLS_FP16 ? VB / 2 : VB / 4;   // fp32 values accumulated
+    static constexpr int NX = is_rowq(DT) ? 2 : 0;                  // scale, bias
     struct Raw { uint32_t w[NW + NX]; };
     float a[NV];
 
@@ -91,19 +92,25 @@ template <int DT, int VB> struct Acc {
         }
         return r;
     }
-    static __device__ __forceinline__ float decode(uint32_t word, int k, float scale, float bias)
+    // byte k of a word of codes as the number the row format gives it: an unsigned integer, or an
+    // E4M3 float (v_cvt_f32_fp8, exact), times the scale, plus the bias
+    template <int K>
+    static __device__ __forceinline__ float decode(uint32_t word, float scale, float bias)
     {
-        const float prod = (float)((word >> (8 * k)) & 0xffu) * scale;
+        float code;
+        if constexpr (DT == BLS_F8_ROWQ) code = __builtin_amdgcn_cvt_f32_fp8((int)word, K);
+        else code = (float)((word >> (8 * K)) & 0xffu);
+        const float prod = code * scale;
         return prod + bias;
     }
     __device__ __forceinline__ void add(const Raw &r)
     {
 #pragma unroll
         for (int i = 0; i < NW; ++i) {
-            if constexpr (DT == BLS_U8_ROWQ) {
+            if constexpr (is_rowq(DT)) {
                 const float sc = __uint_as_float(r.w[NW]), bi = __uint_as_float(r.w[NW + 1]);
-#pragma unroll
-                for (int k = 0; k < 4; ++k) a[4 * i + k] += decode(r.w[i], k, sc, bi);
+                a[4 * i + 0] += decode<0>(r.w[i], sc, bi); a[4 * i + 1] += decode<1>(r.w[i], sc, bi);
+                a[4 * i + 2] += decode<2>(r.w[i], sc, bi); a[4 * i + 3] += decode<3>(r.w[i], sc, bi);
             } else if constexpr (DT == BLS_FP16) { a[2 * i] += half_lo(r.w[i]); a[2 * i + 1] += half_hi(r.w[i]); }
             else a[i] += __uint_as_float(r.w[i]);
         }
@@ -113,13 +120,11 @@ template <int DT, int VB> struct Acc {
     {
 #pragma unroll
         for (int i = 0; i < NW; ++i) {
-            if constexpr (DT == BLS_U8_ROWQ) {
+            if constexpr (is_rowq(DT)) {
                 const float sc = __uint_as_float(r.w[NW]), bi = __uint_as_float(r.w[NW + 1]);
-#pragma unroll
-                for (int k = 0; k < 4; ++k) {
-                    const float term = w * decode(r.w[i], k, sc, bi);
-                    a[4 * i + k] += term;
-                }
+                const float t0 = w * decode<0>(r.w[i], sc, bi), t1 = w * decode<1>(r.w[i], sc, bi);
+                const float t2 = w * decode<2>(r.w[i], sc, bi), t3 = w * decode<3>(r.w[i], sc, bi);
+                a[4 * i + 0] += t0; a[4 * i + 1] += t1; a[4 * i + 2] += t2; a[4 * i + 3] += t3;
             } else if constexpr (DT == BLS_FP16) {
                 const float p0 = w * half_lo(r.w[i]), p1 = w * half_hi(r.w[i]);
                 a[2 * i] += p0; a[2 * i + 1] += p1;
@@ -410,12 +415,13 @@ __global__ __launch_bounds__(kThreads) void pool_rows_generic(DevDesc dd, const 
             const int64_t r = ridx[j];
             if (r < 0 || r >= shard_rows) { if (c == 0) flag_error(dd); continue; }
             float x;
-            if constexpr (DT == BLS_U8_ROWQ) {
+            if constexpr (is_rowq(DT)) {
                 const unsigned char *row = (const unsigned char *)base + r * stride_bytes(DT, dd.D);
                 float scale, bias;                              // any D: no alignment to rely on
                 __builtin_memcpy(&scale, row + dd.D, 4);
                 __builtin_memcpy(&bias, row + dd.D + 4, 4);
-                const float prod = (float)row[c] * scale;
+                const float code = DT == BLS_F8_ROWQ ? __builtin_amdgcn_cvt_f32_fp8((int)row[c], 0) : (float)row[c];
+                const float prod = code * scale;
                 x = prod + bias;
             } else {
                 const int64_t e = r * dd.D + c;
@@ -514,12 +520,14 @@ int bls_launch_pool(bls_ctx *ctx, const int64_t *ridx, const float *rw, const in
         int lanes = 1;
         while ((int64_t)lanes * vb < row_bytes) lanes <<= 1;
         done = ctx->dtype == BLS_U8_ROWQ ? dispatch_rows<BLS_U8_ROWQ>(ctx, vb, lanes, ridx, rw, segoff, nnz, Y, to_slot, q0, qn, st)
+             : ctx->dtype == BLS_F8_ROWQ ? dispatch_rows<BLS_F8_ROWQ>(ctx, vb, lanes, ridx, rw, segoff, nnz, Y, to_slot, q0, qn, st)
              : ctx->dtype == BLS_FP16  ? dispatch_rows<BLS_FP16>(ctx, vb, lanes, ridx, rw, segoff, nnz, Y, to_slot, q0, qn, st)
                                        : dispatch_rows<BLS_FP32>(ctx, vb, lanes, ridx, rw, segoff, nnz, Y, to_slot, q0, qn, st);
     }
     if (!done) {
         dim3 grid((unsigned)((ctx->B + kThreads / 64 - 1) / (kThreads / 64)), qn);
         if (ctx->dtype == BLS_U8_ROWQ) pool_rows_generic<BLS_U8_ROWQ><<<grid, kThreads, 0, st>>>(ctx->desc, ridx, rw, segoff, nnz, Y, to_slot, q0);
+        else if (ctx->dtype == BLS_F8_ROWQ) pool_rows_generic<BLS_F8_ROWQ><<<grid, kThreads, 0, st>>>(ctx->desc, ridx, rw, segoff, nnz, Y, to_slot, q0);
         else if (ctx->dtype == BLS_FP16) pool_rows_generic<BLS_FP16><<<grid, kThreads, 0, st>>>(ctx->desc, ridx, rw, segoff, nnz, Y, to_slot, q0);
         else pool_rows_generic<BLS_FP32><<<grid, kThreads, 0, st>>>(ctx->desc, ridx, rw, segoff, nnz, Y, to_slot, q0);
     }

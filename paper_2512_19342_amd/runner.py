@@ -13,7 +13,7 @@ from . import bls
 class Pipeline:
     """Device buffers + one Context for a fixed problem shape.
 
-    ``w`` is any object with P, T, D, k, B, rows, table_owner, table_dtype ("fp32" / "fp16" / "u8rq")
+    ``w`` is any object with P, T, D, k, B, rows, table_owner, table_dtype ("fp32" / "fp16" / "u8rq" / "f8rq")
     and part_kind; ``tables`` are the T full tables (global row numbering) on the GPU.
     Row-wise shards are views into those tables.
     """
@@ -22,8 +22,8 @@ class Pipeline:
         dev = tables[0].device
         assert dev.type == "cuda", "the hot path runs on the GPU only"
         self.w, self.dev, self.max_nnz = w, dev, int(max_nnz)
-        dt = {"fp32": bls.BLS_FP32, "fp16": bls.BLS_FP16, "u8rq": bls.BLS_U8_ROWQ}[w.table_dtype]
-        width = (w.D + 8 + 15) // 16 * 16 if dt == bls.BLS_U8_ROWQ else w.D   # bytes per row-quantised row
+        dt = {"fp32": bls.BLS_FP32, "fp16": bls.BLS_FP16, "u8rq": bls.BLS_U8_ROWQ, "f8rq": bls.BLS_F8_ROWQ}[w.table_dtype]
+        width = (w.D + 8 + 15) // 16 * 16 if dt in (bls.BLS_U8_ROWQ, bls.BLS_F8_ROWQ) else w.D   # bytes per row-quantised row
         self.ctx = bls.Context(w.P, w.T, w.D, w.k, w.B, w.rows, w.table_owner, dt, w.part_kind)
         c = self.ctx
         for t, tab in enumerate(tables):

@@ -40,7 +40,7 @@ def test_configuration_is_validated(B):
     ok = dict(P=2, T=3, D=8, k=1, B=4, rows=[5, 6, 7], table_owner=[0, 1, 0])
     B.Context(**ok).bls_destroy()
     bad = [dict(P=0), dict(P=65), dict(T=0, rows=[], table_owner=[]), dict(D=0), dict(k=-1), dict(B=1),
-           dict(B=2 ** 31), dict(rows=[5, 0, 7]), dict(table_owner=[0, 2, 0]), dict(table_dtype=3), dict(part_kind=3)]
+           dict(B=2 ** 31), dict(rows=[5, 0, 7]), dict(table_owner=[0, 2, 0]), dict(table_dtype=4), dict(part_kind=3)]
     for change in bad:
         with pytest.raises(B.BlsError):
             B.Context(**{**ok, **change})

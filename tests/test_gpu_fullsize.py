@@ -35,18 +35,18 @@ def bag_sum32(w, t, idx):
     """fp32 sum, in order, of rows idx of table t: the rows are regenerated on the host and handed
     to the oracle (as a little table of their own when the storage is row-quantised)."""
     ids = torch.from_numpy(np.ascontiguousarray(idx))
-    if w.table_dtype == "u8rq":
+    if w.table_dtype in ("u8rq", "f8rq"):
         n = len(idx)
         if n == 0:
             return np.zeros(w.D, np.float32)
-        mini = oracle.Case(1, 1, w.D, 1, 0, [n], [0], 2)
+        mini = oracle.Case(1, 1, w.D, 1, 0, [n], [0], w.dtype_code)
         _, o32 = oracle.embbag_plain(mini, [synth.rowq_rows(w, t, ids).numpy()], np.arange(n, dtype=np.int64),
                                      np.array([0, n], np.int64))
         return o32.reshape(w.D)
     return oracle.bag_sum(synth.table_rows(w, t, ids).numpy().reshape(-1, w.D))[0]
 
 
-@pytest.mark.parametrize("cfg,storage", [(3, None), (4, None), (5, None), (4, "u8rq")])
+@pytest.mark.parametrize("cfg,storage", [(3, None), (4, None), (5, None), (4, "u8rq"), (4, "f8rq")])
 def test_full_size(cfg, storage):
     from paper_2512_19342_amd.runner import Pipeline
     w = synth.workload(cfg, "full")

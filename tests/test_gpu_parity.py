@@ -16,7 +16,7 @@ import synth
 
 pytestmark = pytest.mark.gpu
 
-TOL = {"fp32": 1e-6, "fp16": 1e-3, "u8rq": 1e-6}
+TOL = {"fp32": 1e-6, "fp16": 1e-3, "u8rq": 1e-6, "f8rq": 1e-6}
 
 
 def case_of(w):
@@ -130,10 +130,12 @@ ROWQ = [
 
 @pytest.mark.parametrize("spec", ROWQ, ids=lambda s: f"D{s['D']}-P{s['P']}-part{s['part_kind']}")
 @pytest.mark.parametrize("values", ["gauss", "grid"])
-def test_row_quantised_tables(spec, values):
-    """8-bit codes with a scale and a bias per row: decoding (two fp32 roundings) and the ordered
-    sum must give the oracle's bits for every row length the kernels treat differently."""
-    w = synth.custom("rowq", k=2, values=values, table_dtype="u8rq", seed=37, index_dist=("zipf", 1.05), **spec)
+@pytest.mark.parametrize("storage", ["u8rq", "f8rq"])
+def test_row_quantised_tables(spec, values, storage):
+    """8-bit codes (integers or E4M3 floats) with a scale and a bias per row: decoding (two fp32
+    roundings) and the ordered sum must give the oracle's bits for every row length the kernels
+    treat differently."""
+    w = synth.custom("rowq", k=2, values=values, table_dtype=storage, seed=37, index_dist=("zipf", 1.05), **spec)
     tabs = [synth.make_table(w, t) for t in range(w.T)]
     batches = [synth.make_batch(w, it) for it in range(2)]
     got, _ = run_gpu(w, tabs, batches)
@@ -142,6 +144,26 @@ def test_row_quantised_tables(spec, values):
         o64, _ = oracle.embbag_plain(case_of(w), [t.numpy() for t in tabs], batches[0][0].numpy(),
                                      batches[0][1].numpy(), want32=False)
         assert np.array_equal(got[0]["Out"].astype(np.float64), o64)
+
+
+def test_e4m3_codes_all_values_on_the_device():
+    """Every finite E4M3 code through the pooling kernel with scale 1 and bias 0 (bags of one row):
+    the hardware conversion must agree with the oracle's decoder, subnormals and signed zeros included."""
+    D = 256
+    codes = np.arange(256, dtype=np.uint8)
+    codes[[0x7F, 0xFF]] = [0x7E, 0xFE]                          # the two NaN patterns are left out
+    stride = synth.rowq_stride(D)
+    tab = np.zeros((3, stride), np.uint8)
+    for r, perm in enumerate((codes, codes[::-1], np.roll(codes, 37))):
+        tab[r, :D] = perm
+        tab[r, D:D + 8] = np.array([1.0, 0.0], np.float32).view(np.uint8)
+    w = synth.custom("codes", P=1, T=1, D=D, B=3, k=1, part_kind=0, rows=[3], table_dtype="f8rq", bag=("fixed", 1))
+    ix, off = torch.tensor([0, 1, 2]), torch.tensor([0, 1, 2, 3])
+    got, _ = run_gpu(w, [torch.from_numpy(tab)], [(ix, off)])
+    ref = oracle.pipeline(case_of(w), [tab], ix.numpy(), off.numpy())
+    assert np.array_equal(bits(got[0]["Out"]), bits(ref["Out"]))
+    want = oracle.e4m3_table()[codes] + np.float32(0.0)         # the sum starts from +0: -0 becomes +0
+    assert np.array_equal(got[0]["Out"][0, 0].view(np.uint32), want.view(np.uint32))
 
 
 def test_all_bags_empty():
@@ -356,8 +378,8 @@ WEIGHTED = [synth.workload(2), synth.workload(3, "small"), synth.workload(4, "sm
             synth.workload(6, "small")] + [
     synth.custom("edge", k=1, values="gauss", table_dtype=dt, seed=31, index_dist=("zipf", 1.1), **EDGE[i])
     for i in (1, 2, 4, 5, 6, 7, 8, 10) for dt in ("fp32", "fp16")] + [
-    synth.custom("edge", k=1, values="gauss", table_dtype="u8rq", seed=31, index_dist=("zipf", 1.1), **EDGE[i])
-    for i in (4, 6, 7, 9, 10)]
+    synth.custom("edge", k=1, values="gauss", table_dtype=dt, seed=31, index_dist=("zipf", 1.1), **EDGE[i])
+    for i in (4, 6, 7, 9, 10) for dt in ("u8rq", "f8rq")]
 
 
 @pytest.mark.parametrize("w", WEIGHTED, ids=lambda w: f"{w.name}-{w.table_dtype}-D{w.D}-P{w.P}-part{w.part_kind}")
