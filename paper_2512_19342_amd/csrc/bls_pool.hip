@@ -26,6 +26,12 @@ namespace {
 constexpr int kThreads = 256;
 constexpr uint32_t kBadRow = 0xffffffffu;
 constexpr int kRowsInFlight = 8;   // U: independent row loads issued per lane before the first add
+#ifndef BLS_POOL_UQ
+#define BLS_POOL_UQ 4
+#endif
+// row-quantised rows are four times shorter, so a load instruction carries four times as many rows:
+// fewer per lane keep as many rows in flight with fewer registers (more wavefronts per SIMD)
+constexpr int kRowsInFlightQuantised = BLS_POOL_UQ;
 
 __device__ __forceinline__ void flag_error(const DevDesc &dd) { atomicOr(dd.err, 1); }
 
@@ -497,7 +503,7 @@ bool dispatch_rows(const bls_ctx *ctx, int vb, int lanes, const int64_t *ridx, c
                    const int64_t *segoff, int64_t nnz, float *Y, int to_slot, int q0, int qn, hipStream_t st)
 {
     switch (vb) {
-    case 16: return dispatch_lanes<DT, 16, kRowsInFlight>(ctx, lanes, ridx, rw, segoff, nnz, Y, to_slot, q0, qn, st);
+    case 16: return dispatch_lanes<DT, 16, (is_rowq(DT) ? kRowsInFlightQuantised : kRowsInFlight)>(ctx, lanes, ridx, rw, segoff, nnz, Y, to_slot, q0, qn, st);
     case 8: return dispatch_lanes<DT, 8, kRowsInFlight>(ctx, lanes, ridx, rw, segoff, nnz, Y, to_slot, q0, qn, st);
     case 4: return dispatch_lanes<DT, 4, kRowsInFlight>(ctx, lanes, ridx, rw, segoff, nnz, Y, to_slot, q0, qn, st);
     }
