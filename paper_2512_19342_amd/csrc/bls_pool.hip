@@ -25,7 +25,10 @@ namespace {
 
 constexpr int kThreads = 256;
 constexpr uint32_t kBadRow = 0xffffffffu;
-constexpr int kRowsInFlight = 8;   // U: independent row loads issued per lane before the first add
+#ifndef BLS_POOL_U
+#define BLS_POOL_U 8
+#endif
+constexpr int kRowsInFlight = BLS_POOL_U;   // U: independent row loads issued per lane before the first add
 #ifndef BLS_POOL_UQ
 #define BLS_POOL_UQ 4
 #endif
