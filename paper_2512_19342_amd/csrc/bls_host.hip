@@ -1,6 +1,7 @@
 // Host side of libbls: context, configuration checks, sizes, descriptor upload, the ring
-// of receive buffers and the C entry points.  Kernels live in bls_plan.hip, bls_pool.hip
-// and bls_permute.hip.
+// of receive buffers and the C entry points.  Kernels live in bls_plan.hip, bls_pool.hip,
+// bls_permute.hip and bls_dense.hip.  Nothing here throws across the C boundary: the two places
+// that allocate host containers catch and report BLS_EINVAL.
 #include <algorithm>
 #include <cstdio>
 #include <cstring>
@@ -46,6 +47,7 @@ extern "C" int bls_create(const bls_config *cfg, bls_ctx **out)
     }
     bls_ctx *c = new (std::nothrow) bls_ctx();
     if (!c) return BLS_EINVAL;
+    try {
     c->P = P; c->T = T; c->D = cfg->D; c->k = cfg->k; c->K = std::max(cfg->k, 1); c->F = F; c->Q = F * T;
     c->dtype = cfg->table_dtype; c->part_kind = cfg->part_kind; c->B = cfg->B;
     c->rows.assign(cfg->rows, cfg->rows + T);
@@ -80,6 +82,10 @@ extern "C" int bls_create(const bls_config *cfg, bls_ctx **out)
     c->nseg = c->nvec = (int64_t)c->Q * c->B;
     c->slot_bytes = (size_t)c->nvec * c->D * sizeof(float);
     c->ring.resize(c->K);
+    } catch (...) {                                            // out of host memory
+        delete c;
+        return BLS_EINVAL;
+    }
     *out = c;
     return BLS_OK;
 }
@@ -185,11 +191,16 @@ int bls_commit(bls_ctx *ctx)
     if (!ctx->dirty && ctx->blob) return BLS_OK;
 
     BlobWriter w;
-    std::vector<int32_t> errflag(4, 0);
-    const size_t o_err = w.put(errflag);
-    const size_t o_first = w.put(ctx->first), o_nloc = w.put(ctx->n_loc), o_nsum = w.put(ctx->nsum);
-    const size_t o_rows = w.put(ctx->rows), o_rps = w.put(ctx->rps), o_tq = w.put(ctx->t_q);
-    const size_t o_qt = w.put(ctx->q_t), o_qd = w.put(ctx->q_d), o_qbase = w.put(ctx->q_base), o_qrows = w.put(ctx->q_rows);
+    size_t o_err, o_first, o_nloc, o_nsum, o_rows, o_rps, o_tq, o_qt, o_qd, o_qbase, o_qrows;
+    try {
+        std::vector<int32_t> errflag(4, 0);
+        o_err = w.put(errflag);
+        o_first = w.put(ctx->first); o_nloc = w.put(ctx->n_loc); o_nsum = w.put(ctx->nsum);
+        o_rows = w.put(ctx->rows); o_rps = w.put(ctx->rps); o_tq = w.put(ctx->t_q);
+        o_qt = w.put(ctx->q_t); o_qd = w.put(ctx->q_d); o_qbase = w.put(ctx->q_base); o_qrows = w.put(ctx->q_rows);
+    } catch (...) {
+        return bls_fail(ctx, BLS_EINVAL, "out of host memory");
+    }
     if (!ctx->blob) {
         BLS_HIP(ctx, hipMalloc(&ctx->blob, w.host.size()));
         ctx->blob_bytes = w.host.size();
@@ -439,14 +450,19 @@ static int rank_ring_init(bls_ctx *ctx)
     RankRing &rr = ctx->rr;
     if (!rr.arrived.empty()) return BLS_OK;
     const size_t n = (size_t)ctx->K * ctx->P;
-    rr.put_next.assign(ctx->P, 0);
-    rr.done_next.assign(ctx->P, 0);
-    rr.arrived.assign(n, nullptr);
-    rr.released.assign(n, nullptr);
-    rr.has_arrived.assign(n, 0);
-    rr.has_released.assign(n, 0);
-    rr.arrived_on.assign(n, nullptr);
-    rr.released_on.assign(n, nullptr);
+    try {
+        rr.put_next.assign(ctx->P, 0);
+        rr.done_next.assign(ctx->P, 0);
+        rr.has_arrived.assign(n, 0);
+        rr.has_released.assign(n, 0);
+        rr.arrived_on.assign(n, nullptr);
+        rr.released_on.assign(n, nullptr);
+        rr.released.assign(n, nullptr);
+        rr.arrived.assign(n, nullptr);                         // last: its size marks the ring as set up
+    } catch (...) {
+        rr.arrived.clear();
+        return bls_fail(ctx, BLS_EINVAL, "out of host memory");
+    }
     for (size_t i = 0; i < n; ++i) {
         BLS_HIP(ctx, hipEventCreateWithFlags(&rr.arrived[i], hipEventDisableTiming));
         BLS_HIP(ctx, hipEventCreateWithFlags(&rr.released[i], hipEventDisableTiming));
