@@ -144,8 +144,9 @@ def dense_section(args, w, pipe, batches, nnzs, note) -> dict:
 
     # Listing 2's loop: lookup (fused owner side) + bottom MLP per call, completion + prediction k calls later
     loops = {}
-    for fused_completion in (False, True):
-        loop = BlsDlrm(pipe, model, fused_completion=fused_completion)
+    side = torch.cuda.Stream()
+    for fused_completion, two_streams in ((False, False), (True, False), (True, True)):
+        loop = BlsDlrm(pipe, model, fused_completion=fused_completion, lookup_stream=side if two_streams else None)
         torch.cuda.synchronize()
         for i in range(args.warmup):
             loop.forward(dense[i % 2], *batches[i % len(batches)], nnzs[i % len(batches)], last_batch=i == args.warmup - 1)
@@ -159,8 +160,9 @@ def dense_section(args, w, pipe, batches, nnzs, note) -> dict:
         c.bls_check()
         assert done == args.steps
         what = "completion folded into the interaction" if fused_completion else "copy-out, then interaction"
+        what += ", lookups on a second stream" if two_streams else ""
         note(f"{args.steps} iterations of the model loop ({what}): {dt / args.steps * 1e3:.3f} ms per iteration")
-        loops["folded_completion" if fused_completion else "staged_completion"] = {
+        loops[("folded_completion_two_streams" if two_streams else "folded_completion") if fused_completion else "staged_completion"] = {
             "ms_per_iteration": dt / args.steps * 1e3, "samples_per_s": w.B * args.steps / dt}
     mm = [k for k in range(n) if names[k] != "interact"]
     return {"layers": {"bottom": bs, "top": ts}, "kernels": kernels, "dense_ms_per_batch": sum(ms),

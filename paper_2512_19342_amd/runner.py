@@ -179,8 +179,12 @@ class BlsDlrm:
     before the one that would reuse its slot is issued (Fig. "bound": the process blocks on
     iteration 0 before it may start iteration k)."""
 
-    def __init__(self, pipe: Pipeline, model: DenseModel, fused_completion: bool = False):
+    def __init__(self, pipe: Pipeline, model: DenseModel, fused_completion: bool = False, lookup_stream=None):
         self.pipe, self.model, self.fused_completion = pipe, model, fused_completion
+        # With a lookup stream the sparse side (plan, pool into the slot) runs there and the dense side
+        # (MLPs, completion, interaction) on the caller's stream: the library's slot events order the
+        # two, and the gather-bound pooling of one iteration overlaps the matrix work of another.
+        self.lookup_stream = lookup_stream
         self.bound = pipe.w.k
         n = pipe.ctx.K + 1
         f32 = dict(dtype=torch.float32, device=pipe.dev)
@@ -203,7 +207,7 @@ class BlsDlrm:
         done = []
         if self.bound > 0 and len(self.unfinished) == self.pipe.ctx.K:
             done.append(self._finish_tail(stream))
-        it, _ = self.pipe.issue_fused(indices, offsets, nnz, stream)
+        it, _ = self.pipe.issue_fused(indices, offsets, nnz, self.lookup_stream if self.lookup_stream is not None else stream)
         self.unfinished.append(it)
         self.model.apply_bottom(dense, self.x_list[it % len(self.x_list)], stream)
         if len(self.unfinished) > self.bound:

@@ -169,7 +169,7 @@ def test_bls_dlrm_loop_does_not_depend_on_the_bound(part_kind):
     from paper_2512_19342_amd.runner import BlsDlrm, DenseModel, Pipeline
     n_iter = 6
     ref_bits, base = None, None
-    for k in (0, 1, 3):
+    for k, folded, second_stream in ((0, False, False), (1, False, False), (3, False, False), (3, True, False), (2, True, True)):
         w = synth.custom("loop", P=4, T=6, D=32, B=96, k=k, part_kind=part_kind, rows=[500, 64, 3000, 17, 256, 999],
                          bag=("uniform", 0, 12), index_dist=("zipf", 1.1), values="gauss", seed=51)
         tabs = [synth.make_table(w, t) for t in range(w.T)]
@@ -179,11 +179,14 @@ def test_bls_dlrm_loop_does_not_depend_on_the_bound(part_kind):
         bs, ts = synth.mlp_sizes(w, "small")
         bot, top = synth.mlp_weights(w, bs, 0), synth.mlp_weights(w, ts, 1)
         model = DenseModel(pipe.ctx, [(W.to(DEV), b.to(DEV)) for W, b in bot], [(W.to(DEV), b.to(DEV)) for W, b in top], w.B)
-        loop = BlsDlrm(pipe, model)
+        # completion folded into the interaction, and the sparse side on a stream of its own, change nothing
+        loop = BlsDlrm(pipe, model, fused_completion=folded, lookup_stream=torch.cuda.Stream() if second_stream else None)
         got = {}
+        staged = [(dense[it].to(DEV), batches[it][0].to(DEV), batches[it][1].to(DEV)) for it in range(n_iter)]
+        torch.cuda.synchronize()                                # inputs are in place before any stream reads them
         for it in range(n_iter):
-            ix, off = batches[it]
-            for j, p in loop.forward(dense[it].to(DEV), ix.to(DEV), off.to(DEV), int(off[-1]), last_batch=it == n_iter - 1):
+            dn, ixd, offd = staged[it]
+            for j, p in loop.forward(dn, ixd, offd, int(batches[it][1][-1]), last_batch=it == n_iter - 1):
                 assert j == len(got) and it - j <= max(k, 0)  # FIFO, lag within the bound
                 got[j] = p.cpu().numpy()
             if it < n_iter - 1:
