@@ -43,9 +43,9 @@ MUTATIONS = {
     "row-quantised scale and bias swapped": ("memcpy(&scale, p + D, 4);\n        memcpy(&bias, p + D + 4, 4);",
                                              "memcpy(&bias, p + D, 4);\n        memcpy(&scale, p + D + 4, 4);"),
     "row-quantised stride not padded": ("return ((int64_t)D + 8 + 15) / 16 * 16;", "return (int64_t)D + 8;"),
-    "row-quantised codes read as signed": ("prod = (float)p[c] * scale;", "prod = (float)(int8_t)p[c] * scale;"),
-    "row-quantised decoding rounded once": ("prod = (float)p[c] * scale;\n        return prod + bias;",
-                                            "return (float)((double)p[c] * (double)scale + (double)bias);"),
+    "row-quantised codes read as signed": ("(dtype == 2 ? (float)p[c] :", "(dtype == 2 ? (float)(int8_t)p[c] :"),
+    "row-quantised decoding rounded once": ("prod = (dtype == 2 ? (float)p[c] : e4m3_to_float(p[c])) * scale;\n        return prod + bias;",
+                                            "return (float)((double)(dtype == 2 ? (float)p[c] : e4m3_to_float(p[c])) * (double)scale + (double)bias);"),
     "layer weight read transposed": ("double w = (double)W[(int64_t)n * K + k], xv = x[m * K + k];",
                                      "double w = (double)W[(int64_t)k * N + n], xv = x[m * K + k];"),
     "layer bias dropped": ("double acc = bias ? (double)bias[n] : 0.0;", "double acc = 0.0;"),
