@@ -492,6 +492,43 @@ def test_per_rank_issue_and_completion(k, cfg):
     assert np.array_equal(bits(out.cpu().numpy()), bits(refs[0]))
 
 
+@pytest.mark.parametrize("part_kind", [0, 1])
+def test_per_rank_weighted_and_mean(part_kind):
+    """The per-rank calls with per-sample weights in the puts and mean pooling at completion."""
+    from paper_2512_19342_amd.runner import Pipeline
+    w = synth.custom("rankw", P=3, T=4, D=24, B=31, k=2, part_kind=part_kind, rows=[300, 17, 1000, 64], values="gauss",
+                     bag=("uniform", 0, 9), index_dist=("zipf", 1.1), seed=63)
+    dev = torch.device("cuda:0")
+    tabs_cpu = [synth.make_table(w, t) for t in range(w.T)]
+    pipe = Pipeline(w, [t.to(dev) for t in tabs_cpu], 4096)
+    c, ctx = case_of(w), pipe.ctx
+    streams = [torch.cuda.Stream() for _ in range(w.P)]
+    rng = np.random.default_rng(7)
+    for mean in (False, True):
+        runs = []
+        for j in range(2):                                      # two iterations in flight (K = 2)
+            it = (2 if mean else 0) + j
+            ix, off = synth.make_batch(w, it)
+            nnz = int(off[-1])
+            wts = torch.from_numpy(rng.uniform(-2, 2, nnz).astype(np.float32))
+            rweights = torch.zeros(max(nnz, 1), dtype=torch.float32, device=dev)
+            ctx.bls_plan_weighted(ix.to(dev), off.to(dev), wts.to(dev), nnz, pipe.sendcounts, pipe.sdispls, pipe.recvcounts,
+                                  pipe.rdispls, pipe.ridx, rweights, pipe.segoff, None, pipe.ws)
+            ridx, segoff, off_d = pipe.ridx[:max(nnz, 1)].clone(), pipe.segoff.clone(), off.to(dev)
+            torch.cuda.synchronize()
+            for d in rng.permutation(w.P):
+                ctx.bls_rank_put(int(d), ridx, rweights, segoff, nnz, it, streams[d])
+            ref = oracle.pipeline(c, [t.numpy() for t in tabs_cpu], ix.numpy(), off.numpy(), weights=wts.numpy(), mean=mean)["Out"]
+            runs.append((it, off_d, ref, pipe.new_out()))
+        for it, off_d, ref, out in runs:
+            for s in rng.permutation(w.P):
+                ctx.bls_rank_complete(int(s), it, off_d if mean else None, out, streams[s])
+        torch.cuda.synchronize()
+        ctx.bls_check()
+        for it, off_d, ref, out in runs:
+            assert np.array_equal(bits(out.cpu().numpy()), bits(ref)), (mean, it)
+
+
 def test_step_can_be_captured_in_a_graph_and_replayed():
     """The whole staged step recorded once into a HIP graph (the calls allocate nothing and clear
     nothing with memsets) and replayed on new batches written into the same input buffers, with
