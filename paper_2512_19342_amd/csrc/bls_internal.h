@@ -145,6 +145,14 @@ __device__ __forceinline__ int64_t bls_sigma(const DevDesc &dd, int q, int s, ui
     return ns * dd.B + (int64_t)dd.n_loc[d] * dd.first[s] + (int64_t)(q - ns) * n + b_loc;
 }
 
+// sigma for a row-wise partition, where every rank serves all T tables: q = d*T + t, nsum(d) = d*T,
+// n_loc = T and first(s) = s*Bq + min(s, Br) - no table look-ups.
+__device__ __forceinline__ int64_t bls_sigma_rowwise(const DevDesc &dd, int d, int t, int s, uint32_t b_loc, uint32_t n)
+{
+    const int64_t first_s = (int64_t)s * dd.Bq + ((uint32_t)s < dd.Br ? (uint32_t)s : dd.Br);
+    return ((int64_t)d * dd.B + first_s) * dd.T + (int64_t)t * n + b_loc;
+}
+
 __device__ __forceinline__ int64_t bls_rho(const DevDesc &dd, int q, int s, uint32_t b_loc, uint32_t n)
 {
     return (int64_t)dd.Q * dd.first[s] + (int64_t)q * n + b_loc;

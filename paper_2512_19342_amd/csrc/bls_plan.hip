@@ -79,23 +79,33 @@ __global__ __launch_bounds__(kThreads) void plan_count_rowwise(DevDesc dd, const
     }
     const int64_t rows = dd.rows[t], rps = dd.rps[t];
     int64_t cnt = 0;
+    int64_t ahead = li < len ? idx[lo + li] : 0;              // the next chunk's index is in flight while this one is counted
     for (int64_t c = 0; __any(c < len); c += G) {
         const int64_t j = c + li;
+        const int64_t ix = ahead;
+        ahead = j + G < len ? idx[lo + j + G] : 0;
         int d = -1;
         if (j < len) {
-            const int64_t ix = idx[lo + j];
             if (ix < 0 || ix >= rows) flag_error(dd);
             else d = owner_of_row(ix, rps);
         }
-        for (int o = 0; o < dd.P; ++o) {
-            const unsigned long long m = (__ballot(d == o) >> gbase) & gmask;
-            if (li == o) cnt += __popcll(m);
+        if (dd.P <= 8) {
+            // up to eight owners: one byte per owner in a 64-bit word, summed over the group's lanes
+            unsigned long long pk = d >= 0 ? 1ull << (8 * d) : 0ull;
+#pragma unroll
+            for (int o = G / 2; o >= 1; o >>= 1) pk += __shfl_xor(pk, o, 64);
+            cnt += (int64_t)((pk >> (8 * (li & 7))) & 0xffull);
+        } else {
+            for (int o = 0; o < dd.P; ++o) {
+                const unsigned long long m = (__ballot(d == o) >> gbase) & gmask;
+                if (li == o) cnt += __popcll(m);
+            }
         }
     }
     if (live && li < dd.P) {
         int s; uint32_t b_loc, n;
         bls_split_sample(dd, b, s, b_loc, n);
-        seglen[bls_sigma(dd, li * dd.T + t, s, b_loc, n)] = cnt;
+        seglen[bls_sigma_rowwise(dd, li, t, s, b_loc, n)] = cnt;
     }
 }
 
@@ -334,24 +344,41 @@ __global__ __launch_bounds__(kThreads) void plan_scatter_rowwise(DevDesc dd, con
         if (li < dd.P) {
             int s; uint32_t b_loc, n;
             bls_split_sample(dd, b, s, b_loc, n);
-            next = segoff[bls_sigma(dd, li * dd.T + t, s, b_loc, n)];
+            next = segoff[bls_sigma_rowwise(dd, li, t, s, b_loc, n)];
             if (perm) to_send = sabs[s * dd.P + li] - rabs[li * dd.P + s];
         }
     }
     const int64_t rows = dd.rows[t], rps = dd.rps[t];
+    int64_t ahead = li < len ? idx[lo + li] : 0;              // the next chunk's index is in flight while this one is placed
     for (int64_t c = 0; __any(c < len); c += G) {
         const int64_t j = c + li;
+        const int64_t ix = ahead;
+        ahead = j + G < len ? idx[lo + j + G] : 0;
         int d = -1;
         int64_t r = 0;
         if (j < len) {
-            const int64_t ix = idx[lo + j];
             if (ix >= 0 && ix < rows) { d = owner_of_row(ix, rps); r = ix - (int64_t)d * rps; }
         }
         int rank = 0, add = 0;
-        for (int o = 0; o < dd.P; ++o) {
-            const unsigned long long m = (__ballot(d == o) >> gbase) & gmask;
-            if (d == o) rank = __popcll(m & below);
-            if (li == o) add = __popcll(m);
+        if (dd.P <= 8) {
+            // one byte per owner: a prefix sum over the group's lanes gives every lookup its rank among
+            // the earlier ones of the same owner, the last lane's sum the chunk's count per owner
+            const unsigned long long pk = d >= 0 ? 1ull << (8 * d) : 0ull;
+            unsigned long long pre = pk;
+#pragma unroll
+            for (int o = 1; o < G; o <<= 1) {
+                const unsigned long long v = __shfl_up(pre, o, G);
+                if (li >= o) pre += v;
+            }
+            if (d >= 0) rank = (int)(((pre - pk) >> (8 * d)) & 0xffull);
+            const unsigned long long total = __shfl(pre, gbase + G - 1, 64);
+            add = (int)((total >> (8 * (li & 7))) & 0xffull);
+        } else {
+            for (int o = 0; o < dd.P; ++o) {
+                const unsigned long long m = (__ballot(d == o) >> gbase) & gmask;
+                if (d == o) rank = __popcll(m & below);
+                if (li == o) add = __popcll(m);
+            }
         }
         const int src = gbase + (d < 0 ? 0 : d);
         const int64_t place = __shfl(next, src, 64) + rank;
