@@ -227,7 +227,7 @@ int bls_rank_delay(bls_ctx *ctx, uint32_t microseconds, void *hip_stream);
 
 /*
  * The dense part of the model around the lookup (Introduction: dense features go through the
- * bottom MLP, the pooled vectors and its output through an explicit dot-interaction layer and
+ * bottom MLP, the pooled vectors and its output through a dot-product interaction layer and
  * the top MLP; Listings 1 and 2: apply_mlp, interact_features).  fp32 in, fp32 out, products
  * accumulated in fp32 on the matrix cores; the summation order is the hardware's, so results
  * match a double-precision evaluation to within (K + 3) * 2^-24 * (|bias| + sum |x||w|).

@@ -9,7 +9,7 @@
  * What the paper fixes (section / listing cited at each function):
  *   - every rank owns a contiguous block of the global batch (Introduction: row-block
  *     partition of the batch into mini-batches) and a share of the embedding tables
- *     ("distributed by a given partitioning strategy");
+ *     (the partitioning strategy is a given, not part of the method);
  *   - each rank works out which vectors it needs from which rank and fetches them
  *     with an alltoallv (Introduction);
  *   - the lookup itself is an EmbeddingBag over (offsets, indices) per table and the
@@ -17,7 +17,7 @@
  *     (Listing 1: apply_emb, then alltoall(ly, n_emb_per_rank));
  *   - with bound k = 0 the exchange is semantically MPI_Alltoallv (A zero-bound
  *     parameter), and for any k the results are unchanged (Abstract; Related Work:
- *     vectors "always fully accurate");
+ *     the retrieved vectors are never approximated);
  *   - completion copies the receive region of the iteration's ring slot to the
  *     caller's buffer (Alltoallv completion).
  * Where the paper is silent the reading taken is stated beside the code and listed in
@@ -103,8 +103,8 @@ static int check_partition(int P, int T, int part_kind, const int64_t *rows, con
 /* ---- index bucketing: counts, displacements, stable placement ------------------- */
 
 /*
- * Introduction ("each process determines the vector IDs required from other
- * processes, and retrieves them through an alltoallv"): for every lookup l, in
+ * Introduction (every process works out which vectors it needs from which other
+ * process and fetches them with an alltoallv): for every lookup l, in
  * increasing l, the requester s, the owner d and the row r inside the owner's shard.
  * sendcounts[s][d] = number of lookups rank s asks of rank d; recvcounts is its
  * transpose; displacements are running sums (the MPI_Alltoallv convention the
@@ -633,7 +633,7 @@ int orc_mlp_layer(int64_t M, int K, int N, const double *x, const float *W, cons
 }
 
 /*
- * interact_features (Listings 1 and 2; Introduction: "an explicit dot-interaction layer"):
+ * interact_features (Listings 1 and 2; Introduction: the vectors are combined by a dot-product interaction layer):
  * per sample the D-vector x from the bottom MLP and the T pooled embedding vectors form
  * Z = [x; e_0; ...; e_{T-1}] ((T+1) x D); the output is x followed by the dot products
  * Z_i . Z_j for every pair i > j, ordered by i, then j (the reference model's order; the
