@@ -3,7 +3,8 @@
 // Every lookup belongs to exactly one segment (owner d, requester s, local table, local
 // sample), and segments are numbered in owner order, so
 //   1. count   - the length of every segment (table-wise: the bag length; row-wise: a
-//                group of lanes per bag splits its lookups over the P owners with ballots),
+//                group of lanes per bag splits its lookups over the P owners: packed byte
+//                counters summed over the lanes for P <= 8, one ballot per owner otherwise),
 //   2. scan    - an exclusive scan of the segment lengths (LDS-staged, three phases) gives
 //                segoff, and the alltoallv counts and displacements are differences of
 //                segoff at the (d, s) block edges - no atomics, no separate histogram,
