@@ -516,6 +516,7 @@ def main() -> int:
     a_staged = sum(sb.values())
     pool_pack_gbps = (sb["pool"] + sb["pack"]) / ((stage_ms["pool"] + stage_ms["pack"]) * 1e-3) / 1e9
 
+    traffic = recorded_traffic(args.config) if not args.index_dist and args.size == "full" and not args.table_dtype else None
     res = {
         "metric": "embedding lookups/sec + achieved HBM GB/s (bucket+pool+pack), 1 MI355X",
         "value": lookups / dt, "unit": "lookups/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -532,7 +533,10 @@ def main() -> int:
                    "table_bytes": w.table_bytes(), "distinct_batches": len(batches)},
         "roofline": {"bound": "hbm", "kernel": "pool_stream (bls_embbag_pool)", "achieved": achieved,
                      "peak": PEAK_HBM_GBPS, "unit": "GB/s", "frac": achieved / PEAK_HBM_GBPS,
-                     "traffic": recorded_traffic(args.config) if not args.index_dist and args.size == "full" else None,
+                     "traffic": traffic,
+                     # what crossed the fabric, from the counters: the rest of the algorithmic bytes came out of L1 / L2
+                     "traffic_gbps": None if traffic is None else traffic / pool_s / 1e9,
+                     "traffic_frac": None if traffic is None else traffic / pool_s / 1e9 / PEAK_HBM_GBPS,
                      "algorithmic_bytes_per_launch": sb["pool"], "avg_launch_ms": stage_ms["pool"]},
         "hbm_gbps": {"whole_path_staged": a_staged / (dt / args.steps) / 1e9, "pool_plus_pack": pool_pack_gbps,
                      "pool_plus_pack_frac_of_peak": pool_pack_gbps / PEAK_HBM_GBPS},
