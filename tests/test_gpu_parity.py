@@ -567,3 +567,41 @@ def test_step_can_be_captured_in_a_graph_and_replayed():
     pipe.ctx.bls_check()
     head, tail, _ = pipe.ctx.bls_ring_state()
     assert head == tail                                          # the recorded step left nothing in flight
+
+
+def _random_spec(rng):
+    P = int(rng.integers(1, 10))
+    T = int(rng.integers(1, 8))
+    D = int(rng.choice([1, 2, 3, 4, 6, 8, 12, 16, 20, 24, 32, 40, 64, 128, int(rng.integers(1, 70))]))
+    B = int(rng.integers(P, 90))
+    rows = [int(rng.choice([1, 2, int(rng.integers(1, 50)), int(rng.integers(50, 5000))])) for _ in range(T)]
+    lo = int(rng.integers(0, 3))
+    bag = ("uniform", lo, lo + int(rng.integers(0, 40))) if rng.random() < 0.8 else ("fixed", int(rng.integers(0, 5)))
+    return dict(P=P, T=T, D=D, B=B, part_kind=int(rng.integers(0, 2)), rows=rows, bag=bag,
+                k=int(rng.integers(0, 4)), table_dtype=str(rng.choice(["fp32", "fp16", "u8rq", "f8rq"])),
+                index_dist=("zipf", 1.1) if rng.random() < 0.5 else ("uniform",))
+
+
+@pytest.mark.parametrize("seed", range(40))
+def test_random_shapes(seed):
+    """Shapes drawn at random (ranks, tables, vector lengths incl. odd ones, ragged batches, one-row
+    tables, empty bags, every storage type, both partitions): the staged path, the fused owner side
+    with weights, and mean pooling, all against the oracle bit for bit."""
+    from paper_2512_19342_amd.runner import Pipeline
+    rng = np.random.default_rng(1000 + seed)
+    spec = _random_spec(rng)
+    w = synth.custom(f"rand{seed}", values="gauss", seed=100 + seed, **spec)
+    tabs = [synth.make_table(w, t) for t in range(w.T)]
+    batches = [synth.make_batch(w, it) for it in range(2)]
+    got, pipe = run_gpu(w, tabs, batches)
+    check_against_oracle(w, tabs, batches, got)
+    dev, c = torch.device("cuda:0"), case_of(w)
+    ix, off = batches[1]
+    nnz = int(off[-1])
+    wts = torch.from_numpy(rng.uniform(-2, 2, max(nnz, 1)).astype(np.float32))[:nnz]
+    out = pipe.new_out()
+    it, _ = pipe.issue_weighted(ix.to(dev), off.to(dev), wts.to(dev), nnz, fused=True)
+    pipe.complete(it, out, mean_offsets=off.to(dev))
+    pipe.ctx.bls_check()
+    ref = oracle.pipeline(c, [t.numpy() for t in tabs], ix.numpy(), off.numpy(), weights=wts.numpy(), mean=True)["Out"]
+    assert np.array_equal(bits(out.cpu().numpy()), bits(ref)), spec
