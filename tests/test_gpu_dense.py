@@ -323,3 +323,28 @@ def test_completion_folded_into_the_interaction(spec):
         c.bls_unpack_interact(it2 + 1, xs[0], z)
     assert e.value.code == A.BLS_ERING_EMPTY
     c.bls_check()
+
+
+@pytest.mark.parametrize("seed", range(20))
+def test_random_dense_shapes(seed):
+    """Layer and interaction shapes drawn at random (tile edges, K not a multiple of 4 or 16, N = 1)."""
+    rng = np.random.default_rng(500 + seed)
+    M, K, N = int(rng.integers(1, 400)), int(rng.choice([1, 3, 13, 16, 17, 64, 100, 128, 260])), int(rng.choice([1, 2, 31, 64, 127, 128, 129, 300]))
+    act = int(rng.integers(0, 3))
+    c = ctx_for()
+    x = rng.normal(size=(M, K)).astype(np.float32)
+    W = (rng.normal(size=(N, K)) / np.sqrt(K)).astype(np.float32)
+    b = rng.normal(size=N).astype(np.float32)
+    y = torch.full((M, N), float("nan"), device=DEV)
+    c.bls_mlp_layer(torch.from_numpy(x).to(DEV), torch.from_numpy(W).to(DEV), torch.from_numpy(b).to(DEV), act, y)
+    ref, err = oracle.mlp_layer(x, W, b, act)
+    assert np.all(np.abs(y.cpu().numpy() - ref) <= err), (M, K, N, act)
+    T, D, B = int(rng.integers(1, 70)), int(rng.choice([1, 4, 5, 16, 24, 33, 64])), int(rng.integers(1, 12))
+    ci = ctx_for(T, D, B)
+    xe = rng.normal(size=(B, D)).astype(np.float32)
+    emb = rng.normal(size=(B, T, D)).astype(np.float32)
+    z = torch.full((B, D + T * (T + 1) // 2), float("nan"), device=DEV)
+    ci.bls_interact(torch.from_numpy(xe).to(DEV), torch.from_numpy(emb).to(DEV), z)
+    ci.bls_check()
+    ref, err = oracle.interact(xe, emb)
+    assert np.all(np.abs(z.cpu().numpy() - ref) <= err), (T, D, B)
