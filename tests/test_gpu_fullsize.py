@@ -142,3 +142,54 @@ def test_dense_model_full_size():
     got = p[pick].cpu().numpy()
     assert np.array_equal(got, a) and np.all((got > 0) & (got < 1))
     print(f"  {len(rows)} sampled samples match through {len(bot) + len(top)} layers and the interaction", flush=True)
+
+
+@pytest.mark.parametrize("cfg", [4, 3])
+def test_full_size_weighted(cfg):
+    """Per-sample weights at full size (the weighted kernels in the launch shape bench.py uses), with
+    mean pooling at completion for the table-wise workload: sampled bags recomputed by the oracle
+    from regenerated rows - per shard in bag order, shards added in rank order."""
+    from paper_2512_19342_amd.runner import Pipeline
+    w = synth.workload(cfg, "full")
+    dev = torch.device("cuda:0")
+    mean = w.part_kind == 0
+    print(f"full-size weighted parity {w.name}: generating {w.table_bytes() / 1e9:.1f} GB of tables", flush=True)
+    tabs = [synth.make_table(w, t, dev) for t in range(w.T)]
+    ix, off = synth.make_batch(w, 5, dev)
+    w._cdf_cache.clear()
+    nnz = int(off[-1].item())
+    gen = torch.Generator(device="cpu").manual_seed(cfg)
+    wts = torch.rand(nnz, generator=gen) * 4 - 2
+    pipe = Pipeline(w, tabs, nnz)
+    out = pipe.new_out()
+    it, _ = pipe.issue_weighted(ix, off, wts.to(dev), nnz)
+    pipe.complete(it, out, mean_offsets=off if mean else None)
+    pipe.ctx.bls_check()
+    ix_h, off_h, wts_h = ix.cpu().numpy(), off.cpu().numpy(), wts.numpy()
+    rng = np.random.default_rng(10 + cfg)
+    n_samples = 600
+    ts, bs = rng.integers(0, w.T, n_samples), rng.integers(0, w.B, n_samples)
+    for t, b in zip(ts.tolist(), bs.tolist()):
+        g = t * w.B + b
+        idx, wt = ix_h[off_h[g]:off_h[g + 1]], wts_h[off_h[g]:off_h[g + 1]]
+        rows = synth.table_rows(w, t, torch.from_numpy(idx)).numpy().reshape(-1, w.D)
+        if w.part_kind == 0:
+            mini = oracle.Case(1, 1, w.D, 1, 0, [max(len(idx), 1)], [0], 0)
+            tab = rows if len(idx) else np.zeros((1, w.D), np.float32)
+            _, want = oracle.embbag_plain(mini, [np.ascontiguousarray(tab)], np.arange(len(idx)), np.array([0, len(idx)]),
+                                          weights=wt, mean=mean)
+            want = want.reshape(w.D)
+        else:
+            rps = -(-w.rows[t] // w.P)
+            parts = np.zeros((w.P, w.D), np.float32)
+            for d in range(w.P):
+                sel = idx // rps == d
+                m = int(sel.sum())
+                if m:
+                    mini = oracle.Case(1, 1, w.D, 1, 0, [m], [0], 0)
+                    _, p32 = oracle.embbag_plain(mini, [np.ascontiguousarray(rows[sel])], np.arange(m), np.array([0, m]),
+                                                 weights=wt[sel])
+                    parts[d] = p32.reshape(w.D)
+            want, _ = oracle.bag_sum(parts)
+        assert np.array_equal(out[b, t].cpu().numpy().view(np.uint32), want.view(np.uint32)), (t, b)
+    print(f"  {n_samples} sampled weighted bags match", flush=True)
