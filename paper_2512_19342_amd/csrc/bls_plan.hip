@@ -20,6 +20,7 @@ constexpr int kThreads = 256;
 constexpr int kItems = 16;                       // scan items per thread
 constexpr int kChunk = kThreads * kItems;        // scan items per block
 constexpr int kSmallScanTiles = 2;               // up to this many tiles one workgroup scans alone
+constexpr int kAhead = 4;                        // row-wise kernels: chunks of a bag's indices loaded ahead
 
 __device__ __forceinline__ void flag_error(const DevDesc &dd) { atomicOr(dd.err, 1); }
 
@@ -80,11 +81,17 @@ __global__ __launch_bounds__(kThreads) void plan_count_rowwise(DevDesc dd, const
     }
     const int64_t rows = dd.rows[t], rps = dd.rps[t];
     int64_t cnt = 0;
-    int64_t ahead = li < len ? idx[lo + li] : 0;              // the next chunk's index is in flight while this one is counted
+    // a bag is a handful of chunks and every chunk a dependent round trip: the indices of the next
+    // kAhead chunks are always in flight while the current one is counted
+    int64_t nx[kAhead];
+#pragma unroll
+    for (int a = 0; a < kAhead; ++a) nx[a] = a * G + li < len ? idx[lo + a * G + li] : 0;
     for (int64_t c = 0; __any(c < len); c += G) {
         const int64_t j = c + li;
-        const int64_t ix = ahead;
-        ahead = j + G < len ? idx[lo + j + G] : 0;
+        const int64_t ix = nx[0];
+#pragma unroll
+        for (int a = 0; a + 1 < kAhead; ++a) nx[a] = nx[a + 1];
+        nx[kAhead - 1] = j + kAhead * G < len ? idx[lo + j + kAhead * G] : 0;
         int d = -1;
         if (j < len) {
             if (ix < 0 || ix >= rows) flag_error(dd);
@@ -350,11 +357,17 @@ __global__ __launch_bounds__(kThreads) void plan_scatter_rowwise(DevDesc dd, con
         }
     }
     const int64_t rows = dd.rows[t], rps = dd.rps[t];
-    int64_t ahead = li < len ? idx[lo + li] : 0;              // the next chunk's index is in flight while this one is placed
+    // a bag is a handful of chunks and every chunk a dependent round trip: the indices of the next
+    // kAhead chunks are always in flight while the current one is placed
+    int64_t nx[kAhead];
+#pragma unroll
+    for (int a = 0; a < kAhead; ++a) nx[a] = a * G + li < len ? idx[lo + a * G + li] : 0;
     for (int64_t c = 0; __any(c < len); c += G) {
         const int64_t j = c + li;
-        const int64_t ix = ahead;
-        ahead = j + G < len ? idx[lo + j + G] : 0;
+        const int64_t ix = nx[0];
+#pragma unroll
+        for (int a = 0; a + 1 < kAhead; ++a) nx[a] = nx[a + 1];
+        nx[kAhead - 1] = j + kAhead * G < len ? idx[lo + j + kAhead * G] : 0;
         int d = -1;
         int64_t r = 0;
         if (j < len) {
