@@ -192,6 +192,7 @@ def alltoallv_demo(args) -> int:
         tabs = [torch.zeros((1, D), dtype=torch.float32, device=dev) for _ in range(P)]
         for t in range(P):
             c.bls_set_shard(t, t, tabs[t])
+        c.bls_commit(torch.empty(c.bls_desc_bytes(), dtype=torch.uint8, device=dev))
         n = P * B * D
         send = torch.rand(n, dtype=torch.float32, device=dev)
         slot = torch.empty(n, dtype=torch.float32, device=dev)

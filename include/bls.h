@@ -34,10 +34,13 @@
  * HOST memory.  `hip_stream` is a hipStream_t passed as void* (NULL = the null
  * stream).  Calls enqueue work and return without waiting.  Data-dependent errors
  * (an index outside its table, offsets that decrease) cannot be seen by the host at
- * call time: kernels skip the offending item, raise a device-side flag, and
- * bls_check reports it.  The library allocates a few KB of device memory per context
- * for its descriptor tables and never anything proportional to the problem; scratch
- * memory comes from the caller (d_ws).  A context is not thread safe.
+ * call time: kernels raise a device-side flag that bls_check reports, and never touch
+ * memory outside the buffers: a lookup with a bad index adds nothing to its bag's vector
+ * (whether the alltoallv counts include it is unspecified), a bag with bad offsets is
+ * treated as empty.  The library allocates no device memory: its small descriptor tables
+ * live in a buffer the caller provides (bls_commit), scratch memory comes from the caller
+ * (d_ws).  No path call allocates, frees or waits for the device.  A context is not thread
+ * safe.
  */
 #ifndef BLS_H
 #define BLS_H
@@ -94,6 +97,31 @@ int bls_destroy(bls_ctx *ctx);
  * call per (t, rank), rows_in_shard = number of rows of table t that fall in the
  * rank's block (may be 0, then d_rows may be NULL). */
 int bls_set_shard(bls_ctx *ctx, int32_t t, int32_t rank, const void *d_rows, int64_t rows_in_shard);
+
+/* Row-wise block partition made visible: rows [first_row, first_row + rows_in_shard) of table t
+ * are the shard of `rank` (block size ceil(rows_t / P); trailing shards may be empty).  Table-wise:
+ * the owner holds (0, rows_t), every other rank (0, 0).  Host outputs, either may be NULL. */
+int bls_shard_range(const bls_ctx *ctx, int32_t t, int32_t rank, int64_t *first_row, int64_t *rows_in_shard);
+
+/* The library's descriptor tables (mini-batch starts, tables per rank, shard pointers and sizes,
+ * the error flag) live in device memory of the caller: bls_desc_bytes gives the size (a few KB),
+ * bls_commit checks that every shard has been set and uploads the tables into d_desc (16-byte
+ * aligned, borrowed until bls_destroy) with an asynchronous copy on `hip_stream`; path calls on
+ * other streams must be ordered after it by the caller.  Every call that launches kernels returns
+ * BLS_EINVAL until bls_commit has been called, and again after a later bls_set_shard until the next
+ * bls_commit (which then waits for the device first: kernels in flight may still read the old
+ * tables; the error flag is kept).  Not allowed while iterations are in flight (BLS_EORDER). */
+int bls_desc_bytes(const bls_ctx *ctx, size_t *bytes);
+int bls_commit(bls_ctx *ctx, void *d_desc, size_t bytes, void *hip_stream);
+
+/* Launch shape of the pooling kernels, for tests and experiments; results are the same bit for
+ * bit under every setting.  lane_bytes: table bytes one lane holds of a row (4, 8, 16; 0 = the
+ * library's choice); segments_per_group: consecutive segments one lane group streams (1..63, capped
+ * at lanes - 1; 0 = chosen from the mean bag length); xcd_map: 1 deals workgroups so that one XCD
+ * works on the same tables, 0 plain grid (-1 = library's choice); wide_positions: 1 forces 64-bit
+ * row positions (-1 / 0 = only when a shard needs them). */
+int bls_set_pool_tuning(bls_ctx *ctx, int32_t lane_bytes, int32_t segments_per_group, int32_t xcd_map,
+                        int32_t wide_positions);
 
 /* Buffer sizes in bytes for a batch of at most max_nnz lookups: plan workspace, the
  * pooled buffer Y, the send buffer S, and one ring slot (all three F*T*B*D fp32). */

@@ -103,7 +103,6 @@ extern "C" int bls_destroy(bls_ctx *ctx)
             }
             for (auto e : ctx->rr.arrived) if (e) (void)hipEventDestroy(e);
             for (auto e : ctx->rr.released) if (e) (void)hipEventDestroy(e);
-            if (ctx->blob) { (void)hipDeviceSynchronize(); (void)hipFree(ctx->blob); }
             if (cur != ctx->device) (void)hipSetDevice(cur);
         }
     }
@@ -127,6 +126,35 @@ extern "C" int bls_set_shard(bls_ctx *ctx, int32_t t, int32_t rank, const void *
     ctx->q_base[q] = d_rows;
     ctx->q_set[q] = 1;
     ctx->dirty = true;
+    return BLS_OK;
+}
+
+extern "C" int bls_shard_range(const bls_ctx *ctx, int32_t t, int32_t rank, int64_t *first_row, int64_t *rows_in_shard)
+{
+    if (!ctx || t < 0 || t >= ctx->T || rank < 0 || rank >= ctx->P) return BLS_EINVAL;
+    int64_t lo = 0, n = 0;
+    if (ctx->part_kind == BLS_TABLE_WISE) {
+        if (rank == ctx->owner[t]) n = ctx->rows[t];
+    } else {
+        lo = std::min<int64_t>((int64_t)rank * ctx->rps[t], ctx->rows[t]);
+        n = ctx->q_rows[rank * ctx->T + t];
+    }
+    if (first_row) *first_row = lo;
+    if (rows_in_shard) *rows_in_shard = n;
+    return BLS_OK;
+}
+
+extern "C" int bls_set_pool_tuning(bls_ctx *ctx, int32_t lane_bytes, int32_t segments_per_group, int32_t xcd_map, int32_t wide_positions)
+{
+    if (!ctx) return BLS_EINVAL;
+    if (lane_bytes != 0 && lane_bytes != 4 && lane_bytes != 8 && lane_bytes != 16)
+        return bls_fail(ctx, BLS_EINVAL, "bls_set_pool_tuning: lane_bytes must be 0, 4, 8 or 16");
+    if (segments_per_group < 0 || segments_per_group > 63 || xcd_map < -1 || xcd_map > 1 || wide_positions < -1 || wide_positions > 1)
+        return bls_fail(ctx, BLS_EINVAL, "bls_set_pool_tuning: value out of range");
+    ctx->tune_lane_bytes = lane_bytes;
+    ctx->tune_segs = segments_per_group;
+    ctx->tune_xcd = xcd_map;
+    ctx->tune_wide = wide_positions;
     return BLS_OK;
 }
 
@@ -166,59 +194,107 @@ extern "C" int bls_pooled_counts(const bls_ctx *ctx, int64_t *pcount, int64_t *p
     return BLS_OK;
 }
 
-// ---- descriptor upload --------------------------------------------------------------
+// ---- descriptor tables ---------------------------------------------------------------
+// The kernels read a few small tables (mini-batch starts, tables per rank, shard pointers and
+// sizes).  They live in device memory the caller provides (bls_desc_bytes / bls_commit): the
+// library allocates none.  Layout: 16 bytes for the error flag, then the arrays, each on a
+// 16-byte boundary.
 
 namespace {
-struct BlobWriter {
-    std::vector<char> host;
-    template <class V> size_t put(const std::vector<V> &v)
-    {
-        size_t at = (host.size() + 15) & ~size_t(15);
-        host.resize(at + v.size() * sizeof(V));
-        if (!v.empty()) memcpy(host.data() + at, v.data(), v.size() * sizeof(V));
-        return at;
-    }
+constexpr size_t kFlagBytes = 16;
+
+struct BlobLayout {
+    size_t first, n_loc, nsum, rows, rps, t_q, q_t, q_d, q_base, q_rows, total;
 };
+
+size_t put(size_t &at, size_t bytes)
+{
+    const size_t here = (at + 15) & ~size_t(15);
+    at = here + bytes;
+    return here;
+}
+
+BlobLayout blob_layout(const bls_ctx *c)
+{
+    BlobLayout L;
+    size_t at = kFlagBytes;
+    const size_t P = (size_t)c->P, T = (size_t)c->T, Q = (size_t)c->Q;
+    L.first = put(at, (P + 1) * sizeof(int64_t));
+    L.n_loc = put(at, P * sizeof(int32_t));
+    L.nsum = put(at, (P + 1) * sizeof(int32_t));
+    L.rows = put(at, T * sizeof(int64_t));
+    L.rps = put(at, T * sizeof(int64_t));
+    L.t_q = put(at, T * sizeof(int32_t));
+    L.q_t = put(at, Q * sizeof(int32_t));
+    L.q_d = put(at, Q * sizeof(int32_t));
+    L.q_base = put(at, Q * sizeof(void *));
+    L.q_rows = put(at, Q * sizeof(int64_t));
+    L.total = (at + 15) & ~size_t(15);
+    return L;
+}
+
+template <class V> void fill(std::vector<char> &blob, size_t at, const std::vector<V> &v)
+{
+    if (!v.empty()) memcpy(blob.data() + at, v.data(), v.size() * sizeof(V));
+}
 }  // namespace
 
-int bls_commit(bls_ctx *ctx)
+size_t bls_desc_size(const bls_ctx *ctx) { return blob_layout(ctx).total; }
+
+extern "C" int bls_desc_bytes(const bls_ctx *ctx, size_t *bytes)
 {
+    if (!ctx || !bytes) return BLS_EINVAL;
+    *bytes = bls_desc_size(ctx);
+    return BLS_OK;
+}
+
+extern "C" int bls_commit(bls_ctx *ctx, void *d_desc, size_t bytes, void *hip_stream)
+{
+    if (!ctx) return BLS_EINVAL;
     for (int q = 0; q < ctx->Q; ++q)
-        if (!ctx->q_set[q]) return bls_fail(ctx, BLS_EINVAL, "a table shard has not been set (bls_set_shard)");
+        if (!ctx->q_set[q]) return bls_fail(ctx, BLS_EINVAL, "bls_commit: a table shard has not been set (bls_set_shard)");
+    if (!d_desc || ((uintptr_t)d_desc & 15u) != 0) return bls_fail(ctx, BLS_EINVAL, "bls_commit: NULL or misaligned descriptor buffer");
+    const BlobLayout L = blob_layout(ctx);
+    if (bytes < L.total) return bls_fail(ctx, BLS_ENOSPC, "bls_commit: descriptor buffer smaller than bls_desc_bytes");
+    if (ctx->head != ctx->tail) return bls_fail(ctx, BLS_EORDER, "bls_commit: iterations in flight");
     int dev = -1;
     BLS_HIP(ctx, hipGetDevice(&dev));
     if (ctx->device >= 0 && dev != ctx->device) return bls_fail(ctx, BLS_EINVAL, "context used on a different device than before");
-    if (!ctx->dirty && ctx->blob) return BLS_OK;
-
-    BlobWriter w;
-    size_t o_err, o_first, o_nloc, o_nsum, o_rows, o_rps, o_tq, o_qt, o_qd, o_qbase, o_qrows;
+    // a second upload: kernels of earlier calls may still read the old tables, and the earlier copy its source
+    if (ctx->blob) BLS_HIP(ctx, hipDeviceSynchronize());
     try {
-        std::vector<int32_t> errflag(4, 0);
-        o_err = w.put(errflag);
-        o_first = w.put(ctx->first); o_nloc = w.put(ctx->n_loc); o_nsum = w.put(ctx->nsum);
-        o_rows = w.put(ctx->rows); o_rps = w.put(ctx->rps); o_tq = w.put(ctx->t_q);
-        o_qt = w.put(ctx->q_t); o_qd = w.put(ctx->q_d); o_qbase = w.put(ctx->q_base); o_qrows = w.put(ctx->q_rows);
+        ctx->host_blob.assign(L.total, 0);
     } catch (...) {
         return bls_fail(ctx, BLS_EINVAL, "out of host memory");
     }
-    if (!ctx->blob) {
-        BLS_HIP(ctx, hipMalloc(&ctx->blob, w.host.size()));
-        ctx->blob_bytes = w.host.size();
-        ctx->device = dev;
-    } else {
-        BLS_HIP(ctx, hipDeviceSynchronize());   // earlier kernels may still read the old tables
-    }
-    BLS_HIP(ctx, hipMemcpy(ctx->blob, w.host.data(), w.host.size(), hipMemcpyHostToDevice));
-    char *b = (char *)ctx->blob;
+    std::vector<char> &h = ctx->host_blob;
+    fill(h, L.first, ctx->first); fill(h, L.n_loc, ctx->n_loc); fill(h, L.nsum, ctx->nsum);
+    fill(h, L.rows, ctx->rows); fill(h, L.rps, ctx->rps); fill(h, L.t_q, ctx->t_q);
+    fill(h, L.q_t, ctx->q_t); fill(h, L.q_d, ctx->q_d); fill(h, L.q_base, ctx->q_base); fill(h, L.q_rows, ctx->q_rows);
+    // a buffer seen for the first time gets a cleared error flag; a re-upload into the same buffer
+    // (a shard was replaced) leaves the flag as the kernels set it
+    const size_t skip = d_desc == ctx->blob ? kFlagBytes : 0;
+    BLS_HIP(ctx, hipMemcpyAsync((char *)d_desc + skip, h.data() + skip, L.total - skip, hipMemcpyHostToDevice,
+                                (hipStream_t)hip_stream));
+    ctx->blob = d_desc;
+    ctx->device = dev;
+    char *b = (char *)d_desc;
     DevDesc &d = ctx->desc;
     d.P = ctx->P; d.T = ctx->T; d.D = ctx->D; d.F = ctx->F; d.Q = ctx->Q; d.part_kind = ctx->part_kind; d.dtype = ctx->dtype;
     d.pad0 = 0; d.B = ctx->B; d.Bq = (uint32_t)(ctx->B / ctx->P); d.Br = (uint32_t)(ctx->B % ctx->P); d.nseg = ctx->nseg;
-    d.err = (int32_t *)(b + o_err);
-    d.first = (const int64_t *)(b + o_first); d.n_loc = (const int32_t *)(b + o_nloc); d.nsum = (const int32_t *)(b + o_nsum);
-    d.rows = (const int64_t *)(b + o_rows); d.rps = (const int64_t *)(b + o_rps); d.t_q = (const int32_t *)(b + o_tq);
-    d.q_t = (const int32_t *)(b + o_qt); d.q_d = (const int32_t *)(b + o_qd);
-    d.q_base = (const void *const *)(b + o_qbase); d.q_rows = (const int64_t *)(b + o_qrows);
+    d.err = (int32_t *)b;
+    d.first = (const int64_t *)(b + L.first); d.n_loc = (const int32_t *)(b + L.n_loc); d.nsum = (const int32_t *)(b + L.nsum);
+    d.rows = (const int64_t *)(b + L.rows); d.rps = (const int64_t *)(b + L.rps); d.t_q = (const int32_t *)(b + L.t_q);
+    d.q_t = (const int32_t *)(b + L.q_t); d.q_d = (const int32_t *)(b + L.q_d);
+    d.q_base = (const void *const *)(b + L.q_base); d.q_rows = (const int64_t *)(b + L.q_rows);
     ctx->dirty = false;
+    return BLS_OK;
+}
+
+int bls_ready(bls_ctx *ctx)
+{
+    if (!ctx->blob || ctx->dirty)
+        return bls_fail(ctx, BLS_EINVAL, "descriptor tables not on the device: call bls_commit after the last bls_set_shard");
     return BLS_OK;
 }
 
@@ -234,7 +310,7 @@ static int plan_common(bls_ctx *ctx, const int64_t *d_indices, const int64_t *d_
     if (nnz > 0 && (!d_indices || !d_ridx)) return bls_fail(ctx, BLS_EINVAL, "bls_plan: NULL indices or ridx with nnz > 0");
     if (ws_bytes < bls_plan_ws_bytes(ctx)) return bls_fail(ctx, BLS_ENOSPC, "bls_plan: workspace too small");
     if (((uintptr_t)d_ws & 7u) != 0) return bls_fail(ctx, BLS_EINVAL, "bls_plan: workspace must be 8-byte aligned");
-    int rc = bls_commit(ctx);
+    int rc = bls_ready(ctx);
     if (rc) return rc;
     return bls_launch_plan(ctx, d_indices, d_offsets, nnz, d_sendcounts, d_sdispls, d_recvcounts, d_rdispls, d_ridx,
                            d_segoff, d_perm, d_weights, d_rweights, d_ws, ws_bytes, (hipStream_t)hip_stream);
@@ -265,7 +341,7 @@ static int pool_common(bls_ctx *ctx, const int64_t *d_ridx, const float *d_rweig
 {
     if (nnz < 0 || !d_segoff || !d_pooled || (nnz > 0 && !d_ridx)) return bls_fail(ctx, BLS_EINVAL, "bls_embbag_pool: NULL argument");
     if (((uintptr_t)d_pooled & 15u) != 0) return bls_fail(ctx, BLS_EINVAL, "bls_embbag_pool: output must be 16-byte aligned");
-    int rc = bls_commit(ctx);
+    int rc = bls_ready(ctx);
     if (rc) return rc;
     return bls_launch_pool(ctx, d_ridx, d_rweights, d_segoff, nnz, d_pooled, 0, 0, ctx->Q, (hipStream_t)hip_stream);
 }
@@ -290,7 +366,7 @@ extern "C" int bls_pack(bls_ctx *ctx, const float *d_pooled, float *d_send, void
     if (!ctx) return BLS_EINVAL;
     if (!d_pooled || !d_send || d_pooled == d_send) return bls_fail(ctx, BLS_EINVAL, "bls_pack: NULL or aliased buffers");
     if ((((uintptr_t)d_pooled | (uintptr_t)d_send) & 15u) != 0) return bls_fail(ctx, BLS_EINVAL, "bls_pack: buffers must be 16-byte aligned");
-    int rc = bls_commit(ctx);
+    int rc = bls_ready(ctx);
     if (rc) return rc;
     return bls_launch_pack(ctx, d_pooled, d_send, (hipStream_t)hip_stream);
 }
@@ -354,7 +430,7 @@ static int slot_to_fill(bls_ctx *ctx, int32_t slot, const char *who, RingSlot **
         ctx->err = std::string(who) + ": slot does not belong to the iteration just started";
         return BLS_EORDER;
     }
-    int rc = bls_commit(ctx);
+    int rc = bls_ready(ctx);
     if (rc) return rc;
     rc = ensure_events(ctx, r);
     if (rc) return rc;
@@ -416,7 +492,7 @@ static int unpack_common(bls_ctx *ctx, int64_t iter, const int64_t *mean_off, fl
     const int slot = (int)(iter % ctx->K);
     RingSlot &r = ctx->ring[slot];
     if (r.state != 2) return bls_fail(ctx, BLS_EORDER, "bls_unpack: the iteration's exchange has not been issued");
-    int rc = bls_commit(ctx);
+    int rc = bls_ready(ctx);
     if (rc) return rc;
     if (r.filled_on != (hipStream_t)hip_stream) BLS_HIP(ctx, hipStreamWaitEvent((hipStream_t)hip_stream, r.filled, 0));
     rc = bls_launch_unpack(ctx, (const float *)(ctx->slots + (size_t)slot * ctx->slot_bytes), d_out, mean_off, 0u,
@@ -478,7 +554,7 @@ extern "C" int bls_rank_put(bls_ctx *ctx, int32_t rank, const int64_t *d_ridx, c
     if (nnz < 0 || !d_segoff || (nnz > 0 && !d_ridx)) return bls_fail(ctx, BLS_EINVAL, "bls_rank_put: NULL argument");
     if (!ctx->slots) return bls_fail(ctx, BLS_EINVAL, "bls_rank_put: no ring (bls_set_ring)");
     if (ctx->head != ctx->tail) return bls_fail(ctx, BLS_EORDER, "bls_rank_put: whole-batch iterations are in flight on this context");
-    int rc = bls_commit(ctx);
+    int rc = bls_ready(ctx);
     if (rc) return rc;
     rc = rank_ring_init(ctx);
     if (rc) return rc;
@@ -570,7 +646,7 @@ extern "C" int bls_unpack_interact(bls_ctx *ctx, int64_t iter, const float *d_x,
     const int slot = (int)(iter % ctx->K);
     RingSlot &r = ctx->ring[slot];
     if (r.state != 2) return bls_fail(ctx, BLS_EORDER, "bls_unpack_interact: the iteration's exchange has not been issued");
-    int rc = bls_commit(ctx);
+    int rc = bls_ready(ctx);
     if (rc) return rc;
     if (r.filled_on != (hipStream_t)hip_stream) BLS_HIP(ctx, hipStreamWaitEvent((hipStream_t)hip_stream, r.filled, 0));
     rc = bls_launch_interact(ctx, d_x, (const float *)(ctx->slots + (size_t)slot * ctx->slot_bytes), 1, d_z, 0u, (uint32_t)ctx->B,

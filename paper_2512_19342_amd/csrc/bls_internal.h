@@ -10,8 +10,8 @@
 
 #include "bls.h"
 
-// Device-side view of the problem.  Passed to kernels by value; the arrays live in one
-// small device allocation owned by the context.
+// Device-side view of the problem.  Passed to kernels by value; the arrays live in the
+// caller's descriptor buffer (bls_commit).
 //
 // q numbers the (owner, local table) pairs in owner-major order, q = nsum[d] + t_loc,
 // 0 <= q < Q = F*T.  Pooled vector (q, b) sits at vector index
@@ -70,10 +70,13 @@ struct bls_ctx {
 
     // device side
     int device = -1;
-    void *blob = nullptr;         // descriptor arrays + error flag
-    size_t blob_bytes = 0;
+    void *blob = nullptr;         // caller's descriptor buffer: error flag, then the arrays
+    std::vector<char> host_blob;  // what was last uploaded there (kept: the upload is asynchronous)
     bool dirty = true;            // host tables changed since the last upload
     DevDesc desc{};
+
+    // pool launch shape overrides (bls_set_pool_tuning); 0 / -1 = the library's choice
+    int tune_lane_bytes = 0, tune_segs = 0, tune_xcd = -1, tune_wide = -1;
 
     // ring
     char *slots = nullptr;
@@ -88,7 +91,8 @@ struct bls_ctx {
 // ---- helpers shared by the translation units -------------------------------------
 int bls_fail(bls_ctx *ctx, int code, const char *what);
 int bls_fail_hip(bls_ctx *ctx, hipError_t e, const char *what);
-int bls_commit(bls_ctx *ctx);   // upload descriptor tables if needed; requires every shard
+int bls_ready(bls_ctx *ctx);    // BLS_OK when the descriptor tables on the device are current (bls_commit)
+size_t bls_desc_size(const bls_ctx *ctx);
 
 #define BLS_HIP(ctx, call)                                         \
     do {                                                           \

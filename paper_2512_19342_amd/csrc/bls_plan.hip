@@ -312,7 +312,7 @@ __global__ __launch_bounds__(kThreads) void plan_scatter_runs(DevDesc dd, const 
             for (int k = 0; k < kPer; ++k) {
                 const int64_t i = i0 + k * kThreads;
                 if (i < len) {
-                    if (v[k] < 0 || v[k] >= rows) { flag_error(dd); v[k] = 0; }
+                    if (v[k] < 0 || v[k] >= rows) { flag_error(dd); v[k] = -1; }   // the pool skips negative rows
                     ridx[dst + i] = v[k];
                     if (w_in) w_out[dst + i] = w_in[lo + i];
                     if (perm) perm[lo + i] = dst + i + to_send;

@@ -16,7 +16,6 @@
 // next block of row numbers be fetched while the current one is consumed, and evens out
 // the lengths of the streams that share a wavefront.
 #include <algorithm>
-#include <cstdlib>
 #include <type_traits>
 
 #include "bls_internal.h"
@@ -443,12 +442,6 @@ __global__ __launch_bounds__(kThreads) void pool_rows_generic(DevDesc dd, const 
     }
 }
 
-int env_int(const char *name, int dflt)
-{
-    const char *v = getenv(name);
-    return v && *v ? atoi(v) : dflt;
-}
-
 template <int G, int DT, int VB, int U>
 void launch_rows(const bls_ctx *ctx, const int64_t *ridx, const float *rw, const int64_t *segoff, int64_t nnz, float *Y, int to_slot, int q0, int qn, hipStream_t st)
 {
@@ -459,18 +452,18 @@ void launch_rows(const bls_ctx *ctx, const int64_t *ridx, const float *rw, const
         const int64_t mean = nnz / std::max<int64_t>(1, ctx->nseg) + 1;
         int nb = 1;
         while (nb * 2 < G && nb * 2 <= 16 && nb * mean < 96) nb *= 2;
-        nb = env_int("BLS_POOL_NB", nb);
+        if (ctx->tune_segs > 0) nb = ctx->tune_segs;
         nb = std::max(1, std::min(nb, G - 1));
         const int64_t n_max = ctx->B / ctx->P + (ctx->B % ctx->P ? 1 : 0);
         const uint32_t chunks = (uint32_t)((n_max + nb - 1) / nb);
         const int64_t groups = (int64_t)chunks * ctx->P;
         const uint32_t wgx = (uint32_t)((groups + per_block - 1) / per_block);
-        const bool xcd = env_int("BLS_POOL_XCD", 1) != 0;
+        const bool xcd = ctx->tune_xcd != 0;
         const dim3 grid = xcd ? dim3((unsigned)((uint64_t)((qn + 7) / 8) * 8u * wgx)) : dim3(wgx, qn);
         const uint32_t deal = xcd ? wgx : 0u;
         // 32-bit row positions unless some shard is too large for them
         const int64_t row_stride = stride_bytes(DT, ctx->D);
-        bool wide = env_int("BLS_POOL_WIDE", 0) != 0;
+        bool wide = ctx->tune_wide == 1;
         for (int q = q0; q < q0 + qn; ++q) wide = wide || ctx->q_rows[q] * (row_stride / VB) >= 0xffffffffLL;
         if (rw) {
             if (wide) pool_stream<G, DT, VB, UU, true, true><<<grid, kThreads, 0, st>>>(ctx->desc, ridx, rw, segoff, nnz, Y, to_slot, nb, chunks, deal, q0, qn);
@@ -519,9 +512,8 @@ bool dispatch_rows(const bls_ctx *ctx, int vb, int lanes, const int64_t *ridx, c
 int bls_launch_pool(bls_ctx *ctx, const int64_t *ridx, const float *rw, const int64_t *segoff, int64_t nnz, float *Y, int to_slot, int q0, int qn, hipStream_t st)
 {
     const int64_t row_bytes = payload_bytes(ctx->dtype, ctx->D);
-    // bytes per lane and row: 16 when the row length allows; BLS_POOL_VB overrides (for tests)
-    int vb = env_int("BLS_POOL_VB", 16);
-    if (vb != 16 && vb != 8 && vb != 4) vb = 16;
+    // bytes per lane and row: 16 when the row length allows, unless bls_set_pool_tuning says otherwise
+    int vb = ctx->tune_lane_bytes ? ctx->tune_lane_bytes : 16;
     while (vb > 4 && row_bytes % vb != 0) vb >>= 1;          // lanes must split the row evenly
     while (vb < 16 && row_bytes > 64 * (int64_t)vb) vb <<= 1; // and 64 of them must cover it
     bool done = false;

@@ -31,15 +31,16 @@ class Pipeline:
             if w.part_kind == bls.BLS_TABLE_WISE:
                 c.bls_set_shard(t, w.table_owner[t], tab)
             else:
-                rps = -(-w.rows[t] // w.P)
                 for d in range(w.P):
-                    lo, hi = min(d * rps, w.rows[t]), min((d + 1) * rps, w.rows[t])
-                    if hi == lo:
+                    lo, n = c.bls_shard_range(t, d)     # the partition rule is the library's
+                    if n == 0:
                         continue                        # empty shard: nothing to hand over
-                    shard = tab[lo:hi]
+                    shard = tab[lo:lo + n]
                     if shard.data_ptr() % 16:
                         shard = shard.clone()
                     c.bls_set_shard(t, d, shard)
+        self.desc = torch.empty(c.bls_desc_bytes(), dtype=torch.uint8, device=dev)
+        c.bls_commit(self.desc)
         sz = c.bls_sizes(self.max_nnz)
         pp = w.P * w.P
         i64 = dict(dtype=torch.int64, device=dev)

@@ -28,12 +28,14 @@ def bits(a):
     return a.view(np.uint32) if a.dtype == np.float32 else a
 
 
-def run_gpu(w, tabs_cpu, batches, want_perm=True):
+def run_gpu(w, tabs_cpu, batches, want_perm=True, tuning=None):
     from paper_2512_19342_amd.runner import Pipeline
     dev = torch.device("cuda:0")
     tabs = [t.to(dev) for t in tabs_cpu]
     max_nnz = max(int(off[-1]) for _, off in batches)
     pipe = Pipeline(w, tabs, max_nnz, want_perm=want_perm)
+    if tuning:
+        pipe.ctx.bls_set_pool_tuning(**tuning)
     res = []
     for ix, off in batches:
         nnz = int(off[-1])
@@ -246,10 +248,19 @@ def test_bad_inputs_are_flagged_not_faulted():
                 boff[10] = boff[12] + 5
             else:
                 boff[-1] = nnz + 1000
-            pipe.step(bix.to(dev), boff.to(dev), nnz, pipe.new_out())
+            bad_out = pipe.new_out()
+            pipe.step(bix.to(dev), boff.to(dev), nnz, bad_out)
             with pytest.raises(B.BlsError) as e:
                 pipe.ctx.bls_check()
             assert e.value.code == B.BLS_ERANGE, how
+            if how.startswith("index"):
+                # the bad lookup adds nothing to its bag: the output is that of the batch without it
+                at = nnz // 2 if how == "index_high" else 5
+                gix = np.delete(ix.numpy(), at)
+                goff = off.numpy().copy()
+                goff[goff > at] -= 1
+                want = oracle.pipeline(case_of(w), [t.cpu().numpy() for t in tabs], gix, goff)["Out"]
+                assert np.array_equal(bits(bad_out.cpu().numpy()), bits(want)), (cfg, how)
         # and the context still works afterwards
         out = pipe.new_out()
         pipe.step(ix.to(dev), off.to(dev), nnz, out)
@@ -280,6 +291,22 @@ def test_host_side_argument_errors():
         c.bls_embbag_pool(z, z, 0, y)
     assert e.value.code == B.BLS_EINVAL
     c.bls_set_shard(1, 1, torch.zeros(6, 4, device="cuda"))
+    with pytest.raises(B.BlsError) as e:                  # every shard set, but the tables are not on the device yet
+        c.bls_embbag_pool(z, z, 0, y)
+    assert e.value.code == B.BLS_EINVAL and "bls_commit" in c.bls_last_error()
+    with pytest.raises(B.BlsError) as e:
+        c.bls_commit(torch.zeros(8, dtype=torch.uint8, device="cuda"))
+    assert e.value.code == B.BLS_ENOSPC
+    desc = torch.empty(c.bls_desc_bytes(), dtype=torch.uint8, device="cuda")
+    c.bls_commit(desc)
+    c.bls_embbag_pool(z, z, 0, y)
+    c.bls_set_shard(1, 1, torch.zeros(6, 4, device="cuda"))   # a shard replaced: commit again
+    with pytest.raises(B.BlsError) as e:
+        c.bls_embbag_pool(z, z, 0, y)
+    assert e.value.code == B.BLS_EINVAL
+    c.bls_commit(desc)
+    c.bls_embbag_pool(z, z, 0, y)
+    c.bls_check()
     with pytest.raises(B.BlsError) as e:
         c.bls_set_ring(torch.zeros(3, device="cuda"))
     assert e.value.code == B.BLS_ENOSPC
@@ -289,14 +316,10 @@ def test_host_side_argument_errors():
 
 
 @pytest.mark.parametrize("vb,nb,xcd", [(16, 1, 0), (16, 3, 1), (16, 16, 0), (8, 0, 1), (8, 7, 0), (4, 0, 0), (4, 2, 1)])
-def test_pool_launch_variants(vb, nb, xcd, monkeypatch):
-    """The overrides pick other lane widths, segments per group, grid mappings and row-position
+def test_pool_launch_variants(vb, nb, xcd):
+    """bls_set_pool_tuning picks other lane widths, segments per group, grid mappings and row-position
     widths; every variant must give the same bits."""
-    monkeypatch.setenv("BLS_POOL_VB", str(vb))
-    monkeypatch.setenv("BLS_POOL_XCD", str(xcd))
-    monkeypatch.setenv("BLS_POOL_WIDE", str(1 - xcd))
-    if nb:
-        monkeypatch.setenv("BLS_POOL_NB", str(nb))
+    tuning = dict(lane_bytes=vb, segments_per_group=nb, xcd_map=xcd, wide_positions=1 - xcd)
     works = [synth.workload(c, "small") for c in (3, 4, 5)]
     for w in works[:2]:
         w.values = "gauss"
@@ -307,7 +330,7 @@ def test_pool_launch_variants(vb, nb, xcd, monkeypatch):
     for w in works:
         tabs = [synth.make_table(w, t) for t in range(w.T)]
         batches = [synth.make_batch(w, 5)]
-        got, _ = run_gpu(w, tabs, batches, want_perm=False)
+        got, _ = run_gpu(w, tabs, batches, want_perm=False, tuning=tuning)
         c = case_of(w)
         ref = oracle.pipeline(c, [t.numpy() for t in tabs], batches[0][0].numpy(), batches[0][1].numpy())
         for k in ("Y", "Out"):
@@ -543,8 +566,7 @@ def test_step_can_be_captured_in_a_graph_and_replayed():
     pipe = Pipeline(w, [t.to(dev) for t in tabs_cpu], nnz)
     out = pipe.new_out()
     s_ix, s_off = batches[0][0].to(dev).clone(), batches[0][1].to(dev).clone()
-    pipe.step(s_ix, s_off, nnz, out)                            # first use uploads the descriptor tables
-    torch.cuda.synchronize()
+    torch.cuda.synchronize()                                    # no eager step first: no call allocates or uploads
     graph, st = torch.cuda.CUDAGraph(), torch.cuda.Stream()
     st.wait_stream(torch.cuda.current_stream())
     with torch.cuda.stream(st):

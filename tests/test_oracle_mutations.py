@@ -58,6 +58,18 @@ MUTATIONS = {
     "e4m3 exponent bias": ("uint32_t bits = ((uint32_t)(e + 120) << 23) | ((uint32_t)m << 20);", "uint32_t bits = ((uint32_t)(e + 119) << 23) | ((uint32_t)m << 20);"),
     "e4m3 subnormals flushed": ("if (e == 0) mag = (float)m * 0.001953125f;", "if (e == 0) mag = 0.0f;"),
     "e4m3 sign dropped": ("return (v & 0x80u) ? -mag : mag;", "return mag;"),
+    "single-bag sum accumulated in double": ("for (j = 0; j < n; ++j) { a32 += rows_nd[j * D + c]; a64 += (double)rows_nd[j * D + c]; }\n        if (out32) out32[c] = a32;",
+                                             "for (j = 0; j < n; ++j) { a32 += rows_nd[j * D + c]; a64 += (double)rows_nd[j * D + c]; }\n        if (out32) out32[c] = (float)a64;"),
+    "single-bag sum in reverse order": ("for (j = 0; j < n; ++j) { a32 += rows_nd[j * D + c];", "for (j = n - 1; j >= 0; --j) { a32 += rows_nd[j * D + c];"),
+    "single-bag sum drops the last row": ("for (j = 0; j < n; ++j) { a32 += rows_nd[j * D + c];", "for (j = 0; j + 1 < n; ++j) { a32 += rows_nd[j * D + c];"),
+    "single-bag sum reads the neighbouring column": ("{ a32 += rows_nd[j * D + c]; a64 += (double)rows_nd[j * D + c]; }",
+                                                     "{ a32 += rows_nd[j * D + (c + 1) % D]; a64 += (double)rows_nd[j * D + (c + 1) % D]; }"),
+    "tolerance mass over one lookup too many": ("double a = 0.0;\n                for (l = offsets[g]; l < offsets[g + 1]; ++l) {\n                    double x",
+                                                "double a = 0.0;\n                for (l = offsets[g]; l < offsets[g + 1] + (g + 1 < (int64_t)T * B); ++l) {\n                    double x"),
+    "tolerance mass over the next bag too": ("double a = 0.0;\n                for (l = offsets[g]; l < offsets[g + 1]; ++l) {\n                    double x",
+                                             "double a = 0.0;\n                for (l = offsets[g]; l < offsets[g + 1 < (int64_t)T * B ? g + 2 : g + 1]; ++l) {\n                    double x"),
+    "tolerance mass without the absolute value": ("a += x < 0 ? -x : x;", "a += x;"),
+    "tolerance mass doubled": ("mass[((int64_t)b * T + t) * D + c] = a;", "mass[((int64_t)b * T + t) * D + c] = 2.0 * a;"),
     "half subnormals flushed": ("if (m == 0) bits = sign;\n        else {", "if (m >= 0) bits = sign;\n        else {"),
 }
 
@@ -84,6 +96,10 @@ PINS = [
     lambda: pins.test_mlp_layer_brute_force_and_closed_forms(),
     lambda: pins.test_mlp_layer_against_torch_linear(2),
     lambda: pins.test_interact_brute_force_order_and_torch(),
+    lambda: pins.test_bag_sum_is_the_ordered_fp32_sum(70),
+    lambda: pins.test_bag_sum_signed_zero_and_exact_cases(),
+    lambda: pins.test_absmass_is_the_sum_of_magnitudes(pins.TINY[1], "fp32"),
+    lambda: pins.test_absmass_bounds_the_plain_sums_tightly(),
 ]
 
 

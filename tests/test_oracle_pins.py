@@ -824,3 +824,104 @@ def test_f8rq_worked_example_and_decoded_tables():
     ix, off = synth.make_batch(wg, 0)
     o64, o32 = oracle.embbag_plain(case_of(wg), tg, ix.numpy(), off.numpy())
     assert np.array_equal(o64, o32.astype(np.float64)) and np.abs(o64).max() > 0.1
+
+
+# ----------------------------------------------------------------------------- single-bag sum and the tolerance scale
+
+def _ordered_fp32_sum(rows):
+    """One fp32 accumulator from +0, rows added in order: spelled out with numpy scalars."""
+    acc = np.zeros(rows.shape[1], np.float32)
+    for r in rows:
+        acc = (acc + r.astype(np.float32)).astype(np.float32)
+    return acc
+
+
+@pytest.mark.parametrize("n", [0, 1, 2, 70])
+def test_bag_sum_is_the_ordered_fp32_sum(n):
+    """orc_bag_sum stands in for the whole-table oracle at sizes the host cannot hold (Listing 1,
+    apply_emb on one bag): bit for bit an ordered numpy fp32 loop, bit for bit orc_embbag_plain on
+    the same rows, float64 output = numpy's float64 sum; Gaussian values, so that a reordered,
+    pairwise or double-accumulated sum would show in the last bit."""
+    rng = np.random.default_rng(40 + n)
+    D = 12
+    rows = (rng.normal(0.0, 0.01, size=(n, D)) * rng.choice([1.0, 64.0, 1 / 64.0], size=(n, 1))).astype(np.float32)
+    o32, o64 = oracle.bag_sum(rows)
+    want = _ordered_fp32_sum(rows)
+    assert np.array_equal(o32.view(np.uint32), want.view(np.uint32))
+    assert np.allclose(o64, rows.astype(np.float64).sum(axis=0), rtol=1e-15, atol=1e-300)
+    if n == 0:
+        assert not o32.any() and not np.signbit(o32).any() and not o64.any()
+    else:
+        mini = oracle.Case(1, 1, D, 1, 0, [n], [0], 0)
+        p64, p32 = oracle.embbag_plain(mini, [rows], np.arange(n), np.array([0, n]))
+        assert np.array_equal(p32.reshape(D).view(np.uint32), o32.view(np.uint32))
+        assert np.array_equal(p64.reshape(D), o64)
+    if n == 70:                                     # the values are order-sensitive: another order gives other bits
+        assert not np.array_equal(_ordered_fp32_sum(rows[::-1]).view(np.uint32), want.view(np.uint32))
+        assert not np.array_equal(o64.astype(np.float32).view(np.uint32), want.view(np.uint32))
+    # column c of the result depends on column c of the rows only, and on every row
+    if n >= 2:
+        probe = rows.copy()
+        probe[n // 2, 3] += np.float32(1.0)
+        q32, _ = oracle.bag_sum(probe)
+        changed = q32.view(np.uint32) != o32.view(np.uint32)
+        assert changed[3] and not np.delete(changed, 3).any()
+
+
+def test_bag_sum_signed_zero_and_exact_cases():
+    """A bag of -0.0 rows gives +0.0 (the accumulator starts at +0); powers of two add exactly;
+    a large term followed by small ones loses them in fp32 but not in float64."""
+    z = np.full((3, 2), -0.0, np.float32)
+    o32, o64 = oracle.bag_sum(z)
+    assert not np.signbit(o32).any() and not o32.any()
+    rows = np.array([[2.0 ** -3], [2.0 ** -5], [2.0 ** 4]], np.float32)
+    o32, o64 = oracle.bag_sum(rows)
+    assert o32[0] == 16.15625 and o64[0] == 16.15625
+    rows = np.array([[1.0]] + [[2.0 ** -25]] * 8, np.float32)
+    o32, o64 = oracle.bag_sum(rows)
+    assert o32[0] == 1.0 and o64[0] == 1.0 + 8 * 2.0 ** -25           # in order: every small term is rounded away
+    o32r, _ = oracle.bag_sum(rows[::-1].copy())
+    assert o32r[0] == np.float32(1.0 + 2.0 ** -22)                    # small terms first: they survive
+
+
+@pytest.mark.parametrize("spec", TINY)
+@pytest.mark.parametrize("dtype", ["fp32", "fp16"])
+def test_absmass_is_the_sum_of_magnitudes(spec, dtype):
+    """orc_embbag_absmass scales every tolerance assertion (|x - exact| <= tol * sum |terms|): it must
+    EQUAL numpy's float64 sum of |row| over exactly the bag's lookups - a mass summed over a wider
+    range, or over the wrong table or column, would make every such assertion pass too easily."""
+    w = synth.custom("tiny", k=1, values="gauss", seed=17, table_dtype=dtype, **spec)
+    ix, off = (x.numpy() for x in synth.make_batch(w, 0))
+    tabs = np_tables(w)
+    mass = oracle.embbag_absmass(case_of(w), tabs, ix, off)
+    assert mass.shape == (w.B, w.T, w.D) and mass.dtype == np.float64
+    for t in range(w.T):
+        for b in range(w.B):
+            g = t * w.B + b
+            rows = tabs[t][ix[off[g]:off[g + 1]]].astype(np.float64).reshape(-1, w.D)
+            want = np.abs(rows).sum(axis=0)
+            assert np.allclose(mass[b, t], want, rtol=1e-15, atol=0.0), (t, b)
+            if off[g + 1] == off[g]:
+                assert not mass[b, t].any()
+    # duplicates count as often as they occur; signs do not cancel
+    c1 = oracle.Case(1, 1, 2, 2, 0, [3], [0], 0)
+    tab = np.array([[1.0, -2.0], [-4.0, 8.0], [0.5, 0.25]], np.float32)
+    m = oracle.embbag_absmass(c1, [tab], np.array([0, 1, 1, 2]), np.array([0, 3, 4]))
+    assert np.array_equal(m, np.array([[[9.0, 18.0]], [[0.5, 0.25]]]))
+    o64, _ = oracle.embbag_plain(c1, [tab], np.array([0, 1, 1, 2]), np.array([0, 3, 4]))
+    assert np.array_equal(o64, np.array([[[-7.0, 14.0]], [[0.5, 0.25]]]))
+
+
+def test_absmass_bounds_the_plain_sums_tightly():
+    """|sum| <= mass with equality for one-signed bags; and mass is no more than that: for bags of
+    non-negative values mass == the float64 sum itself."""
+    w = synth.custom("pos", P=2, T=2, D=4, k=1, B=6, rows=[9, 5], part_kind=0, bag=("uniform", 0, 7), seed=3)
+    ix, off = (x.numpy() for x in synth.make_batch(w, 2))
+    rng = np.random.default_rng(8)
+    tabs = [np.abs(rng.normal(0, 1, size=(r, 4))).astype(np.float32) for r in w.rows]
+    c = case_of(w)
+    o64, _ = oracle.embbag_plain(c, tabs, ix, off)
+    assert np.array_equal(oracle.embbag_absmass(c, tabs, ix, off), o64)
+    neg = [-t for t in tabs]
+    o64n, _ = oracle.embbag_plain(c, neg, ix, off)
+    assert np.array_equal(oracle.embbag_absmass(c, neg, ix, off), -o64n)
