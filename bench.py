@@ -13,6 +13,7 @@ import argparse
 import json
 import os
 import re
+import statistics
 import sys
 import time
 
@@ -21,6 +22,7 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 PEAK_HBM_GBPS = 8000.0          # MI355X published HBM3E peak
+PEAK_L1_GBPS = 256 * 64 * 2.4   # vector L1 path: 256 compute units x 64 B per clock x 2.4 GHz
 
 WORKLOAD_TEXT = {
     1: "cfg1: 8 tables x 10000 rows x dim 16 fp32, batch 128, pooling 1, uniform, P=2 table-wise round-robin, k=1",
@@ -50,14 +52,37 @@ def stage_bytes(w, nnz: int) -> dict:
     }
 
 
-def recorded_traffic(cfg: int):
-    """HBM bytes per pool launch from the committed rocprofv3 counter summary, if present."""
-    path = os.path.join(ROOT, "profiles", f"pool_stream_cfg{cfg}_pmc.txt")
+def recorded_traffic(cfg: int, uniform: bool = False):
+    """(HBM bytes per pool launch, file) from the committed rocprofv3 counter summary of this workload
+    (FETCH_SIZE and WRITE_SIZE scaled by a plain copy's readings), or None if there is none."""
+    name = f"pool_stream_cfg{cfg}{'_uniform' if uniform else ''}_pmc.txt"
     try:
-        m = re.search(r"^traffic_bytes_per_launch:\s*([0-9.eE+]+)", open(path).read(), re.M)
-        return float(m.group(1)) if m else None
+        m = re.search(r"^traffic_bytes_per_launch:\s*([0-9.eE+]+)", open(os.path.join(ROOT, "profiles", name)).read(), re.M)
+        return (float(m.group(1)), "profiles/" + name) if m else None
     except OSError:
         return None
+
+
+def pool_roofline(algorithmic_bytes: int, ms: dict, recorded) -> dict:
+    """Roofline entry of the pool kernel.  achieved = algorithmic bytes per launch over the mean
+    launch time between two HIP events.  When that rate is above what HBM can deliver the rows
+    are coming out of the caches, and the ceiling that applies is the vector L1 path (64 B per
+    clock per compute unit); the HBM side is then given by the counter traffic alone."""
+    achieved = algorithmic_bytes / (ms["mean"] * 1e-3) / 1e9
+    cached = achieved > PEAK_HBM_GBPS
+    peak = PEAK_L1_GBPS if cached else PEAK_HBM_GBPS
+    traffic, src = recorded if recorded else (None, None)
+    r = {"bound": "l1" if cached else "hbm", "kernel": "pool_stream (bls_embbag_pool)", "achieved": achieved, "peak": peak,
+         "unit": "GB/s", "frac": achieved / peak, "traffic": traffic, "traffic_source": src,
+         "algorithmic_bytes_per_launch": algorithmic_bytes, "avg_launch_ms": ms["mean"],
+         "median_launch_ms": ms["median"], "min_launch_ms": ms["min"],
+         "peak_note": ("vector L1 path: 256 compute units x 64 B per clock x 2.4 GHz; the algorithmic rate is above the "
+                       "8 TB/s HBM peak because popular rows are served by L1 and L2") if cached else "MI355X HBM3E peak"}
+    if traffic is not None:
+        r["hbm_traffic_gbps"] = traffic / (ms["mean"] * 1e-3) / 1e9
+        r["hbm_traffic_frac_of_peak"] = r["hbm_traffic_gbps"] / PEAK_HBM_GBPS
+        r["algorithmic_over_traffic"] = algorithmic_bytes / traffic
+    return r
 
 
 def cpu_baseline(w, tabs_gpu, batches, budget_s: float) -> dict:
@@ -66,10 +91,9 @@ def cpu_baseline(w, tabs_gpu, batches, budget_s: float) -> dict:
     import oracle
     tabs = [t.cpu().numpy() for t in tabs_gpu]
     case = oracle.Case(w.P, w.T, w.D, w.B, w.part_kind, w.rows, w.table_owner, w.dtype_code)
-    host = [(ix.cpu().numpy(), off.cpu().numpy()) for ix, off in batches]
     spent, nnz, n = 0.0, 0, 0
     while spent < budget_s and n < 64:
-        ix, off = host[n % len(host)]
+        ix, off = (x.cpu().numpy() for x in batches[n % len(batches)])
         t0 = time.perf_counter()
         oracle.pipeline(case, tabs, ix, off)
         spent += time.perf_counter() - t0
@@ -337,7 +361,11 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", type=int, default=4, help="benchmark workload 1..6 (default 4, the target)")
     ap.add_argument("--size", default="full", choices=["full", "small"])
-    ap.add_argument("--batches", type=int, default=4, help="distinct pre-generated batches, rotated")
+    ap.add_argument("--batches", type=int, default=16, help="distinct pre-generated batches, rotated")
+    ap.add_argument("--no-uniform-control", action="store_true", help="skip the uniform-index control run")
+    ap.add_argument("--flat-rows", action="store_true",
+                    help="experiment: every table gets the same number of rows (same total), so that uniform indices leave "
+                         "no small table for the caches to hold")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="CPU time to spend on the oracle baseline")
     ap.add_argument("--index-dist", default=None, choices=[None, "uniform"],
@@ -387,6 +415,8 @@ def main() -> int:
         w.table_dtype = args.table_dtype
     if args.rows_cap:
         w.rows = [min(r, args.rows_cap) for r in w.rows]
+    if args.flat_rows:
+        w.rows = [sum(w.rows) // w.T] * w.T
     def note(msg: str):
         print(f"[bench] {msg}", file=sys.stderr, flush=True)
 
@@ -406,38 +436,60 @@ def main() -> int:
     c = pipe.ctx
     names = ["plan", "pool", "pack", "exchange", "unpack"]
 
-    def one_step(i: int, ev=None):
+    def timed_run(bts, nz, steps: int, warmup: int) -> dict:
+        """`warmup` untimed and `steps` timed staged steps over the batches `bts`; HIP events on the
+        launch stream around every stage of every timed step."""
+        def one_step(i: int, ev=None):
+            ix, off = bts[i % len(bts)]
+            nnz = nz[i % len(bts)]
+            if ev: ev[0].record()
+            c.bls_plan(ix, off, nnz, pipe.sendcounts, pipe.sdispls, pipe.recvcounts, pipe.rdispls,
+                       pipe.ridx, pipe.segoff, None, pipe.ws)
+            if ev: ev[1].record()
+            c.bls_embbag_pool(pipe.ridx, pipe.segoff, nnz, pipe.pooled)
+            if ev: ev[2].record()
+            c.bls_pack(pipe.pooled, pipe.send)
+            if ev: ev[3].record()
+            it, slot = c.bls_ring_advance()
+            c.bls_alltoallv_local(pipe.send, slot)
+            if ev: ev[4].record()
+            c.bls_unpack(it, out)
+            if ev: ev[5].record()
+            return nnz
+
+        for i in range(warmup):
+            one_step(i)
+        c.bls_check()
+        events = [[torch.cuda.Event(enable_timing=True) for _ in range(6)] for _ in range(steps)]
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        lookups = 0
+        for i in range(steps):
+            lookups += one_step(warmup + i, events[i])
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+        c.bls_check()
+        per_stage = {n: [e[k].elapsed_time(e[k + 1]) for e in events] for k, n in enumerate(names)}
+        per_step = [e[0].elapsed_time(e[5]) for e in events]
+        stat = lambda v: {"mean": statistics.fmean(v), "median": statistics.median(v), "min": min(v)}
+        return {"dt": dt, "lookups": lookups, "stage_ms": {n: statistics.fmean(v) for n, v in per_stage.items()},
+                "stage_ms_stats": {n: stat(v) for n, v in per_stage.items()}, "step_ms_stats": stat(per_step)}
+
+    run = timed_run(batches, nnzs, args.steps, args.warmup)
+    dt, lookups = run["dt"], run["lookups"]
+    note(f"{args.steps} timed steps: {dt / args.steps * 1e3:.3f} ms per step")
+
+    def one_step(i: int):
         ix, off = batches[i % len(batches)]
         nnz = nnzs[i % len(batches)]
-        if ev: ev[0].record()
         c.bls_plan(ix, off, nnz, pipe.sendcounts, pipe.sdispls, pipe.recvcounts, pipe.rdispls,
                    pipe.ridx, pipe.segoff, None, pipe.ws)
-        if ev: ev[1].record()
         c.bls_embbag_pool(pipe.ridx, pipe.segoff, nnz, pipe.pooled)
-        if ev: ev[2].record()
         c.bls_pack(pipe.pooled, pipe.send)
-        if ev: ev[3].record()
         it, slot = c.bls_ring_advance()
         c.bls_alltoallv_local(pipe.send, slot)
-        if ev: ev[4].record()
         c.bls_unpack(it, out)
-        if ev: ev[5].record()
         return nnz
-
-    for i in range(args.warmup):
-        one_step(i)
-    c.bls_check()
-    note("warm-up done")
-    events = [[torch.cuda.Event(enable_timing=True) for _ in range(6)] for _ in range(args.steps)]
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    lookups = 0
-    for i in range(args.steps):
-        lookups += one_step(args.warmup + i, events[i])
-    torch.cuda.synchronize()
-    dt = time.perf_counter() - t0
-    c.bls_check()
-    note(f"{args.steps} timed steps: {dt / args.steps * 1e3:.3f} ms per step")
 
     copy_gbps = dtf = dtr = fused_lookups = None
     if not args.timed_only:
@@ -509,15 +561,38 @@ def main() -> int:
     if not args.timed_only or args.dense:
         dlrm = dense_section(args, w, pipe, batches, nnzs, note)
 
-    stage_ms = {n: sum(e[k].elapsed_time(e[k + 1]) for e in events) / args.steps for k, n in enumerate(names)}
+    stage_ms = run["stage_ms"]
     mean_nnz = lookups / args.steps
     sb = stage_bytes(w, int(mean_nnz))
-    pool_s = stage_ms["pool"] * 1e-3
-    achieved = sb["pool"] / pool_s / 1e9
     a_staged = sum(sb.values())
     pool_pack_gbps = (sb["pool"] + sb["pack"]) / ((stage_ms["pool"] + stage_ms["pack"]) * 1e-3) / 1e9
+    plain = args.size == "full" and not args.table_dtype and not args.bag_fixed and not args.rows_cap and not args.flat_rows
+    roofline = pool_roofline(sb["pool"], run["stage_ms_stats"]["pool"],
+                             recorded_traffic(args.config, uniform=bool(args.index_dist)) if plain else None)
 
-    traffic = recorded_traffic(args.config) if not args.index_dist and args.size == "full" and not args.table_dtype else None
+    # cache-defeating control: the same tables and bag lengths with uniform indices, the same staged step
+    control = None
+    if w.index_dist[0] == "zipf" and not args.timed_only and not args.no_uniform_control:
+        wu = synth.workload(args.config, args.size)
+        wu.rows, wu.table_dtype, wu.bag, wu.index_dist = w.rows, w.table_dtype, w.bag, ("uniform",)
+        ub = [synth.make_batch(wu, it, dev) for it in range(args.batches)]
+        un = [int(off[-1].item()) for _, off in ub]
+        urun = timed_run(ub, un, args.steps, args.warmup)
+        usb = stage_bytes(w, int(urun["lookups"] / args.steps))
+        ums = urun["stage_ms"]
+        control = {
+            "what": "the same tables, bag lengths and staged step with uniform indices: no popular rows for the caches to hold",
+            "ms_per_step": urun["dt"] / args.steps * 1e3, "lookups_per_s": urun["lookups"] / urun["dt"],
+            "stage_ms": ums, "stage_ms_stats": urun["stage_ms_stats"],
+            "roofline": pool_roofline(usb["pool"], urun["stage_ms_stats"]["pool"],
+                                      recorded_traffic(args.config, uniform=True) if plain else None),
+            "pool_plus_pack_gbps": (usb["pool"] + usb["pack"]) / ((ums["pool"] + ums["pack"]) * 1e-3) / 1e9,
+        }
+        control["pool_plus_pack_frac_of_hbm_peak"] = control["pool_plus_pack_gbps"] / PEAK_HBM_GBPS
+        note(f"uniform-index control: {control['ms_per_step']:.3f} ms per step, pool {ums['pool']:.3f} ms = "
+             f"{control['roofline']['achieved']:.0f} GB/s of algorithmic bytes")
+        del ub
+
     res = {
         "metric": "embedding lookups/sec + achieved HBM GB/s (bucket+pool+pack), 1 MI355X",
         "value": lookups / dt, "unit": "lookups/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -529,19 +604,18 @@ def main() -> int:
                    + (" [uniform-index control]" if args.index_dist else "")
                    + (f" [every bag {args.bag_fixed} lookups]" if args.bag_fixed else "")
                    + (f" [tables capped at {args.rows_cap} rows]" if args.rows_cap else "")
+                   + (" [all tables the same size]" if args.flat_rows else "")
                    + (f" [tables stored as {args.table_dtype}]" if args.table_dtype else ""),
                    "P": w.P, "T": w.T, "D": w.D, "B": w.B, "k": w.k, "lookups_per_step": mean_nnz,
-                   "table_bytes": w.table_bytes(), "distinct_batches": len(batches)},
-        "roofline": {"bound": "hbm", "kernel": "pool_stream (bls_embbag_pool)", "achieved": achieved,
-                     "peak": PEAK_HBM_GBPS, "unit": "GB/s", "frac": achieved / PEAK_HBM_GBPS,
-                     "traffic": traffic,
-                     # what crossed the fabric, from the counters: the rest of the algorithmic bytes came out of L1 / L2
-                     "traffic_gbps": None if traffic is None else traffic / pool_s / 1e9,
-                     "traffic_frac": None if traffic is None else traffic / pool_s / 1e9 / PEAK_HBM_GBPS,
-                     "algorithmic_bytes_per_launch": sb["pool"], "avg_launch_ms": stage_ms["pool"]},
-        "hbm_gbps": {"whole_path_staged": a_staged / (dt / args.steps) / 1e9, "pool_plus_pack": pool_pack_gbps,
-                     "pool_plus_pack_frac_of_peak": pool_pack_gbps / PEAK_HBM_GBPS},
+                   "table_bytes": w.table_bytes(), "distinct_batches": args.batches},
+        "roofline": roofline,
+        "uniform_control": control,
+        "step_ms_stats": run["step_ms_stats"],
+        "hbm_gbps": {"note": "algorithmic bytes over time; above the HBM peak when popular rows are served by L1 / L2",
+                     "whole_path_staged": a_staged / (dt / args.steps) / 1e9, "pool_plus_pack": pool_pack_gbps,
+                     "pool_plus_pack_over_hbm_peak": pool_pack_gbps / PEAK_HBM_GBPS},
         "stage_ms": stage_ms,
+        "stage_ms_stats": run["stage_ms_stats"],
         "stage_gbps": {n: sb[n] / (stage_ms[n] * 1e-3) / 1e9 for n in names},
         "fused_owner_side": None if dtf is None else {
             "entry_point": "bls_plan + bls_embbag_pool_put + bls_unpack", "ms_per_step": dtf / args.steps * 1e3,
