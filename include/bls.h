@@ -156,6 +156,22 @@ int bls_plan(bls_ctx *ctx, const int64_t *d_indices, const int64_t *d_offsets, i
              int64_t *d_ridx, int64_t *d_segoff, int64_t *d_perm, void *d_ws, size_t ws_bytes, void *hip_stream);
 
 /*
+ * bls_plan for callers that cannot allocate device memory (code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc): the same work and the same outputs, bit for bit,
+ * with the scratch taken from a 1 MiB array that is part of the library's device code (one copy
+ * per GPU, held until the process ends) instead of d_ws.  Calls nothing that allocates or frees.
+ * BLS_ENOSPC when the problem needs more than that (bls_sizes' plan_ws_bytes > 1 MiB, i.e. beyond
+ * about 10^8 segments F*T*B): use bls_plan then.  All calls on one GPU share the one array, from
+ * every context and stream: two calls that may run at the same time on one GPU race - order them
+ * (one stream, or events).  The array needs no clearing between calls: every word a call reads it
+ * has written first.  The first call on a device looks the array's address up (no allocation, but
+ * not a stream operation): make it before starting a capture.
+ */
+int bls_plan_noalloc(bls_ctx *ctx, const int64_t *d_indices, const int64_t *d_offsets, int64_t nnz,
+                     int64_t *d_sendcounts, int64_t *d_sdispls, int64_t *d_recvcounts, int64_t *d_rdispls,
+                     int64_t *d_ridx, int64_t *d_segoff, int64_t *d_perm, void *hip_stream);
+
+/*
  * EmbeddingBag, sum mode (Listing 1: apply_emb over offsets and indices; the paper's
  * profile shows it dominating the run).  For owner d, local table t_loc and sample b:
  *   Y_d[t_loc][b][:] = sum over the segment's rows of W_{t,d}[ridx[.]][:]

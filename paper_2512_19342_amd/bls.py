@@ -20,7 +20,7 @@ BLS_ACT_NONE, BLS_ACT_RELU, BLS_ACT_SIGMOID = 0, 1, 2
 BLS_TABLE_WISE, BLS_ROW_WISE = 0, 1
 
 EXPORTS = [
-    "bls_create", "bls_destroy", "bls_set_shard", "bls_shard_range", "bls_desc_bytes", "bls_commit", "bls_set_pool_tuning", "bls_sizes", "bls_pooled_counts", "bls_plan", "bls_plan_weighted",
+    "bls_create", "bls_destroy", "bls_set_shard", "bls_shard_range", "bls_desc_bytes", "bls_commit", "bls_set_pool_tuning", "bls_sizes", "bls_pooled_counts", "bls_plan", "bls_plan_noalloc", "bls_plan_weighted",
     "bls_embbag_pool", "bls_embbag_pool_weighted", "bls_embbag_pool_put", "bls_embbag_pool_put_weighted", "bls_pack",
     "bls_set_ring", "bls_ring_advance", "bls_alltoallv_local", "bls_unpack", "bls_unpack_mean", "bls_ring_state",
     "bls_rank_put", "bls_rank_complete", "bls_rank_delay", "bls_mlp_layer", "bls_interact", "bls_unpack_interact", "bls_check", "bls_last_error",
@@ -60,6 +60,7 @@ def lib() -> C.CDLL:
         L.bls_sizes.argtypes = [vp, C.c_int64] + [C.POINTER(C.c_size_t)] * 4
         L.bls_pooled_counts.argtypes = [vp] + [C.POINTER(C.c_int64)] * 4
         L.bls_plan.argtypes = [vp, i64p, i64p, C.c_int64, i64p, i64p, i64p, i64p, i64p, i64p, i64p, vp, C.c_size_t, vp]
+        L.bls_plan_noalloc.argtypes = [vp, i64p, i64p, C.c_int64, i64p, i64p, i64p, i64p, i64p, i64p, i64p, vp]
         L.bls_plan_weighted.argtypes = [vp, i64p, i64p, vp, C.c_int64, i64p, i64p, i64p, i64p, i64p, vp, i64p, i64p, vp,
                                         C.c_size_t, vp]
         L.bls_embbag_pool.argtypes = [vp, i64p, i64p, C.c_int64, vp, vp]
@@ -191,6 +192,10 @@ class Context:
         self._call("bls_plan", _ptr(indices), _ptr(offsets), int(nnz), _ptr(sendcounts), _ptr(sdispls), _ptr(recvcounts),
                    _ptr(rdispls), _ptr(ridx), _ptr(segoff), _ptr(perm), _ptr(ws), ws.numel() * ws.element_size(),
                    _stream(stream))
+
+    def bls_plan_noalloc(self, indices, offsets, nnz, sendcounts, sdispls, recvcounts, rdispls, ridx, segoff, perm, stream=None):
+        self._call("bls_plan_noalloc", _ptr(indices), _ptr(offsets), int(nnz), _ptr(sendcounts), _ptr(sdispls),
+                   _ptr(recvcounts), _ptr(rdispls), _ptr(ridx), _ptr(segoff), _ptr(perm), _stream(stream))
 
     def bls_plan_weighted(self, indices, offsets, weights, nnz, sendcounts, sdispls, recvcounts, rdispls, ridx, rweights,
                           segoff, perm, ws, stream=None):

@@ -5,6 +5,7 @@
 #include <algorithm>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <new>
 
 #include "bls_internal.h"
@@ -323,6 +324,50 @@ extern "C" int bls_plan(bls_ctx *ctx, const int64_t *d_indices, const int64_t *d
     if (!ctx) return BLS_EINVAL;
     return plan_common(ctx, d_indices, d_offsets, nullptr, nnz, d_sendcounts, d_sdispls, d_recvcounts, d_rdispls, d_ridx,
                        nullptr, d_segoff, d_perm, d_ws, ws_bytes, hip_stream);
+}
+
+// ---- bls_plan without a caller workspace ---------------------------------------------------
+// For callers that cannot allocate device memory: the plan's scratch (block sums of the scan, bucket
+// starts) lives in a file-scope device array.  Every GPU the library runs on holds its own copy of
+// the array at its own address, so the address is asked for once per device, with that device
+// current, and host code only ever uses that address - never the array's name, which on the host
+// is a stand-in and not a device pointer.
+namespace {
+constexpr size_t kStaticWsBytes = size_t(1) << 20;            // 1 MiB per device, held until the process ends
+constexpr int kMaxDevices = 64;
+static __device__ __align__(256) unsigned char scratch[kStaticWsBytes];
+void *g_scratch_ptr[kMaxDevices];                             // device address of `scratch` on device i, once known
+std::mutex g_scratch_mutex;
+
+int static_workspace(bls_ctx *ctx, void **out)
+{
+    int dev = -1;
+    BLS_HIP(ctx, hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) return bls_fail(ctx, BLS_EINVAL, "bls_plan_noalloc: device number out of range");
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void *p = nullptr;
+        BLS_HIP(ctx, hipGetSymbolAddress((void **)&p, HIP_SYMBOL(scratch)));
+        if (!p) return bls_fail(ctx, BLS_EHIP, "bls_plan_noalloc: no device address for the static workspace");
+        g_scratch_ptr[dev] = p;
+    }
+    *out = g_scratch_ptr[dev];
+    return BLS_OK;
+}
+}  // namespace
+
+extern "C" int bls_plan_noalloc(bls_ctx *ctx, const int64_t *d_indices, const int64_t *d_offsets, int64_t nnz,
+                                int64_t *d_sendcounts, int64_t *d_sdispls, int64_t *d_recvcounts, int64_t *d_rdispls,
+                                int64_t *d_ridx, int64_t *d_segoff, int64_t *d_perm, void *hip_stream)
+{
+    if (!ctx) return BLS_EINVAL;
+    if (bls_plan_ws_bytes(ctx) > kStaticWsBytes)
+        return bls_fail(ctx, BLS_ENOSPC, "bls_plan_noalloc: this problem needs more than the 1 MiB static workspace; use bls_plan");
+    void *ws = nullptr;
+    const int rc = static_workspace(ctx, &ws);
+    if (rc) return rc;
+    return plan_common(ctx, d_indices, d_offsets, nullptr, nnz, d_sendcounts, d_sdispls, d_recvcounts, d_rdispls, d_ridx,
+                       nullptr, d_segoff, d_perm, ws, kStaticWsBytes, hip_stream);
 }
 
 extern "C" int bls_plan_weighted(bls_ctx *ctx, const int64_t *d_indices, const int64_t *d_offsets, const float *d_weights,
