@@ -142,6 +142,12 @@ __device__ __forceinline__ void bls_split_sample(const DevDesc &dd, uint32_t b, 
     }
 }
 
+// First sample of rank s's mini-batch (s = P gives B): the first Br ranks hold one sample more.
+__device__ __forceinline__ int64_t bls_first(const DevDesc &dd, int s)
+{
+    return (int64_t)s * dd.Bq + ((uint32_t)s < dd.Br ? (uint32_t)s : dd.Br);
+}
+
 __device__ __forceinline__ int64_t bls_sigma(const DevDesc &dd, int q, int s, uint32_t b_loc, uint32_t n)
 {
     const int d = dd.q_d[q];

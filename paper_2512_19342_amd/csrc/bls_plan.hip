@@ -1,15 +1,21 @@
 // bls_plan: index bucketing by owning rank.
 //
-// Every lookup belongs to exactly one segment (owner d, requester s, local table, local
-// sample), and segments are numbered in owner order, so
-//   1. count   - the length of every segment (table-wise: the bag length; row-wise: a
-//                group of lanes per bag splits its lookups over the P owners: packed byte
-//                counters summed over the lanes for P <= 8, one ballot per owner otherwise),
-//   2. scan    - an exclusive scan of the segment lengths (LDS-staged, three phases) gives
-//                segoff, and the alltoallv counts and displacements are differences of
-//                segoff at the (d, s) block edges - no atomics, no separate histogram,
-//   3. scatter - every lookup is written to segoff[segment] + its rank among the
-//                segment's earlier lookups (lane prefix counts), which is the stable order.
+// Owner-side order is (owner d, requester s, local table, local sample, position in the bag).
+// All bags of one table in one rank's mini-batch - a run (t, s) - are contiguous in the input,
+// and inside the run the order of the lookups an owner receives is their input order.  So the
+// owner-side place of a lookup is
+//      start of block (d, s, t)  +  number of earlier lookups of the run that go to the same owner,
+// i.e. a stable split of every run's lookup stream by owner, and the start of a segment
+// (d, s, t, b) is the same expression evaluated at the bag's first lookup.  Three launches:
+//   1. count   - runs are cut into tiles of consecutive bags; every tile counts its lookups per
+//                owner (table-wise: one tile per run, its length read off the offsets),
+//   2. scan    - exclusive scan of the tile counts in owner order (d, s, t, tile) gives every
+//                tile's start per owner; the alltoallv counts and displacements are differences
+//                of that scan at the (d, s) block edges - no atomics, no separate histogram,
+//   3. place   - every tile streams its lookups once more, ranks them per owner with a scan of
+//                packed per-owner counters over the workgroup (running counts carried from chunk
+//                to chunk) and writes ridx, perm and the weights; the segment starts fall out of
+//                the same running counts.
 #include <algorithm>
 
 #include "bls_internal.h"
@@ -17,10 +23,15 @@
 namespace {
 
 constexpr int kThreads = 256;
+constexpr int kWaves = kThreads / 64;
 constexpr int kItems = 16;                       // scan items per thread
 constexpr int kChunk = kThreads * kItems;        // scan items per block
-constexpr int kSmallScanTiles = 2;               // up to this many tiles one workgroup scans alone
-constexpr int kAhead = 4;                        // row-wise kernels: chunks of a bag's indices loaded ahead
+constexpr int kWideThreads = 1024;               // the one-workgroup scan
+constexpr int kWideChunk = kWideThreads * kItems;
+constexpr int kSmallScanTiles = 8;               // up to this many scan tiles one workgroup scans alone
+constexpr int kRounds = 8;                       // place: lookups per thread and chunk
+constexpr int kStream = kThreads * kRounds;      // place: lookups per chunk of a tile's stream
+constexpr int kOwnersPerPass = 8;                // owners ranked together (packed counters)
 
 __device__ __forceinline__ void flag_error(const DevDesc &dd) { atomicOr(dd.err, 1); }
 
@@ -34,97 +45,124 @@ __device__ __forceinline__ int64_t wave_inclusive_scan(int64_t v, int lane)
     return v;
 }
 
+// Geometry of the row-wise tiles: a run (t, s) is cut into `tiles` tiles of `cb` bags.
+struct Tiles {
+    uint32_t cb, tiles;
+};
+
+// Entry of (owner d, requester s, table t, tile c) in the count array: owner order.
+__device__ __forceinline__ int64_t tile_entry(const DevDesc &dd, const Tiles &tg, int d, int s, int t, uint32_t c)
+{
+    return (((int64_t)d * dd.P + s) * dd.T + t) * tg.tiles + c;
+}
+
+// Owner and local row of a global row number under the block partition of ceil(rows / P) rows
+// per shard.  The owner is below 64, so a single-precision estimate of the quotient (two 32-bit
+// halves converted and combined, times the reciprocal) is off by less than one; the remainder is
+// taken exactly in integers and corrects it.  In place of a 64-bit division.
+__device__ __forceinline__ void owner_and_row(int64_t ix, int64_t rps, float inv, int &d, int64_t &r)
+{
+    const float x = fmaf((float)(uint32_t)((uint64_t)ix >> 32), 4294967296.f, (float)(uint32_t)ix);
+    d = (int)(x * inv);
+    r = ix - (int64_t)d * rps;
+    if (r < 0) { --d; r += rps; }
+    else if (r >= rps) { ++d; r -= rps; }
+}
+
+// The lookups [lo, hi) of the bags [g0, g0 + nb); empty (and flagged) if the offsets are not usable.
+__device__ __forceinline__ void tile_range(const DevDesc &dd, const int64_t *__restrict__ off, int64_t g0, uint32_t nb,
+                                           int64_t nnz, int64_t &lo, int64_t &hi)
+{
+    lo = off[g0];
+    hi = off[g0 + nb];
+    if (lo < 0 || hi > nnz || hi < lo) {
+        if (threadIdx.x == 0) flag_error(dd);
+        lo = hi = 0;
+    }
+}
+
 // ---- 1. count ------------------------------------------------------------------------
 
-// Table-wise: one thread per (q, b); the segment is the whole bag.
-__global__ __launch_bounds__(kThreads) void plan_count_tablewise(DevDesc dd, const int64_t *__restrict__ off,
-                                                                 int64_t nnz, int64_t *__restrict__ seglen)
+// Table-wise: one entry per run (q, s) in owner order, its number of lookups.
+__global__ __launch_bounds__(kThreads) void plan_count_runs(DevDesc dd, const int64_t *__restrict__ off, int64_t nnz,
+                                                            int64_t *__restrict__ cnt)
 {
-    const int q = blockIdx.y;
-    const uint32_t b = blockIdx.x * kThreads + threadIdx.x;
-    if (b >= (uint32_t)dd.B) return;
-    const int64_t g = (int64_t)dd.q_t[q] * dd.B + b;
-    const int64_t lo = off[g], hi = off[g + 1];
+    const int64_t run = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    if (run >= (int64_t)dd.Q * dd.P) return;
+    const int q = (int)(run / dd.P), s = (int)(run - (int64_t)q * dd.P);
+    const int t = dd.q_t[q], d = dd.q_d[q];
+    const int64_t lo = off[(int64_t)t * dd.B + dd.first[s]], hi = off[(int64_t)t * dd.B + dd.first[s + 1]];
     int64_t len = hi - lo;
     if (lo < 0 || hi > nnz || len < 0) { flag_error(dd); len = 0; }
-    int s; uint32_t b_loc, n;
-    bls_split_sample(dd, b, s, b_loc, n);
-    seglen[bls_sigma(dd, q, s, b_loc, n)] = len;
+    cnt[(int64_t)dd.nsum[d] * dd.P + (int64_t)s * dd.n_loc[d] + (q - dd.nsum[d])] = len;
 }
 
-__device__ __forceinline__ int owner_of_row(int64_t ix, int64_t rps)
+// Row-wise: every tile streams its lookups (coalesced, several loads in flight) and counts them
+// per owner.  Up to eight owners are counted in two registers of four 16-bit fields; more owners
+// in a histogram in LDS.
+__global__ __launch_bounds__(kThreads) void plan_count_tiles(DevDesc dd, Tiles tg, const int64_t *__restrict__ idx,
+                                                             const int64_t *__restrict__ off, int64_t nnz,
+                                                             int64_t *__restrict__ cnt)
 {
-    return rps <= 0xffffffffLL && ix <= 0xffffffffLL ? (int)((uint32_t)ix / (uint32_t)rps) : (int)(ix / rps);
-}
-
-// Row-wise: a group of G >= P lanes per bag (t, b), several bags per wavefront.  One ballot
-// per owner tells every group how many of its lookups fall in that owner's block of rows;
-// lane o of the group accumulates owner o's count.
-template <int G>
-__global__ __launch_bounds__(kThreads) void plan_count_rowwise(DevDesc dd, const int64_t *__restrict__ idx,
-                                                               const int64_t *__restrict__ off, int64_t nnz,
-                                                               int64_t *__restrict__ seglen)
-{
-    const int lane = threadIdx.x & 63;
-    const int li = lane & (G - 1), gbase = lane & ~(G - 1);
-    const unsigned long long gmask = G == 64 ? ~0ull : (1ull << (G & 63)) - 1ull;
-    const int t = blockIdx.y;
-    const uint32_t b = blockIdx.x * (kThreads / G) + threadIdx.x / G;
-    const bool live = b < (uint32_t)dd.B;
-    int64_t lo = 0, len = 0;
-    if (live) {
-        const int64_t g = (int64_t)t * dd.B + b;
-        lo = off[g];
-        const int64_t hi = off[g + 1];
-        len = hi - lo;
-        if (lo < 0 || hi > nnz || len < 0) { if (li == 0) flag_error(dd); len = 0; }
-    }
+    __shared__ unsigned long long hist[64];
+    const int t = blockIdx.y / dd.P, s = blockIdx.y - t * dd.P;
+    const uint32_t c = blockIdx.x;
+    const int64_t f = bls_first(dd, s), n = bls_first(dd, s + 1) - f;   // no table look-up: the offsets can be asked for at once
     const int64_t rows = dd.rows[t], rps = dd.rps[t];
-    int64_t cnt = 0;
-    // a bag is a handful of chunks and every chunk a dependent round trip: the indices of the next
-    // kAhead chunks are always in flight while the current one is counted
-    int64_t nx[kAhead];
+    const int64_t b0 = (int64_t)c * tg.cb;
+    if (threadIdx.x < 64) hist[threadIdx.x] = 0ull;
+    __syncthreads();
+    if (b0 < n) {                                             // uniform over the workgroup
+        const uint32_t nb = (uint32_t)(n - b0 < tg.cb ? n - b0 : tg.cb);
+        int64_t lo, hi;
+        tile_range(dd, off, (int64_t)t * dd.B + f + b0, nb, nnz, lo, hi);
+        const float inv = 1.f / (float)rps;
+        constexpr int kLoads = 8;                              // independent loads per thread in flight
+        constexpr int64_t kEpoch = (int64_t)kThreads * 32768;  // no 16-bit field can overflow within one epoch
+        for (int64_t e0 = lo; e0 < hi; e0 += kEpoch) {
+            const int64_t e1 = e0 + kEpoch < hi ? e0 + kEpoch : hi;
+            unsigned long long pk0 = 0ull, pk1 = 0ull;
+            for (int64_t i0 = e0 + threadIdx.x; i0 < e1; i0 += (int64_t)kThreads * kLoads) {
+                int64_t ix[kLoads];
 #pragma unroll
-    for (int a = 0; a < kAhead; ++a) nx[a] = a * G + li < len ? idx[lo + a * G + li] : 0;
-    for (int64_t c = 0; __any(c < len); c += G) {
-        const int64_t j = c + li;
-        const int64_t ix = nx[0];
+                for (int k = 0; k < kLoads; ++k) ix[k] = i0 + k * kThreads < e1 ? idx[i0 + k * kThreads] : -1;
 #pragma unroll
-        for (int a = 0; a + 1 < kAhead; ++a) nx[a] = nx[a + 1];
-        nx[kAhead - 1] = j + kAhead * G < len ? idx[lo + j + kAhead * G] : 0;
-        int d = -1;
-        if (j < len) {
-            if (ix < 0 || ix >= rows) flag_error(dd);
-            else d = owner_of_row(ix, rps);
-        }
-        if (dd.P <= 8) {
-            // up to eight owners: one byte per owner in a 64-bit word, summed over the group's lanes
-            unsigned long long pk = d >= 0 ? 1ull << (8 * d) : 0ull;
+                for (int k = 0; k < kLoads; ++k) {
+                    if (i0 + k * kThreads >= e1) continue;
+                    if (ix[k] < 0 || ix[k] >= rows) { flag_error(dd); continue; }
+                    int d; int64_t r;
+                    owner_and_row(ix[k], rps, inv, d, r);
+                    if (dd.P <= 8) {
+                        if (d < 4) pk0 += 1ull << (16 * d);
+                        else pk1 += 1ull << (16 * (d - 4));
+                    } else {
+                        atomicAdd(&hist[d], 1ull);
+                    }
+                }
+            }
+            if (dd.P <= 8) {
 #pragma unroll
-            for (int o = G / 2; o >= 1; o >>= 1) pk += __shfl_xor(pk, o, 64);
-            cnt += (int64_t)((pk >> (8 * (li & 7))) & 0xffull);
-        } else {
-            for (int o = 0; o < dd.P; ++o) {
-                const unsigned long long m = (__ballot(d == o) >> gbase) & gmask;
-                if (li == o) cnt += __popcll(m);
+                for (int o = 0; o < 8; ++o) {
+                    unsigned int v = (unsigned int)(((o < 4 ? pk0 : pk1) >> (16 * (o & 3))) & 0xffffull);
+#pragma unroll
+                    for (int sh = 32; sh >= 1; sh >>= 1) v += __shfl_xor(v, sh, 64);
+                    if ((threadIdx.x & 63) == 0 && v) atomicAdd(&hist[o], (unsigned long long)v);
+                }
             }
         }
     }
-    if (live && li < dd.P) {
-        int s; uint32_t b_loc, n;
-        bls_split_sample(dd, b, s, b_loc, n);
-        seglen[bls_sigma_rowwise(dd, li, t, s, b_loc, n)] = cnt;
-    }
+    __syncthreads();
+    if (threadIdx.x < dd.P) cnt[tile_entry(dd, tg, threadIdx.x, s, t, c)] = (int64_t)hist[threadIdx.x];
 }
 
 // ---- 2. scan ---------------------------------------------------------------------------
-// In-place inclusive scan of v[0..n) (v = segoff + 1, holding segment lengths), so that
-// segoff becomes the exclusive scan with segoff[nseg] = total.
+// From the counts C[0 .. n) to their exclusive scan X[0 .. n]: X[i] = sum of the counts before entry i,
+// X[0] = 0, X[n] = the total (the inclusive scan of C, written one place up).
 
 __global__ __launch_bounds__(kThreads) void scan_block_sums(const int64_t *__restrict__ v, int64_t n,
                                                             int64_t *__restrict__ sums)
 {
-    __shared__ int64_t part[kThreads / 64];
+    __shared__ int64_t part[kWaves];
     const int64_t base = (int64_t)blockIdx.x * kChunk;
     int64_t a = 0;
 #pragma unroll
@@ -138,7 +176,7 @@ __global__ __launch_bounds__(kThreads) void scan_block_sums(const int64_t *__res
     __syncthreads();
     if (threadIdx.x == 0) {
         int64_t tot = 0;
-        for (int w = 0; w < kThreads / 64; ++w) tot += part[w];
+        for (int w = 0; w < kWaves; ++w) tot += part[w];
         sums[blockIdx.x] = tot;
     }
 }
@@ -146,7 +184,7 @@ __global__ __launch_bounds__(kThreads) void scan_block_sums(const int64_t *__res
 // One block: exclusive scan of the block sums, in place.
 __global__ __launch_bounds__(kThreads) void scan_spine(int64_t *__restrict__ sums, int64_t nblk)
 {
-    __shared__ int64_t part[kThreads / 64];
+    __shared__ int64_t part[kWaves];
     __shared__ int64_t carry_s;
     const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
     if (threadIdx.x == 0) carry_s = 0;
@@ -166,18 +204,18 @@ __global__ __launch_bounds__(kThreads) void scan_spine(int64_t *__restrict__ sum
     }
 }
 
-// Inclusive scan of one tile v[base .. base + kChunk) in place, offset by `carry`; returns
+// Inclusive scan of one tile src[base .. base + kChunk) into v, offset by `carry`; returns
 // carry + the tile's total (the same value in every thread).  Items are staged in LDS so that
 // global accesses stay coalesced while every thread owns a contiguous run; one padding word
 // per run keeps the per-thread walks off one bank.
-__device__ __forceinline__ int64_t scan_tile(int64_t *__restrict__ v, int64_t n, int64_t base, int64_t carry,
-                                             int64_t *tile, int64_t *part)
+__device__ __forceinline__ int64_t scan_tile(const int64_t *__restrict__ src, int64_t *__restrict__ v, int64_t n, int64_t base,
+                                             int64_t carry, int64_t *tile, int64_t *part)
 {
 #pragma unroll
     for (int k = 0; k < kItems; ++k) {
         const int e = k * kThreads + threadIdx.x;
         const int64_t i = base + e;
-        tile[e + e / kItems] = i < n ? v[i] : 0;
+        tile[e + e / kItems] = i < n ? src[i] : 0;
     }
     __syncthreads();
     const int mine = threadIdx.x * (kItems + 1);
@@ -189,7 +227,7 @@ __device__ __forceinline__ int64_t scan_tile(int64_t *__restrict__ v, int64_t n,
     if (lane == 63) part[wv] = inc;
     __syncthreads();
     int64_t before = carry + inc - run, total = carry;
-    for (int w = 0; w < kThreads / 64; ++w) {
+    for (int w = 0; w < kWaves; ++w) {
         if (w < wv) before += part[w];
         total += part[w];
     }
@@ -206,97 +244,225 @@ __device__ __forceinline__ int64_t scan_tile(int64_t *__restrict__ v, int64_t n,
     return total;
 }
 
-__global__ __launch_bounds__(kThreads) void scan_apply(int64_t *__restrict__ v, int64_t n,
+__global__ __launch_bounds__(kThreads) void scan_apply(const int64_t *__restrict__ src, int64_t *__restrict__ v, int64_t n,
                                                        const int64_t *__restrict__ sums, int64_t *__restrict__ head)
 {
     __shared__ int64_t tile[kChunk + kThreads];
-    __shared__ int64_t part[kThreads / 64];
-    if (blockIdx.x == 0 && threadIdx.x == 0) *head = 0;   // segoff[0]
-    scan_tile(v, n, (int64_t)blockIdx.x * kChunk, sums[blockIdx.x], tile, part);
+    __shared__ int64_t part[kWaves];
+    if (blockIdx.x == 0 && threadIdx.x == 0) *head = 0;
+    scan_tile(src, v, n, (int64_t)blockIdx.x * kChunk, sums[blockIdx.x], tile, part);
 }
 
-// Counts and displacements from segoff at the (d, s) block edges, by one workgroup.
+// First entry of block (d, s) in the scanned array X (owner order); block (P, 0) is the end.
+__device__ __forceinline__ int64_t block_edge(const DevDesc &dd, uint32_t tiles, int d, int s)
+{
+    if (dd.part_kind == BLS_ROW_WISE) return ((int64_t)d * dd.P + s) * dd.T * tiles;
+    if (d >= dd.P) return (int64_t)dd.Q * dd.P;
+    return (int64_t)dd.nsum[d] * dd.P + (int64_t)s * dd.n_loc[d];
+}
+
+// Counts and displacements from the scan X at the (d, s) block edges, by one workgroup; also the
+// last segment start, segoff[nseg] = number of lookups placed.  Called by every thread of the workgroup.
 // sabs[s][d] / rabs[d][s]: absolute start of bucket (s, d) in requester / owner order.
-__device__ __forceinline__ void finish_counts(const DevDesc &dd, const int64_t *__restrict__ segoff,
+__device__ __forceinline__ void finish_counts(const DevDesc &dd, uint32_t tiles, const int64_t *__restrict__ X,
                                               int64_t *__restrict__ sendcounts, int64_t *__restrict__ sdispls,
                                               int64_t *__restrict__ recvcounts, int64_t *__restrict__ rdispls,
-                                              int64_t *__restrict__ sabs, int64_t *__restrict__ rabs, int64_t *rowtot)
+                                              int64_t *__restrict__ sabs, int64_t *__restrict__ rabs,
+                                              int64_t *__restrict__ segoff_end, int64_t *sc, int64_t *rowtot)
 {
     const int P = dd.P;
-    for (int e = threadIdx.x; e < P * P; e += kThreads) {
+    for (int e = threadIdx.x; e < P * P; e += blockDim.x) {
         const int d = e / P, s = e - d * P;
-        const int64_t edge0 = (int64_t)dd.nsum[d] * dd.B;
-        const int64_t lo = segoff[edge0 + (int64_t)dd.n_loc[d] * dd.first[s]];
-        const int64_t hi = segoff[edge0 + (int64_t)dd.n_loc[d] * dd.first[s + 1]];
+        const int64_t lo = X[block_edge(dd, tiles, d, s)];
+        const int64_t hi = X[s + 1 < P ? block_edge(dd, tiles, d, s + 1) : block_edge(dd, tiles, d + 1, 0)];
         recvcounts[d * P + s] = hi - lo;
-        rdispls[d * P + s] = lo - segoff[edge0];
+        rdispls[d * P + s] = lo - X[block_edge(dd, tiles, d, 0)];
         rabs[d * P + s] = lo;
         sendcounts[s * P + d] = hi - lo;
+        sc[s * P + d] = hi - lo;                      // a copy in LDS for the running sums below
     }
+    if (threadIdx.x == 0) *segoff_end = X[block_edge(dd, tiles, P, 0)];
     __syncthreads();
     if (threadIdx.x < P) {
         const int s = threadIdx.x;
         int64_t run = 0;
-        for (int d = 0; d < P; ++d) { sdispls[s * P + d] = run; run += sendcounts[s * P + d]; }
+        for (int d = 0; d < P; ++d) run += sc[s * P + d];
         rowtot[s] = run;
     }
     __syncthreads();
     if (threadIdx.x < P) {
         const int s = threadIdx.x;
-        int64_t sbase = 0;
-        for (int r = 0; r < s; ++r) sbase += rowtot[r];
-        for (int d = 0; d < P; ++d) sabs[s * P + d] = sbase + sdispls[s * P + d];
+        int64_t run = 0;
+        for (int r = 0; r < s; ++r) run += rowtot[r];
+        const int64_t sbase = run;
+        for (int d = 0; d < P; ++d) {
+            sdispls[s * P + d] = run - sbase;
+            sabs[s * P + d] = run;
+            run += sc[s * P + d];
+        }
     }
 }
 
-__global__ __launch_bounds__(kThreads) void plan_finish(DevDesc dd, const int64_t *__restrict__ segoff,
+__global__ __launch_bounds__(kThreads) void plan_finish(DevDesc dd, uint32_t tiles, const int64_t *__restrict__ X,
                                                         int64_t *__restrict__ sendcounts, int64_t *__restrict__ sdispls,
                                                         int64_t *__restrict__ recvcounts, int64_t *__restrict__ rdispls,
-                                                        int64_t *__restrict__ sabs, int64_t *__restrict__ rabs)
+                                                        int64_t *__restrict__ sabs, int64_t *__restrict__ rabs,
+                                                        int64_t *__restrict__ segoff_end)
 {
+    __shared__ int64_t sc[64 * 64];
     __shared__ int64_t rowtot[64];
-    finish_counts(dd, segoff, sendcounts, sdispls, recvcounts, rdispls, sabs, rabs, rowtot);
+    finish_counts(dd, tiles, X, sendcounts, sdispls, recvcounts, rdispls, sabs, rabs, segoff_end, sc, rowtot);
 }
 
-// Small problems are bound by the number of launches: one workgroup scans all tiles in turn and
-// derives the counts, in place of the three scan kernels and plan_finish.
-__global__ __launch_bounds__(kThreads) void plan_scan_small(DevDesc dd, int64_t *__restrict__ segoff, int64_t n,
+// Up to kSmallScanTiles * kChunk counts: one workgroup scans them and derives the alltoallv counts,
+// in place of the three scan kernels and plan_finish.
+__global__ __launch_bounds__(kThreads) void plan_scan_small(DevDesc dd, uint32_t tiles, const int64_t *__restrict__ C,
+                                                            int64_t *__restrict__ X, int64_t n,
                                                             int64_t *__restrict__ sendcounts, int64_t *__restrict__ sdispls,
                                                             int64_t *__restrict__ recvcounts, int64_t *__restrict__ rdispls,
-                                                            int64_t *__restrict__ sabs, int64_t *__restrict__ rabs)
+                                                            int64_t *__restrict__ sabs, int64_t *__restrict__ rabs,
+                                                            int64_t *__restrict__ segoff_end)
 {
     __shared__ int64_t tile[kChunk + kThreads];
-    __shared__ int64_t part[kThreads / 64];
+    __shared__ int64_t part[kWaves];
     __shared__ int64_t rowtot[64];
-    if (threadIdx.x == 0) segoff[0] = 0;
+    if (threadIdx.x == 0) X[0] = 0;
     int64_t carry = 0;
-    for (int64_t base = 0; base < n; base += kChunk) carry = scan_tile(segoff + 1, n, base, carry, tile, part);
-    __syncthreads();                                  // every segoff entry written by this workgroup is visible to it
-    finish_counts(dd, segoff, sendcounts, sdispls, recvcounts, rdispls, sabs, rabs, rowtot);
+    for (int64_t base = 0; base < n; base += kChunk) carry = scan_tile(C, X + 1, n, base, carry, tile, part);
+    __syncthreads();                                  // every entry written by this workgroup is visible to it
+    finish_counts(dd, tiles, X, sendcounts, sdispls, recvcounts, rdispls, sabs, rabs, segoff_end, tile, rowtot);
 }
 
-// ---- 3. scatter ------------------------------------------------------------------------
+// Row-wise, few ranks: one workgroup per block (d, s) of the count array.  Every workgroup adds up
+// the whole array for itself (it is small and sits in L2), keeping apart what lies before its block,
+// what belongs to its owner, to its requester and to earlier requesters; that gives the block's
+// start and its row of the counts and displacements without waiting for any other workgroup.  Then
+// it scans its own T * tiles entries.  One launch in place of the scan kernels and plan_finish.
+__global__ __launch_bounds__(kWideThreads) void plan_scan_blocks(DevDesc dd, uint32_t tiles, const int64_t *__restrict__ cnt,
+                                                                 int64_t *__restrict__ X, int64_t n,
+                                                                 int64_t *__restrict__ sendcounts, int64_t *__restrict__ sdispls,
+                                                                 int64_t *__restrict__ recvcounts, int64_t *__restrict__ rdispls,
+                                                                 int64_t *__restrict__ sabs, int64_t *__restrict__ rabs,
+                                                                 int64_t *__restrict__ segoff_end)
+{
+    constexpr int kW = kWideThreads / 64;
+    constexpr int kSums = 6;          // before the block; same owner, earlier requesters; same requester, earlier owners;
+                                      // earlier requesters, any owner; the block itself; everything
+    __shared__ int64_t part[kW][kSums];
+    __shared__ int64_t scanpart[kW];
+    const int P = dd.P;
+    const int d = blockIdx.x / P, s = blockIdx.x - d * P;
+    const uint32_t per_block = (uint32_t)dd.T * tiles;        // entries per (d, s) block
+    const int64_t e0 = (int64_t)blockIdx.x * per_block;
+    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+    // n is below 2^22 here: entry numbers are exact in single precision, and a quotient estimated
+    // with the reciprocal is off by one at most
+    const float inv_block = 1.f / (float)per_block, inv_p = 1.f / (float)P;
 
-// Table-wise: all bags of one table in one rank's mini-batch - a run (q, s) - are contiguous
-// both in input order and in owner order, so the scatter is Q*P block copies of index
-// lists.  grid: x strides over a run, y strides over the runs.
-__global__ __launch_bounds__(kThreads) void plan_scatter_runs(DevDesc dd, const int64_t *__restrict__ idx,
-                                                              const int64_t *__restrict__ off, int64_t nnz,
-                                                              const int64_t *__restrict__ segoff,
-                                                              int64_t *__restrict__ ridx, int64_t *__restrict__ perm,
-                                                              const int64_t *__restrict__ sabs,
-                                                              const int64_t *__restrict__ rabs,
-                                                              const float *__restrict__ w_in, float *__restrict__ w_out)
+    int64_t acc[kSums] = {0, 0, 0, 0, 0, 0};
+    for (int64_t base = 0; base < n; base += (int64_t)kWideThreads * kItems) {
+        int64_t x[kItems];
+#pragma unroll
+        for (int k = 0; k < kItems; ++k) {                    // consecutive threads read consecutive entries
+            const int64_t e = base + (int64_t)k * kWideThreads + threadIdx.x;
+            x[k] = e < n ? cnt[e] : 0;
+        }
+#pragma unroll
+        for (int k = 0; k < kItems; ++k) {
+            const uint32_t e = (uint32_t)(base + (int64_t)k * kWideThreads + threadIdx.x);
+            uint32_t b = (uint32_t)((float)e * inv_block);
+            if (b * per_block > e) --b;
+            else if ((b + 1u) * per_block <= e) ++b;
+            uint32_t dp = (uint32_t)((float)b * inv_p);
+            if (dp * (uint32_t)P > b) --dp;
+            else if ((dp + 1u) * (uint32_t)P <= b) ++dp;
+            const int sp = (int)(b - dp * (uint32_t)P);
+            if (b < blockIdx.x) acc[0] += x[k];
+            if ((int)dp == d && sp < s) acc[1] += x[k];
+            if (sp == s && (int)dp < d) acc[2] += x[k];
+            if (sp < s) acc[3] += x[k];
+            if (b == blockIdx.x) acc[4] += x[k];
+            acc[5] += x[k];
+        }
+    }
+#pragma unroll
+    for (int a = 0; a < kSums; ++a) {
+#pragma unroll
+        for (int sh = 32; sh >= 1; sh >>= 1) acc[a] += __shfl_xor(acc[a], sh, 64);
+        if (lane == 0) part[wv][a] = acc[a];
+    }
+    __syncthreads();
+    int64_t mine[kSums] = {0, 0, 0, 0, 0, 0};
+    for (int w = 0; w < kW; ++w)
+#pragma unroll
+        for (int a = 0; a < kSums; ++a) mine[a] += part[w][a];
+    if (threadIdx.x == 0) {
+        recvcounts[d * P + s] = mine[4];
+        sendcounts[s * P + d] = mine[4];
+        rdispls[d * P + s] = mine[1];
+        sdispls[s * P + d] = mine[2];
+        rabs[d * P + s] = mine[0];
+        sabs[s * P + d] = mine[3] + mine[2];
+        if ((int)blockIdx.x == P * P - 1) { X[n] = mine[5]; *segoff_end = mine[5]; }
+    }
+    int64_t carry = mine[0];
+    // the block's own entries: X[e] = start of the block + the counts before e inside it
+    for (int64_t base = 0; base < per_block; base += kWideChunk) {
+        const int64_t at = base + (int64_t)threadIdx.x * kItems;
+        int64_t x[kItems];
+#pragma unroll
+        for (int k = 0; k < kItems; ++k) x[k] = at + k < per_block ? cnt[e0 + at + k] : 0;
+        int64_t run = 0;
+#pragma unroll
+        for (int k = 0; k < kItems; ++k) { const int64_t v = x[k]; x[k] = run; run += v; }
+        const int64_t inc = wave_inclusive_scan(run, lane);
+        __syncthreads();                              // scanpart is free again
+        if (lane == 63) scanpart[wv] = inc;
+        __syncthreads();
+        int64_t before = carry + inc - run, total = carry;
+        for (int w = 0; w < kW; ++w) {
+            if (w < wv) before += scanpart[w];
+            total += scanpart[w];
+        }
+#pragma unroll
+        for (int k = 0; k < kItems; ++k)
+            if (at + k < per_block) X[e0 + at + k] = x[k] + before;
+        carry = total;
+    }
+}
+
+// ---- 3. place --------------------------------------------------------------------------
+
+// Table-wise: a run (q, s) is contiguous both in input order and in owner order, so placing is
+// Q*P block copies of index lists, and a segment starts as far into the owner-side block as its
+// bag starts into the run.  grid: x strides over a run, y strides over the runs.
+__global__ __launch_bounds__(kThreads) void plan_place_runs(DevDesc dd, const int64_t *__restrict__ idx,
+                                                            const int64_t *__restrict__ off, int64_t nnz,
+                                                            const int64_t *__restrict__ X, int64_t *__restrict__ segoff,
+                                                            int64_t *__restrict__ ridx, int64_t *__restrict__ perm,
+                                                            const int64_t *__restrict__ sabs,
+                                                            const int64_t *__restrict__ rabs,
+                                                            const float *__restrict__ w_in, float *__restrict__ w_out)
 {
     constexpr int kPer = 4;
     for (int run = blockIdx.y; run < dd.Q * dd.P; run += gridDim.y) {
         const int q = run / dd.P, s = run - q * dd.P;
         const int t = dd.q_t[q], d = dd.q_d[q];
-        const int64_t lo = off[(int64_t)t * dd.B + dd.first[s]], hi = off[(int64_t)t * dd.B + dd.first[s + 1]];
+        const int64_t f = dd.first[s], n = dd.first[s + 1] - f;
+        const int64_t g0 = (int64_t)t * dd.B + f;
+        int64_t lo = off[g0], hi = off[g0 + n];
+        if (lo < 0 || hi > nnz || hi < lo) lo = hi = 0;       // flagged by the count kernel; the run counts as empty
         const int64_t len = hi - lo;
-        if (lo < 0 || hi > nnz || len <= 0) continue;        // bad offsets are flagged by the count kernel
-        const int64_t n = dd.first[s + 1] - dd.first[s];
-        const int64_t dst = segoff[(int64_t)dd.nsum[d] * dd.B + (int64_t)dd.n_loc[d] * dd.first[s] + (int64_t)(q - dd.nsum[d]) * n];
+        const int64_t dst = X[(int64_t)dd.nsum[d] * dd.P + (int64_t)s * dd.n_loc[d] + (q - dd.nsum[d])];
+        // segment starts of the run's bags
+        const int64_t sg0 = (int64_t)dd.nsum[d] * dd.B + (int64_t)dd.n_loc[d] * f + (int64_t)(q - dd.nsum[d]) * n;
+        for (int64_t b = (int64_t)blockIdx.x * kThreads + threadIdx.x; b < n; b += (int64_t)gridDim.x * kThreads) {
+            int64_t at = off[g0 + b] - lo;
+            const int64_t nxt = off[g0 + b + 1] - lo;
+            if (at < 0 || at > len || nxt < at) { flag_error(dd); at = at < 0 ? 0 : (at > len ? len : at); }
+            segoff[sg0 + b] = dst + at;
+        }
+        if (len <= 0) continue;
         if (dst < 0 || dst + len > nnz) { if (threadIdx.x == 0 && blockIdx.x == 0) flag_error(dd); continue; }
         const int64_t rows = dd.rows[t];
         const int64_t to_send = perm ? sabs[s * dd.P + d] - rabs[d * dd.P + s] : 0;
@@ -322,99 +488,225 @@ __global__ __launch_bounds__(kThreads) void plan_scatter_runs(DevDesc dd, const 
     }
 }
 
-// Row-wise: a group of G >= P lanes per bag.  Lane o of the group holds the start of owner
-// o's segment and how many of the bag's lookups it has already received; a lookup's place is
-// that start plus the number of earlier lanes of the group with the same owner.
-template <int G>
-__global__ __launch_bounds__(kThreads) void plan_scatter_rowwise(DevDesc dd, const int64_t *__restrict__ idx,
-                                                                 const int64_t *__restrict__ off, int64_t nnz,
-                                                                 const int64_t *__restrict__ segoff,
-                                                                 int64_t *__restrict__ ridx, int64_t *__restrict__ perm,
-                                                                 const int64_t *__restrict__ sabs,
-                                                                 const int64_t *__restrict__ rabs,
-                                                                 const float *__restrict__ w_in, float *__restrict__ w_out)
+// Four bytes spread to four 16-bit fields of a 64-bit word.
+__device__ __forceinline__ unsigned long long spread4(uint32_t x)
 {
-    const int lane = threadIdx.x & 63;
-    const int li = lane & (G - 1), gbase = lane & ~(G - 1);
-    const unsigned long long gmask = G == 64 ? ~0ull : (1ull << (G & 63)) - 1ull;
-    const unsigned long long below = (1ull << li) - 1ull;
-    const int t = blockIdx.y;
-    const uint32_t b = blockIdx.x * (kThreads / G) + threadIdx.x / G;
-    const bool live = b < (uint32_t)dd.B;
-    int64_t lo = 0, len = 0;
-    int64_t next = 0, to_send = 0;                        // lane o: next free place of owner o
-    if (live) {
-        const int64_t g = (int64_t)t * dd.B + b;
-        lo = off[g];
-        const int64_t hi = off[g + 1];
-        len = hi - lo;
-        if (lo < 0 || hi > nnz || len < 0) len = 0;       // flagged by the count kernel
-        if (li < dd.P) {
-            int s; uint32_t b_loc, n;
-            bls_split_sample(dd, b, s, b_loc, n);
-            next = segoff[bls_sigma_rowwise(dd, li, t, s, b_loc, n)];
-            if (perm) to_send = sabs[s * dd.P + li] - rabs[li * dd.P + s];
-        }
-    }
+    unsigned long long v = x;
+    v = (v | (v << 16)) & 0x0000ffff0000ffffull;
+    v = (v | (v << 8)) & 0x00ff00ff00ff00ffull;
+    return v;
+}
+
+// Field o (0..7) of a pair of words with four 16-bit fields each.
+__device__ __forceinline__ uint32_t field16(unsigned long long w0, unsigned long long w1, int o)
+{
+    return (uint32_t)(((o < 4 ? w0 : w1) >> (16 * (o & 3))) & 0xffffull);
+}
+
+// Row-wise: a tile streams its lookups in chunks of kStream.  They are loaded coalesced (lookup e
+// of the chunk by thread e % 256), which gives owner and local row; the owners go to LDS, one byte
+// each, and are ranked in blocks: thread i reads the owners of lookups 8i .. 8i+7, counts them per
+// owner in byte fields, and an exclusive scan of those counts over the workgroup (16-bit fields,
+// up to eight owners in two words, more owners eight at a time) gives every lookup its rank among
+// the chunk's lookups of the same owner.  The ranks return through LDS to the threads that hold
+// the rows; running totals carry the rank from chunk to chunk.  The start of segment (d, bag) is
+// the same count taken at the bag's first lookup.
+template <bool PERM, bool WGT>
+__global__ __launch_bounds__(kThreads) void plan_place_tiles(DevDesc dd, Tiles tg, const int64_t *__restrict__ idx,
+                                                             const int64_t *__restrict__ off, int64_t nnz,
+                                                             const int64_t *__restrict__ X, int64_t *__restrict__ segoff,
+                                                             int64_t *__restrict__ ridx, int64_t *__restrict__ perm,
+                                                             const int64_t *__restrict__ sabs,
+                                                             const int64_t *__restrict__ rabs,
+                                                             const float *__restrict__ w_in, float *__restrict__ w_out)
+{
+    __shared__ unsigned long long ownb[kThreads];             // owners of the chunk's lookups, a byte each (0xff: none)
+    __shared__ unsigned long long excl[kThreads][2];          // per thread: same-owner lookups before its first one
+    __shared__ __attribute__((aligned(16))) unsigned short rk[kStream];   // rank of every lookup among its owner's
+    __shared__ unsigned long long wtot[kWaves][2];            // per wavefront: its lookups per owner
+    __shared__ int64_t start[64];                             // owner's next free place: tile start + running count
+    __shared__ int64_t shift[64];                             // owner-side place -> requester-side place
+
+    const int t = blockIdx.y / dd.P, s = blockIdx.y - t * dd.P;
+    const uint32_t c = blockIdx.x;
+    const int64_t f = bls_first(dd, s), n = bls_first(dd, s + 1) - f;
+    const int64_t b0 = (int64_t)c * tg.cb;
+    if (b0 >= n) return;                                      // uniform over the workgroup: no bags in this tile
     const int64_t rows = dd.rows[t], rps = dd.rps[t];
-    // a bag is a handful of chunks and every chunk a dependent round trip: the indices of the next
-    // kAhead chunks are always in flight while the current one is placed
-    int64_t nx[kAhead];
-#pragma unroll
-    for (int a = 0; a < kAhead; ++a) nx[a] = a * G + li < len ? idx[lo + a * G + li] : 0;
-    for (int64_t c = 0; __any(c < len); c += G) {
-        const int64_t j = c + li;
-        const int64_t ix = nx[0];
-#pragma unroll
-        for (int a = 0; a + 1 < kAhead; ++a) nx[a] = nx[a + 1];
-        nx[kAhead - 1] = j + kAhead * G < len ? idx[lo + j + kAhead * G] : 0;
-        int d = -1;
-        int64_t r = 0;
-        if (j < len) {
-            if (ix >= 0 && ix < rows) { d = owner_of_row(ix, rps); r = ix - (int64_t)d * rps; }
+    const uint32_t nb = (uint32_t)(n - b0 < tg.cb ? n - b0 : tg.cb);
+    const int64_t g0 = (int64_t)t * dd.B + f + b0;
+    int64_t lo, hi;
+    tile_range(dd, off, g0, nb, nnz, lo, hi);
+    const int64_t len = hi - lo;
+    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+    if (threadIdx.x < dd.P) {
+        start[threadIdx.x] = X[tile_entry(dd, tg, threadIdx.x, s, t, c)];
+        shift[threadIdx.x] = PERM ? sabs[s * dd.P + threadIdx.x] - rabs[threadIdx.x * dd.P + s] : 0;
+    }
+    const float inv = 1.f / (float)rps;
+    const int passes = (dd.P + kOwnersPerPass - 1) / kOwnersPerPass;
+
+    // where bag b of the tile starts in the tile's stream, clamped into it (bad offsets are flagged once)
+    auto bag_start = [&](uint32_t b, bool report) -> int64_t {
+        int64_t at = off[g0 + b] - lo;
+        if (at < 0 || at > len || off[g0 + b + 1] - lo < at) {
+            if (report) flag_error(dd);
+            at = at < 0 ? 0 : (at > len ? len : at);
         }
-        int rank = 0, add = 0;
-        if (dd.P <= 8) {
-            // one byte per owner: a prefix sum over the group's lanes gives every lookup its rank among
-            // the earlier ones of the same owner, the last lane's sum the chunk's count per owner
-            const unsigned long long pk = d >= 0 ? 1ull << (8 * d) : 0ull;
-            unsigned long long pre = pk;
+        return at;
+    };
+    const int64_t at_first = threadIdx.x < nb ? bag_start(threadIdx.x, true) : -1;   // bag b = threadIdx.x
+    for (uint32_t b = threadIdx.x + kThreads; b < nb; b += kThreads) (void)bag_start(b, true);
+
+    for (int64_t c0 = 0; c0 < len || c0 == 0; c0 += kStream) {
+        const bool last = c0 + kStream >= len;
+        // this thread's lookups of the chunk: owner (a byte each, 0xff: none or a bad index) and local
+        // row (below 2^32: no shard has more rows)
+        unsigned long long owns = ~0ull;
+        uint32_t row[kRounds];
+        {
+            int64_t ix[kRounds];
 #pragma unroll
-            for (int o = 1; o < G; o <<= 1) {
-                const unsigned long long v = __shfl_up(pre, o, G);
-                if (li >= o) pre += v;
+            for (int k = 0; k < kRounds; ++k) {
+                const int64_t i = c0 + k * kThreads + threadIdx.x;
+                ix[k] = i < len ? idx[lo + i] : -1;
             }
-            if (d >= 0) rank = (int)(((pre - pk) >> (8 * d)) & 0xffull);
-            const unsigned long long total = __shfl(pre, gbase + G - 1, 64);
-            add = (int)((total >> (8 * (li & 7))) & 0xffull);
-        } else {
-            for (int o = 0; o < dd.P; ++o) {
-                const unsigned long long m = (__ballot(d == o) >> gbase) & gmask;
-                if (d == o) rank = __popcll(m & below);
-                if (li == o) add = __popcll(m);
+#pragma unroll
+            for (int k = 0; k < kRounds; ++k) {
+                uint32_t o = 0xffu;
+                row[k] = 0u;
+                if (c0 + k * kThreads + threadIdx.x < len) {
+                    if (ix[k] < 0 || ix[k] >= rows) flag_error(dd);
+                    else { int d; int64_t r; owner_and_row(ix[k], rps, inv, d, r); o = (uint32_t)d; row[k] = (uint32_t)r; }
+                }
+                owns = (owns & ~(0xffull << (8 * k))) | ((unsigned long long)o << (8 * k));
+                reinterpret_cast<unsigned char *>(ownb)[k * kThreads + threadIdx.x] = (unsigned char)o;
             }
         }
-        const int src = gbase + (d < 0 ? 0 : d);
-        const int64_t place = __shfl(next, src, 64) + rank;
-        const int64_t shift = __shfl(to_send, src, 64);
-        if (d >= 0) {
-            if (place >= 0 && place < nnz) {
-                ridx[place] = r;
-                if (w_in) w_out[place] = w_in[lo + j];
-                if (perm) perm[lo + j] = place + shift;
-            } else flag_error(dd);
+        __syncthreads();                                      // the owners are in LDS; start[] is up to date
+        for (int pass = 0; pass < passes; ++pass) {
+            const uint32_t o0 = (uint32_t)(pass * kOwnersPerPass);
+            // blocked: lookups 8i .. 8i+7 of the chunk
+            const unsigned long long own8 = ownb[threadIdx.x];
+            unsigned long long pk8 = 0ull;                     // lookups per owner among this thread's eight, byte fields
+            uint32_t lr = 0u;                                  // rank of each of the eight inside the thread, 4 bits each
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const uint32_t o = (uint32_t)((own8 >> (8 * j)) & 0xffull) - o0;
+                const bool mine = o < (uint32_t)kOwnersPerPass;
+                const int sh = mine ? (int)(8 * o) : 0;
+                lr |= (uint32_t)((pk8 >> sh) & 0xfull) << (4 * j);
+                if (mine) pk8 += 1ull << sh;
+            }
+            const unsigned long long e0 = spread4((uint32_t)pk8), e1 = spread4((uint32_t)(pk8 >> 32));
+            const unsigned long long i0 = (unsigned long long)wave_inclusive_scan((int64_t)e0, lane);
+            const unsigned long long i1 = (unsigned long long)wave_inclusive_scan((int64_t)e1, lane);
+            if (lane == 63) { wtot[wv][0] = i0; wtot[wv][1] = i1; }
+            __syncthreads();
+            unsigned long long x0 = i0 - e0, x1 = i1 - e1, t0 = 0ull, t1 = 0ull;
+#pragma unroll
+            for (int w = 0; w < kWaves; ++w) {
+                if (w < wv) { x0 += wtot[w][0]; x1 += wtot[w][1]; }
+                t0 += wtot[w][0]; t1 += wtot[w][1];
+            }
+            excl[threadIdx.x][0] = x0;
+            excl[threadIdx.x][1] = x1;
+            {
+                unsigned long long r0 = 0ull, r1 = 0ull;       // eight 16-bit ranks
+#pragma unroll
+                for (int j = 0; j < 8; ++j) {
+                    const uint32_t o = (uint32_t)((own8 >> (8 * j)) & 0xffull) - o0;
+                    const unsigned long long v = o < (uint32_t)kOwnersPerPass ? (unsigned long long)(field16(x0, x1, (int)o) + ((lr >> (4 * j)) & 0xfu)) : 0ull;
+                    if (j < 4) r0 |= v << (16 * j);
+                    else r1 |= v << (16 * (j - 4));
+                }
+                unsigned long long *dst = reinterpret_cast<unsigned long long *>(rk + 8 * threadIdx.x);
+                dst[0] = r0;
+                dst[1] = r1;
+            }
+            __syncthreads();
+            // back to the threads that hold the rows
+#pragma unroll
+            for (int k = 0; k < kRounds; ++k) {
+                const uint32_t d = (uint32_t)((owns >> (8 * k)) & 0xffull);
+                if (d - o0 < (uint32_t)kOwnersPerPass) {
+                    const int64_t place = start[d] + rk[k * kThreads + threadIdx.x];
+                    if (place >= 0 && place < nnz) {
+                        const int64_t l = lo + c0 + k * kThreads + threadIdx.x;
+                        ridx[place] = (int64_t)row[k];
+                        if constexpr (WGT) w_out[place] = w_in[l];
+                        if constexpr (PERM) perm[l] = place + shift[d];
+                    } else flag_error(dd);
+                }
+            }
+            // segments that start inside this chunk; one that starts where the chunk's last lookup ends
+            // can only be at the end of the tile's stream and takes the chunk's totals
+            for (uint32_t b = threadIdx.x; b < nb; b += kThreads) {
+                const int64_t at = b < (uint32_t)kThreads ? at_first : bag_start(b, false);
+                if (at < c0 || at > c0 + kStream || (at == c0 + kStream && !last)) continue;
+                const int e = (int)(at - c0);
+                unsigned long long w0 = t0, w1 = t1, before8 = 0ull;
+                if (e < kStream) {
+                    const int th = e >> 3, j = e & 7;
+                    w0 = excl[th][0];
+                    w1 = excl[th][1];
+                    const unsigned long long o8 = ownb[th];
+#pragma unroll
+                    for (int jj = 0; jj < 7; ++jj) {
+                        const uint32_t o = (uint32_t)((o8 >> (8 * jj)) & 0xffull) - o0;
+                        if (jj < j && o < (uint32_t)kOwnersPerPass) before8 += 1ull << (8 * o);
+                    }
+                }
+                // segments (owner, bag) of consecutive owners lie B*T entries apart
+                int64_t *so = segoff + bls_sigma_rowwise(dd, (int)o0, t, s, (uint32_t)(b0 + b), (uint32_t)n);
+                const int64_t per_owner = dd.B * dd.T;
+#pragma unroll 1
+                for (uint32_t o = 0; o < (uint32_t)kOwnersPerPass && o0 + o < (uint32_t)dd.P; ++o, so += per_owner)
+                    *so = start[o0 + o] + field16(w0, w1, (int)o) + (uint32_t)((before8 >> (8 * o)) & 0xffull);
+            }
+            __syncthreads();
+            if (threadIdx.x < kOwnersPerPass && o0 + threadIdx.x < (uint32_t)dd.P)
+                start[o0 + threadIdx.x] += field16(t0, t1, (int)threadIdx.x);
         }
-        next += add;
+        __syncthreads();                                      // start[] is final before the next chunk reads it; LDS is free
     }
 }
 
 int64_t scan_blocks(int64_t n) { return (n + kChunk - 1) / kChunk; }
 
+uint32_t pow2_at_least(int64_t x)
+{
+    uint32_t p = 1;
+    while ((int64_t)p < x && p < (1u << 30)) p <<= 1;
+    return p;
+}
+
+// Row-wise tiles: about kTilesWanted tiles in all, none below `min_bags` bags.
+constexpr int64_t kTilesWanted = 2048;
+uint32_t bags_per_tile(const bls_ctx *ctx, int64_t min_bags)
+{
+    const int64_t n_max = ctx->B / ctx->P + (ctx->B % ctx->P ? 1 : 0);
+    const int64_t runs = (int64_t)ctx->T * ctx->P;
+    const int64_t for_count = (n_max * runs + kTilesWanted - 1) / kTilesWanted;
+    return pow2_at_least(std::max<int64_t>({for_count, min_bags, 32}));
+}
+
+// Entries of the count array: runs (table-wise), or owners * runs * tiles per run.
+int64_t count_entries(const bls_ctx *ctx, uint32_t cb)
+{
+    if (ctx->part_kind == BLS_TABLE_WISE) return (int64_t)ctx->Q * ctx->P;
+    const int64_t n_max = ctx->B / ctx->P + (ctx->B % ctx->P ? 1 : 0);
+    return (int64_t)ctx->P * ctx->P * ctx->T * ((n_max + cb - 1) / cb);
+}
+
 }  // namespace
 
+// Workspace: the count array, its scan (one more entry for the total), the scan's block sums, the
+// bucket starts in requester and in owner order.  The smallest tiles any call may choose bound the size.
 size_t bls_plan_ws_bytes(const bls_ctx *ctx)
 {
-    return (size_t)(scan_blocks(ctx->nseg) + 2 * ctx->P * ctx->P + 2) * sizeof(int64_t);
+    const int64_t n = count_entries(ctx, bags_per_tile(ctx, 0));
+    return (size_t)(2 * n + 1 + scan_blocks(n) + 2 * ctx->P * ctx->P + 2) * sizeof(int64_t);
 }
 
 int bls_launch_plan(bls_ctx *ctx, const int64_t *idx, const int64_t *off, int64_t nnz, int64_t *sendcounts,
@@ -423,49 +715,44 @@ int bls_launch_plan(bls_ctx *ctx, const int64_t *idx, const int64_t *off, int64_
 {
     (void)ws_bytes;
     const DevDesc &dd = ctx->desc;
-    const int64_t nseg = ctx->nseg, nblk = scan_blocks(nseg);
-    int64_t *sums = (int64_t *)ws;
-    int64_t *sabs = sums + nblk, *rabs = sabs + ctx->P * ctx->P;
-    const uint32_t B = (uint32_t)ctx->B;
     const bool rowwise = ctx->part_kind == BLS_ROW_WISE;
+    // tiles of about a thousand lookups or more, going by the batch's mean bag length
+    const int64_t mean = nnz / std::max<int64_t>(1, (int64_t)ctx->T * ctx->B) + 1;
+    const int64_t n_max = ctx->B / ctx->P + (ctx->B % ctx->P ? 1 : 0);
+    Tiles tg;
+    tg.cb = rowwise ? bags_per_tile(ctx, 1024 / mean) : 1u;
+    tg.tiles = rowwise ? (uint32_t)((n_max + tg.cb - 1) / tg.cb) : 1u;
+    const int64_t n = count_entries(ctx, tg.cb), nblk = scan_blocks(n);
+    int64_t *C = (int64_t *)ws;                       // n counts
+    int64_t *X = C + n;                               // n + 1 entries: their exclusive scan
+    int64_t *sums = X + n + 1;
+    int64_t *sabs = sums + nblk, *rabs = sabs + ctx->P * ctx->P;
+    int64_t *segoff_end = segoff + ctx->nseg;
+    const dim3 tgrid(tg.tiles, (unsigned)(ctx->T * ctx->P));
 
-    // lanes per bag for row-wise partitions: at least P (lane o keeps owner o's counters)
-    const int rg = ctx->P <= 8 ? 8 : ctx->P <= 16 ? 16 : ctx->P <= 32 ? 32 : 64;
-    const dim3 rgrid((B + kThreads / rg - 1) / (kThreads / rg), ctx->T);
-    if (rowwise) {
-        switch (rg) {
-        case 8: plan_count_rowwise<8><<<rgrid, kThreads, 0, st>>>(dd, idx, off, nnz, segoff + 1); break;
-        case 16: plan_count_rowwise<16><<<rgrid, kThreads, 0, st>>>(dd, idx, off, nnz, segoff + 1); break;
-        case 32: plan_count_rowwise<32><<<rgrid, kThreads, 0, st>>>(dd, idx, off, nnz, segoff + 1); break;
-        default: plan_count_rowwise<64><<<rgrid, kThreads, 0, st>>>(dd, idx, off, nnz, segoff + 1); break;
-        }
+    if (rowwise) plan_count_tiles<<<tgrid, kThreads, 0, st>>>(dd, tg, idx, off, nnz, C);
+    else plan_count_runs<<<dim3((unsigned)((n + kThreads - 1) / kThreads)), kThreads, 0, st>>>(dd, off, nnz, C);
+    if (rowwise && (int64_t)ctx->P * ctx->P * n <= (int64_t)1 << 22) {
+        plan_scan_blocks<<<dim3((unsigned)(ctx->P * ctx->P)), kWideThreads, 0, st>>>(dd, tg.tiles, C, X, n, sendcounts, sdispls, recvcounts, rdispls, sabs, rabs, segoff_end);
+    } else if (nblk <= kSmallScanTiles) {
+        plan_scan_small<<<1, kThreads, 0, st>>>(dd, tg.tiles, C, X, n, sendcounts, sdispls, recvcounts, rdispls, sabs, rabs, segoff_end);
     } else {
-        dim3 grid((B + kThreads - 1) / kThreads, ctx->Q);
-        plan_count_tablewise<<<grid, kThreads, 0, st>>>(dd, off, nnz, segoff + 1);
-    }
-    if (nblk <= kSmallScanTiles) {
-        plan_scan_small<<<1, kThreads, 0, st>>>(dd, segoff, nseg, sendcounts, sdispls, recvcounts, rdispls, sabs, rabs);
-    } else {
-        scan_block_sums<<<dim3((unsigned)nblk), kThreads, 0, st>>>(segoff + 1, nseg, sums);
+        scan_block_sums<<<dim3((unsigned)nblk), kThreads, 0, st>>>(C, n, sums);
         scan_spine<<<1, kThreads, 0, st>>>(sums, nblk);
-        scan_apply<<<dim3((unsigned)nblk), kThreads, 0, st>>>(segoff + 1, nseg, sums, segoff);
-        plan_finish<<<1, kThreads, 0, st>>>(dd, segoff, sendcounts, sdispls, recvcounts, rdispls, sabs, rabs);
+        scan_apply<<<dim3((unsigned)nblk), kThreads, 0, st>>>(C, X + 1, n, sums, X);
+        plan_finish<<<1, kThreads, 0, st>>>(dd, tg.tiles, X, sendcounts, sdispls, recvcounts, rdispls, sabs, rabs, segoff_end);
     }
-    if (nnz > 0) {
-        if (rowwise) {
-            switch (rg) {
-            case 8: plan_scatter_rowwise<8><<<rgrid, kThreads, 0, st>>>(dd, idx, off, nnz, segoff, ridx, perm, sabs, rabs, w_in, w_out); break;
-            case 16: plan_scatter_rowwise<16><<<rgrid, kThreads, 0, st>>>(dd, idx, off, nnz, segoff, ridx, perm, sabs, rabs, w_in, w_out); break;
-            case 32: plan_scatter_rowwise<32><<<rgrid, kThreads, 0, st>>>(dd, idx, off, nnz, segoff, ridx, perm, sabs, rabs, w_in, w_out); break;
-            default: plan_scatter_rowwise<64><<<rgrid, kThreads, 0, st>>>(dd, idx, off, nnz, segoff, ridx, perm, sabs, rabs, w_in, w_out); break;
-            }
-        } else {
-            const int64_t runs = (int64_t)ctx->Q * ctx->P;
-            const int64_t per_run = nnz / runs + 1;
-            const unsigned gx = (unsigned)std::min<int64_t>(256, std::max<int64_t>(1, (per_run + 2047) / 2048));
-            dim3 grid(gx, (unsigned)std::min<int64_t>(runs, 65535));
-            plan_scatter_runs<<<grid, kThreads, 0, st>>>(dd, idx, off, nnz, segoff, ridx, perm, sabs, rabs, w_in, w_out);
-        }
+    if (rowwise) {
+        if (perm && w_in) plan_place_tiles<true, true><<<tgrid, kThreads, 0, st>>>(dd, tg, idx, off, nnz, X, segoff, ridx, perm, sabs, rabs, w_in, w_out);
+        else if (perm) plan_place_tiles<true, false><<<tgrid, kThreads, 0, st>>>(dd, tg, idx, off, nnz, X, segoff, ridx, perm, sabs, rabs, w_in, w_out);
+        else if (w_in) plan_place_tiles<false, true><<<tgrid, kThreads, 0, st>>>(dd, tg, idx, off, nnz, X, segoff, ridx, perm, sabs, rabs, w_in, w_out);
+        else plan_place_tiles<false, false><<<tgrid, kThreads, 0, st>>>(dd, tg, idx, off, nnz, X, segoff, ridx, perm, sabs, rabs, w_in, w_out);
+    } else {
+        const int64_t runs = (int64_t)ctx->Q * ctx->P;
+        const int64_t per_run = std::max<int64_t>(nnz / runs, n_max) + 1;
+        const unsigned gx = (unsigned)std::min<int64_t>(256, std::max<int64_t>(1, (per_run + 2047) / 2048));
+        dim3 grid(gx, (unsigned)std::min<int64_t>(runs, 65535));
+        plan_place_runs<<<grid, kThreads, 0, st>>>(dd, idx, off, nnz, X, segoff, ridx, perm, sabs, rabs, w_in, w_out);
     }
     BLS_HIP(ctx, hipGetLastError());
     return BLS_OK;

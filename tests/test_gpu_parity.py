@@ -105,6 +105,10 @@ EDGE = [
     dict(P=5, T=7, D=64, B=5000, part_kind=0, rows=[1000] * 7, bag=("uniform", 0, 3)),       # several scan tiles, one workgroup
     dict(P=4, T=16, D=8, B=2000, part_kind=1, rows=[300] * 16, bag=("uniform", 0, 3)),       # 32 scan tiles: multi-block scan
     dict(P=3, T=40, D=4, B=3001, part_kind=0, rows=[64] * 40, bag=("uniform", 0, 2)),        # 30 scan tiles, table-wise
+    dict(P=16, T=200, D=4, B=64, part_kind=1, rows=[50] * 200, bag=("uniform", 0, 3)),       # 51200 tile counts: multi-block scan
+    dict(P=3, T=2, D=4, B=600, part_kind=1, rows=[5000, 77], bag=("uniform", 0, 200)),       # tiles of several chunks, several tiles per run
+    dict(P=2, T=1, D=4, B=128, part_kind=1, rows=[1000], bag=("fixed", 64)),                 # tiles of exactly one full chunk
+    dict(P=9, T=3, D=4, B=400, part_kind=1, rows=[900, 10, 4000], bag=("uniform", 0, 30)),   # more than eight owners: two ranking passes
 ]
 
 
@@ -166,6 +170,26 @@ def test_e4m3_codes_all_values_on_the_device():
     assert np.array_equal(bits(got[0]["Out"]), bits(ref["Out"]))
     want = oracle.e4m3_table()[codes] + np.float32(0.0)         # the sum starts from +0: -0 becomes +0
     assert np.array_equal(got[0]["Out"][0, 0].view(np.uint32), want.view(np.uint32))
+
+
+def test_rowwise_plan_chunk_edges():
+    """Hand-made offsets for the row-wise placement: a tile whose lookups fill a chunk exactly and whose
+    remaining bags are empty (they start where the chunk ends), a bag longer than two chunks, empty bags
+    in front, and a run without any lookup."""
+    P, T, B, D = 2, 2, 64, 4
+    lens = np.zeros((T, B), np.int64)
+    lens[0, 0] = 2048                                        # run (0, 0): one full chunk, then 31 empty bags
+    lens[0, 40] = 4096 + 5                                   # run (0, 1): empty bags, a long bag, empty bags
+    lens[1, 3], lens[1, 31] = 2047, 1                        # run (1, 0): ends one short of a chunk, then a single lookup
+    # exact-grid values: a bag of 4101 lookups summed in fp32 is then still exact, as the 1e-6 bound needs
+    w = synth.custom("chunks", P=P, T=T, D=D, B=B, k=1, part_kind=1, rows=[777, 10], values="grid", bag=("fixed", 0))
+    off = np.concatenate([[0], np.cumsum(lens.reshape(-1))])
+    rng = np.random.default_rng(5)
+    ix = np.concatenate([rng.integers(0, w.rows[t], int(lens[t].sum())) for t in range(T)])
+    tabs = [synth.make_table(w, t) for t in range(T)]
+    batches = [(torch.from_numpy(ix), torch.from_numpy(off))]
+    got, _ = run_gpu(w, tabs, batches)
+    check_against_oracle(w, tabs, batches, got)
 
 
 def test_all_bags_empty():
