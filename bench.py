@@ -363,6 +363,9 @@ def main() -> int:
     ap.add_argument("--size", default="full", choices=["full", "small"])
     ap.add_argument("--batches", type=int, default=16, help="distinct pre-generated batches, rotated")
     ap.add_argument("--no-uniform-control", action="store_true", help="skip the uniform-index control run")
+    ap.add_argument("--hot-rows", type=int, default=0,
+                    help="name this many popular rows per shard (counted on a batch that is not among the timed ones): "
+                         "the pooling kernels keep them in LDS (bls_set_hot_rows)")
     ap.add_argument("--flat-rows", action="store_true",
                     help="experiment: every table gets the same number of rows (same total), so that uniform indices leave "
                          "no small table for the caches to hold")
@@ -431,6 +434,11 @@ def main() -> int:
     nnzs = [int(off[-1].item()) for _, off in batches]
     pipe = Pipeline(w, tabs, max(nnzs))
     out = pipe.new_out()
+    if args.hot_rows:                                      # traffic statistics from a batch of its own
+        sx, so = synth.make_batch(w, args.batches + 1000, dev)
+        pipe.set_hot_rows(pipe.hot_rows_from_batch(sx, so.cpu(), args.hot_rows))
+        del sx, so
+        w._cdf_cache.clear()
     torch.cuda.synchronize()
     t_setup = time.perf_counter() - t_setup
     c = pipe.ctx
@@ -566,7 +574,7 @@ def main() -> int:
     sb = stage_bytes(w, int(mean_nnz))
     a_staged = sum(sb.values())
     pool_pack_gbps = (sb["pool"] + sb["pack"]) / ((stage_ms["pool"] + stage_ms["pack"]) * 1e-3) / 1e9
-    plain = args.size == "full" and not args.table_dtype and not args.bag_fixed and not args.rows_cap and not args.flat_rows
+    plain = args.size == "full" and not args.table_dtype and not args.bag_fixed and not args.rows_cap and not args.flat_rows and not args.hot_rows
     roofline = pool_roofline(sb["pool"], run["stage_ms_stats"]["pool"],
                              recorded_traffic(args.config, uniform=bool(args.index_dist)) if plain else None)
 
@@ -605,6 +613,7 @@ def main() -> int:
                    + (f" [every bag {args.bag_fixed} lookups]" if args.bag_fixed else "")
                    + (f" [tables capped at {args.rows_cap} rows]" if args.rows_cap else "")
                    + (" [all tables the same size]" if args.flat_rows else "")
+                   + (f" [{args.hot_rows} popular rows per shard named]" if args.hot_rows else "")
                    + (f" [tables stored as {args.table_dtype}]" if args.table_dtype else ""),
                    "P": w.P, "T": w.T, "D": w.D, "B": w.B, "k": w.k, "lookups_per_step": mean_nnz,
                    "table_bytes": w.table_bytes(), "distinct_batches": args.batches},

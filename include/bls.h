@@ -114,6 +114,18 @@ int bls_shard_range(const bls_ctx *ctx, int32_t t, int32_t rank, int64_t *first_
 int bls_desc_bytes(const bls_ctx *ctx, size_t *bytes);
 int bls_commit(bls_ctx *ctx, void *d_desc, size_t bytes, void *hip_stream);
 
+/* Popular rows of a shard (a hint; Related Work: systems for these models keep frequently used
+ * embedding rows in faster memory).  rows[0 .. n): local row numbers of shard (t, rank), most
+ * popular first, host memory, copied; at most BLS_HOT_ROWS_MAX are kept, repeats are dropped, a
+ * row outside the shard is BLS_EINVAL, n = 0 clears the list.  When lists are set the pooling
+ * calls may run workgroups that stay on a compute unit, copy the listed rows of the table they work
+ * on to LDS once and serve lookups of them from there; every result is the same bit for bit with or
+ * without lists, whatever they name.  Where the rows come from (counts over earlier batches, say)
+ * is the caller's business.  Takes effect with the next bls_commit (bls_desc_bytes grows by four
+ * bytes per listed row). */
+enum { BLS_HOT_ROWS_MAX = 256 };
+int bls_set_hot_rows(bls_ctx *ctx, int32_t t, int32_t rank, const int64_t *rows, int32_t n);
+
 /* Launch shape of the pooling kernels, for tests and experiments; results are the same bit for
  * bit under every setting.  lane_bytes: table bytes one lane holds of a row (4, 8, 16; 0 = the
  * library's choice); segments_per_group: consecutive segments one lane group streams (1..63, capped

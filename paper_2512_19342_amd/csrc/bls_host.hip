@@ -64,7 +64,7 @@ extern "C" int bls_create(const bls_config *cfg, bls_ctx **out)
     if (c->part_kind == BLS_ROW_WISE) c->n_loc.assign(P, T);
     for (int d = 0; d < P; ++d) c->nsum[d + 1] = c->nsum[d] + c->n_loc[d];
     c->q_t.assign(c->Q, 0); c->q_d.assign(c->Q, 0); c->q_rows.assign(c->Q, 0);
-    c->q_base.assign(c->Q, nullptr); c->q_set.assign(c->Q, 0);
+    c->q_base.assign(c->Q, nullptr); c->q_set.assign(c->Q, 0); c->q_hot.assign(c->Q, std::vector<uint32_t>());
     for (int t = 0; t < T; ++t) {
         if (c->part_kind == BLS_TABLE_WISE) {
             const int q = c->nsum[c->owner[t]] + c->t_loc[t];
@@ -145,6 +145,30 @@ extern "C" int bls_shard_range(const bls_ctx *ctx, int32_t t, int32_t rank, int6
     return BLS_OK;
 }
 
+extern "C" int bls_set_hot_rows(bls_ctx *ctx, int32_t t, int32_t rank, const int64_t *rows, int32_t n)
+{
+    if (!ctx) return BLS_EINVAL;
+    if (t < 0 || t >= ctx->T || rank < 0 || rank >= ctx->P) return bls_fail(ctx, BLS_EINVAL, "bls_set_hot_rows: table or rank out of range");
+    if (n < 0 || (n > 0 && !rows)) return bls_fail(ctx, BLS_EINVAL, "bls_set_hot_rows: bad list");
+    int q;
+    if (ctx->part_kind == BLS_TABLE_WISE) {
+        if (rank != ctx->owner[t]) return bls_fail(ctx, BLS_EINVAL, "bls_set_hot_rows: rank is not the table's owner");
+        q = ctx->t_q[t];
+    } else q = rank * ctx->T + t;
+    try {
+        std::vector<uint32_t> keep;
+        for (int32_t i = 0; i < n && keep.size() < (size_t)BLS_HOT_ROWS_MAX; ++i) {
+            if (rows[i] < 0 || rows[i] >= ctx->q_rows[q]) return bls_fail(ctx, BLS_EINVAL, "bls_set_hot_rows: a row outside the shard");
+            if (std::find(keep.begin(), keep.end(), (uint32_t)rows[i]) == keep.end()) keep.push_back((uint32_t)rows[i]);
+        }
+        ctx->q_hot[q].swap(keep);
+    } catch (...) {
+        return bls_fail(ctx, BLS_EINVAL, "out of host memory");
+    }
+    ctx->dirty = true;
+    return BLS_OK;
+}
+
 extern "C" int bls_set_pool_tuning(bls_ctx *ctx, int32_t lane_bytes, int32_t segments_per_group, int32_t xcd_map, int32_t wide_positions)
 {
     if (!ctx) return BLS_EINVAL;
@@ -205,7 +229,7 @@ namespace {
 constexpr size_t kFlagBytes = 16;
 
 struct BlobLayout {
-    size_t first, n_loc, nsum, rows, rps, t_q, q_t, q_d, q_base, q_rows, total;
+    size_t first, n_loc, nsum, rows, rps, t_q, q_t, q_d, q_base, q_rows, hot_n, hot_off, hot_rows, total;
 };
 
 size_t put(size_t &at, size_t bytes)
@@ -230,6 +254,11 @@ BlobLayout blob_layout(const bls_ctx *c)
     L.q_d = put(at, Q * sizeof(int32_t));
     L.q_base = put(at, Q * sizeof(void *));
     L.q_rows = put(at, Q * sizeof(int64_t));
+    size_t hot = 0;
+    for (const auto &h : c->q_hot) hot += h.size();
+    L.hot_n = put(at, Q * sizeof(int32_t));
+    L.hot_off = put(at, Q * sizeof(int32_t));
+    L.hot_rows = put(at, hot * sizeof(uint32_t));
     L.total = (at + 15) & ~size_t(15);
     return L;
 }
@@ -272,6 +301,18 @@ extern "C" int bls_commit(bls_ctx *ctx, void *d_desc, size_t bytes, void *hip_st
     fill(h, L.first, ctx->first); fill(h, L.n_loc, ctx->n_loc); fill(h, L.nsum, ctx->nsum);
     fill(h, L.rows, ctx->rows); fill(h, L.rps, ctx->rps); fill(h, L.t_q, ctx->t_q);
     fill(h, L.q_t, ctx->q_t); fill(h, L.q_d, ctx->q_d); fill(h, L.q_base, ctx->q_base); fill(h, L.q_rows, ctx->q_rows);
+    {
+        std::vector<int32_t> hn(ctx->Q, 0), ho(ctx->Q, 0);
+        size_t at = 0;
+        for (int q = 0; q < ctx->Q; ++q) {
+            hn[q] = (int32_t)ctx->q_hot[q].size();
+            ho[q] = (int32_t)at;
+            if (hn[q]) memcpy(h.data() + L.hot_rows + at * sizeof(uint32_t), ctx->q_hot[q].data(), hn[q] * sizeof(uint32_t));
+            at += ctx->q_hot[q].size();
+        }
+        fill(h, L.hot_n, hn); fill(h, L.hot_off, ho);
+    }
+    BLS_HIP(ctx, hipDeviceGetAttribute(&ctx->compute_units, hipDeviceAttributeMultiprocessorCount, dev));
     // a buffer seen for the first time gets a cleared error flag; a re-upload into the same buffer
     // (a shard was replaced) leaves the flag as the kernels set it
     const size_t skip = d_desc == ctx->blob ? kFlagBytes : 0;
@@ -288,6 +329,8 @@ extern "C" int bls_commit(bls_ctx *ctx, void *d_desc, size_t bytes, void *hip_st
     d.rows = (const int64_t *)(b + L.rows); d.rps = (const int64_t *)(b + L.rps); d.t_q = (const int32_t *)(b + L.t_q);
     d.q_t = (const int32_t *)(b + L.q_t); d.q_d = (const int32_t *)(b + L.q_d);
     d.q_base = (const void *const *)(b + L.q_base); d.q_rows = (const int64_t *)(b + L.q_rows);
+    d.hot_n = (const int32_t *)(b + L.hot_n); d.hot_off = (const int32_t *)(b + L.hot_off);
+    d.hot_rows = (const uint32_t *)(b + L.hot_rows);
     ctx->dirty = false;
     return BLS_OK;
 }

@@ -34,6 +34,9 @@ struct DevDesc {
     const int32_t *q_d;          // [Q]
     const void *const *q_base;   // [Q] shard storage
     const int64_t *q_rows;       // [Q] rows in the shard
+    const int32_t *hot_n;        // [Q] popular rows named for the shard (bls_set_hot_rows), 0 if none
+    const int32_t *hot_off;      // [Q] where the shard's list starts in hot_rows
+    const uint32_t *hot_rows;    // the lists, local row numbers, most popular first
     int32_t *err;                // error flag, set to 1 by kernels that skip a bad item
 };
 
@@ -66,6 +69,8 @@ struct bls_ctx {
     std::vector<int32_t> owner, n_loc, nsum, t_loc, t_q, q_t, q_d;
     std::vector<const void *> q_base;
     std::vector<uint8_t> q_set;
+    std::vector<std::vector<uint32_t>> q_hot;   // [Q] popular rows of the shard, most popular first (may be empty)
+    int compute_units = 0;        // of the device the tables were committed on
     int64_t nseg = 0, nvec = 0;   // nvec = nseg = F*T*B pooled vectors per iteration
 
     // device side
@@ -76,7 +81,7 @@ struct bls_ctx {
     DevDesc desc{};
 
     // pool launch shape overrides (bls_set_pool_tuning); 0 / -1 = the library's choice
-    int tune_lane_bytes = 0, tune_segs = 0, tune_xcd = -1, tune_wide = -1;
+    int tune_lane_bytes = 0, tune_segs = 0, tune_xcd = -1, tune_wide = -1, tune_hot = -1;
 
     // ring
     char *slots = nullptr;

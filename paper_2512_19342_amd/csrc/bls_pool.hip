@@ -100,6 +100,25 @@ template <int DT, int VB> struct Acc {
         }
         return r;
     }
+    // the same from LDS (a row copied there whole, scale and bias included)
+    static __device__ __forceinline__ Raw load_lds(const unsigned char *p, int tail)
+    {
+        Raw r;
+        if constexpr (NX == 2) {
+            const u32x2 sb = *(const __attribute__((address_space(3))) u32x2_a4 *)(p + tail);
+            r.w[NW] = sb.x; r.w[NW + 1] = sb.y;
+        }
+        if constexpr (NW == 4) {
+            const u32x4 v = *(const __attribute__((address_space(3))) u32x4 *)p;
+            r.w[0] = v.x; r.w[1] = v.y; r.w[2] = v.z; r.w[3] = v.w;
+        } else if constexpr (NW == 2) {
+            const u32x2 v = *(const __attribute__((address_space(3))) u32x2 *)p;
+            r.w[0] = v.x; r.w[1] = v.y;
+        } else {
+            r.w[0] = *(const __attribute__((address_space(3))) uint32_t *)p;
+        }
+        return r;
+    }
     // byte k of a word of codes as the number the row format gives it: an unsigned integer, or an
     // E4M3 float (v_cvt_f32_fp8, exact), times the scale, plus the bias
     template <int K>
@@ -250,34 +269,32 @@ __global__ __launch_bounds__(kThreads) void pool_rows(DevDesc dd, const int64_t 
     if (live && col_ok) acc.store(Y + out * dd.D + li * A::NV);
 }
 
-// G >= 4 lanes stream up to nb_max (< G) consecutive segments of one (q, s) block.
-// grid: x over groups (s-major, then chunks of nb_max samples), y = q.
-// WIDE: row positions as 64-bit byte offsets; otherwise 32-bit, in units of VB bytes (shards
-// below 2^32 * VB bytes), which halves the lane exchanges and the registers they occupy.
-// WGT: per-sample weights rw[] (in ridx order) multiply every row before it is added.
-template <int G, int DT, int VB, int U, bool WIDE, bool WGT>
-__global__ __launch_bounds__(kThreads) void pool_stream(DevDesc dd, const int64_t *__restrict__ ridx,
-                                                        const float *__restrict__ rw,
-                                                        const int64_t *__restrict__ segoff, int64_t nnz,
-                                                        float *__restrict__ Y, int to_slot, int nb_max, uint32_t chunks_per_s, uint32_t wgx,
-                                                        int q0, int qn)
+// The popular rows of the table a workgroup is working on, copied to LDS (pool_stream_hot), and
+// an open-addressing table from row number to the row's place there.
+constexpr uint32_t kHotBit = 0x80000000u;      // a row position with this bit set is a place in LDS
+constexpr int kHotHash = 1024;                 // slots of the row -> place table (a power of two)
+constexpr uint32_t kHotEmpty = 0xffffffffu;
+struct HotRows {
+    const unsigned char *data;                 // LDS: the rows, row_stride bytes each
+    const uint32_t *keys;                      // LDS: row number per slot, or kHotEmpty
+    const unsigned short *vals;                // LDS: the row's place
+    int n;                                     // rows held (0: none)
+};
+__device__ __forceinline__ uint32_t hot_hash(uint32_t row) { return (row * 2654435761u) >> 22; }   // 10 bits
+
+// One lane group's work: G >= 4 lanes stream up to nb_max (< G) consecutive segments of (q, s)
+// block number gx / chunks_per_s, chunk gx % chunks_per_s.  HOT: rows found in `hot` are read from
+// LDS instead of global memory.
+template <int G, int DT, int VB, int U, bool WIDE, bool WGT, bool HOT>
+__device__ __forceinline__ void stream_group(const DevDesc &dd, int q, uint32_t gx, const int64_t *__restrict__ ridx,
+                                             const float *__restrict__ rw, const int64_t *__restrict__ segoff, int64_t nnz,
+                                             float *__restrict__ Y, int to_slot, int nb_max, uint32_t chunks_per_s,
+                                             const HotRows &hot)
 {
     using A = Acc<DT, VB>;
-    // wgx = 0: grid y = q.  Otherwise a flat grid dealt out so that the workgroups an XCD receives
-    // (every eighth one) all belong to the same few tables: q = 8 * (round of tables) + XCD.
-    // Only the (owner, table) pairs q0 .. q0+qn-1 are worked on (all of them, or one owner's).
-    uint32_t bx = blockIdx.x;
-    int q = q0 + blockIdx.y;
-    if (wgx) {
-        const uint32_t xcd = blockIdx.x & 7u, r = blockIdx.x >> 3;
-        q = q0 + (int)((r / wgx) * 8u + xcd);
-        bx = r % wgx;
-        if (q >= q0 + qn) return;
-    }
     const int lane = threadIdx.x & 63;
     const int li = lane & (G - 1);
     const int gbase = lane & ~(G - 1);
-    const uint32_t gx = bx * (kThreads / G) + threadIdx.x / G;
     const uint32_t s = gx / chunks_per_s;
     const uint32_t chunk = gx - s * chunks_per_s;
     const uint32_t row_bytes = (uint32_t)payload_bytes(DT, dd.D), row_stride = (uint32_t)stride_bytes(DT, dd.D);
@@ -344,7 +361,18 @@ __global__ __launch_bounds__(kThreads) void pool_stream(DevDesc dd, const int64_
         if (c0 + li < total) {
             const int64_t r = ridx[beg + c0 + li];
             if (r < 0 || r >= shard_rows) flag_error(dd);
-            else m = (pos_t)((pos_t)r * row_units);
+            else {
+                m = (pos_t)((pos_t)r * row_units);
+                if constexpr (HOT) {
+                    if (hot.n > 0) {                          // the table is never full: the walk ends at an empty slot
+                        for (uint32_t h = hot_hash((uint32_t)r);; h = (h + 1u) & (kHotHash - 1)) {
+                            const uint32_t key = hot.keys[h];
+                            if (key == (uint32_t)r) { m = (pos_t)(kHotBit | hot.vals[h]); break; }
+                            if (key == kHotEmpty) break;
+                        }
+                    }
+                }
+            }
         }
         return m;
     };
@@ -377,8 +405,16 @@ __global__ __launch_bounds__(kThreads) void pool_stream(DevDesc dd, const int64_
             }
             // lanes without a row keep stale registers and skip the add: nothing to clear
 #pragma unroll
-            for (int u = 0; u < U; ++u)
-                if (is_row(off[u])) v[u] = A::load(base + (WIDE ? (uint64_t)off[u] : (uint64_t)off[u] * VB), tail);
+            for (int u = 0; u < U; ++u) {
+                if constexpr (HOT) {
+                    if (is_row(off[u])) {
+                        if ((uint32_t)off[u] & kHotBit) v[u] = A::load_lds(hot.data + ((uint32_t)off[u] & ~kHotBit) * row_stride + (col_ok ? li * VB : 0), tail);
+                        else v[u] = A::load(base + (uint64_t)off[u] * VB, tail);
+                    }
+                } else {
+                    if (is_row(off[u])) v[u] = A::load(base + (WIDE ? (uint64_t)off[u] : (uint64_t)off[u] * VB), tail);
+                }
+            }
             // every load of the batch has landed before the first add: said once, here, so that
             // no wait is placed between the conditional loads of the next batch
             __builtin_amdgcn_s_waitcnt(0x0f70);              // vmcnt(0)
@@ -394,6 +430,87 @@ __global__ __launch_bounds__(kThreads) void pool_stream(DevDesc dd, const int64_
         }
         mine = ahead;
         wmine = wahead;
+    }
+}
+
+// grid: x over groups (s-major, then chunks of nb_max samples), y = q.
+// WIDE: row positions as 64-bit byte offsets; otherwise 32-bit, in units of VB bytes (shards
+// below 2^32 * VB bytes), which halves the lane exchanges and the registers they occupy.
+// WGT: per-sample weights rw[] (in ridx order) multiply every row before it is added.
+template <int G, int DT, int VB, int U, bool WIDE, bool WGT>
+__global__ __launch_bounds__(kThreads) void pool_stream(DevDesc dd, const int64_t *__restrict__ ridx,
+                                                        const float *__restrict__ rw,
+                                                        const int64_t *__restrict__ segoff, int64_t nnz,
+                                                        float *__restrict__ Y, int to_slot, int nb_max, uint32_t chunks_per_s, uint32_t wgx,
+                                                        int q0, int qn)
+{
+    // wgx = 0: grid y = q.  Otherwise a flat grid dealt out so that the workgroups an XCD receives
+    // (every eighth one) all belong to the same few tables: q = 8 * (round of tables) + XCD.
+    // Only the (owner, table) pairs q0 .. q0+qn-1 are worked on (all of them, or one owner's).
+    uint32_t bx = blockIdx.x;
+    int q = q0 + blockIdx.y;
+    if (wgx) {
+        const uint32_t xcd = blockIdx.x & 7u, r = blockIdx.x >> 3;
+        q = q0 + (int)((r / wgx) * 8u + xcd);
+        bx = r % wgx;
+        if (q >= q0 + qn) return;
+    }
+    const HotRows none{nullptr, nullptr, nullptr, 0};
+    stream_group<G, DT, VB, U, WIDE, WGT, false>(dd, q, bx * (kThreads / G) + threadIdx.x / G, ridx, rw, segoff, nnz, Y, to_slot,
+                                                 nb_max, chunks_per_s, none);
+}
+
+// The same work by workgroups that stay: one workgroup of 1024 threads per compute unit, XCD x
+// (workgroups x, x + 8, ...) takes the tables q0 + x, q0 + x + 8, ... one after the other, and its
+// workgroups share a table's lane-group streams.  Before a table's first stream a workgroup copies
+// the rows the caller named as popular (bls_set_hot_rows) to LDS and builds the row -> place table;
+// lookups of those rows are then served from LDS, which takes them off the vector L1 path that
+// bounds the kernel when a few rows receive most of the lookups.  Same adds in the same order.
+constexpr int kHotThreads = 1024;
+constexpr size_t kHotLdsBytes = 128 * 1024;     // LDS for the rows themselves (of 160 KB per compute unit)
+template <int G, int DT, int VB, int U, bool WGT>
+__global__ __launch_bounds__(kHotThreads) void pool_stream_hot(DevDesc dd, const int64_t *__restrict__ ridx,
+                                                               const float *__restrict__ rw,
+                                                               const int64_t *__restrict__ segoff, int64_t nnz,
+                                                               float *__restrict__ Y, int to_slot, int nb_max,
+                                                               uint32_t chunks_per_s, int q0, int qn, int cap_rows)
+{
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
+    const uint32_t row_stride = (uint32_t)stride_bytes(DT, dd.D);
+    unsigned char *data = lds;
+    uint32_t *keys = reinterpret_cast<uint32_t *>(lds + (size_t)cap_rows * row_stride);
+    unsigned short *vals = reinterpret_cast<unsigned short *>(keys + kHotHash);
+    const uint32_t xcd = blockIdx.x & 7u, j = blockIdx.x >> 3, per_xcd = gridDim.x >> 3;
+    const uint32_t groups = chunks_per_s * (uint32_t)dd.P, per_wg = kHotThreads / G;
+    const uint32_t blocks = (groups + per_wg - 1) / per_wg;
+    for (int q = q0 + (int)xcd; q < q0 + qn; q += 8) {
+        __syncthreads();                                      // the previous table's rows are no longer read
+        const int n_hot = dd.hot_n[q] < cap_rows ? dd.hot_n[q] : cap_rows;
+        if (n_hot > 0) {
+            for (int i = threadIdx.x; i < kHotHash; i += kHotThreads) keys[i] = kHotEmpty;
+            const uint32_t *rows = dd.hot_rows + dd.hot_off[q];
+            const unsigned char *src = (const unsigned char *)dd.q_base[q];
+            const uint32_t per_row = row_stride / 16;         // 16-byte pieces per row
+            for (uint32_t i = threadIdx.x; i < (uint32_t)n_hot * per_row; i += kHotThreads) {
+                const uint32_t r = i / per_row, piece = i - r * per_row;
+                *reinterpret_cast<u32x4 *>(data + (size_t)r * row_stride + piece * 16) =
+                    *reinterpret_cast<const u32x4 *>(src + (uint64_t)rows[r] * row_stride + piece * 16);
+            }
+            __syncthreads();                                  // the table is empty before anyone inserts
+            for (int i = threadIdx.x; i < n_hot; i += kHotThreads) {
+                const uint32_t row = rows[i];
+                for (uint32_t h = hot_hash(row);; h = (h + 1u) & (kHotHash - 1)) {
+                    const uint32_t seen = atomicCAS(&keys[h], kHotEmpty, row);
+                    if (seen == kHotEmpty) { vals[h] = (unsigned short)i; break; }
+                    if (seen == row) break;                   // named twice: the first copy serves
+                }
+            }
+        }
+        __syncthreads();
+        const HotRows hot{data, keys, vals, n_hot};
+        for (uint32_t blk = j; blk < blocks; blk += per_xcd)
+            stream_group<G, DT, VB, U, false, WGT, true>(dd, q, blk * per_wg + threadIdx.x / G, ridx, rw, segoff, nnz, Y, to_slot,
+                                                         nb_max, chunks_per_s, hot);
     }
 }
 
@@ -465,6 +582,29 @@ void launch_rows(const bls_ctx *ctx, const int64_t *ridx, const float *rw, const
         const int64_t row_stride = stride_bytes(DT, ctx->D);
         bool wide = ctx->tune_wide == 1;
         for (int q = q0; q < q0 + qn; ++q) wide = wide || ctx->q_rows[q] * (row_stride / VB) >= 0xffffffffLL;
+        // popular rows named for some shard of this launch: the staying workgroups that keep them in LDS,
+        // if every row position leaves the top bit free for the "in LDS" mark
+        bool hot = VB == 16 && !wide && ctx->tune_hot != 0 && ctx->compute_units >= 8;
+        bool any_hot = false;
+        for (int q = q0; q < q0 + qn; ++q) {
+            any_hot = any_hot || !ctx->q_hot[q].empty();
+            hot = hot && ctx->q_rows[q] * (row_stride / VB) < (int64_t)kHotBit;
+        }
+        if constexpr (VB == 16) {
+            if (hot && any_hot) {
+                const int cap = (int)std::min<int64_t>(BLS_HOT_ROWS_MAX, (int64_t)kHotLdsBytes / row_stride);
+                const size_t lds = (size_t)cap * row_stride + kHotHash * (sizeof(uint32_t) + sizeof(unsigned short));
+                const dim3 hgrid((unsigned)(ctx->compute_units / 8 * 8));
+                auto launch = [&](auto kernel) -> hipError_t {
+                    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+                    if (e != hipSuccess) return e;
+                    kernel<<<hgrid, kHotThreads, lds, st>>>(ctx->desc, ridx, rw, segoff, nnz, Y, to_slot, nb, chunks, q0, qn, cap);
+                    return hipSuccess;
+                };
+                if (cap > 0 && (rw ? launch(pool_stream_hot<G, DT, VB, UU, true>) : launch(pool_stream_hot<G, DT, VB, UU, false>)) == hipSuccess)
+                    return;
+            }
+        }
         if (rw) {
             if (wide) pool_stream<G, DT, VB, UU, true, true><<<grid, kThreads, 0, st>>>(ctx->desc, ridx, rw, segoff, nnz, Y, to_slot, nb, chunks, deal, q0, qn);
             else pool_stream<G, DT, VB, UU, false, true><<<grid, kThreads, 0, st>>>(ctx->desc, ridx, rw, segoff, nnz, Y, to_slot, nb, chunks, deal, q0, qn);

@@ -58,6 +58,36 @@ class Pipeline:
         c.bls_set_ring(self.slots)
         self.n_floats = nfl
 
+    def set_hot_rows(self, lists):
+        """Name popular rows: ``lists`` maps (table, rank) to local row numbers of that shard, most
+        popular first (bls_set_hot_rows); the descriptor tables are committed again."""
+        c = self.ctx
+        for (t, rank), rows in lists.items():
+            c.bls_set_hot_rows(t, rank, rows)
+        self.desc = torch.empty(c.bls_desc_bytes(), dtype=torch.uint8, device=self.dev)
+        c.bls_commit(self.desc)
+
+    def hot_rows_from_batch(self, indices: torch.Tensor, offsets: torch.Tensor, per_shard: int):
+        """The ``per_shard`` most looked-up rows of every shard in one batch (counted with torch on the
+        batch's device): what a caller would take from its own traffic statistics."""
+        w, c = self.w, self.ctx
+        lists = {}
+        for t in range(w.T):
+            ix = indices[int(offsets[t * w.B]):int(offsets[(t + 1) * w.B])]
+            if ix.numel() == 0:
+                continue
+            rows, counts = torch.unique(ix, return_counts=True)
+            ranks = range(w.P) if w.part_kind == bls.BLS_ROW_WISE else [w.table_owner[t]]
+            for d in ranks:
+                lo, n = c.bls_shard_range(t, d)
+                sel = (rows >= lo) & (rows < lo + n)
+                r, k = rows[sel], counts[sel]
+                if r.numel() == 0:
+                    continue
+                top = torch.topk(k, min(per_shard, r.numel())).indices
+                lists[(t, d)] = (r[top] - lo).tolist()
+        return lists
+
     def new_out(self) -> torch.Tensor:
         return torch.empty((self.w.B, self.w.T, self.w.D), dtype=torch.float32, device=self.dev)
 

@@ -361,6 +361,66 @@ def test_pool_launch_variants(vb, nb, xcd):
             assert np.array_equal(bits(got[0][k]), bits(ref[k])), (w.name, k)
 
 
+HOT = [(3, "small", None), (4, "small", None), (5, "small", None), (4, "small", "u8rq"), (6, "small", None)]
+
+
+@pytest.mark.parametrize("cfg,size,storage", HOT)
+def test_hot_row_lists_change_nothing(cfg, size, storage):
+    """Popular rows named by the caller are served from LDS by workgroups that stay: whatever the lists
+    name (the batch's truly popular rows, rows never looked up, repeats, lists for some shards only),
+    every buffer equals the oracle's bit for bit, through the staged and the fused owner side, with
+    and without per-sample weights."""
+    from paper_2512_19342_amd.runner import Pipeline
+    w = synth.workload(cfg, size)
+    if storage:
+        w.table_dtype = storage
+    if w.table_dtype == "fp32":
+        w.values = "gauss"
+    dev = torch.device("cuda:0")
+    tabs_cpu = [synth.make_table(w, t) for t in range(w.T)]
+    batches = [synth.make_batch(w, it) for it in range(2)]
+    pipe = Pipeline(w, [t.to(dev) for t in tabs_cpu], max(int(o[-1]) for _, o in batches))
+    c, ctx = case_of(w), pipe.ctx
+    tabs_np = [t.numpy() for t in tabs_cpu]
+    rng = np.random.default_rng(cfg)
+    true_hot = pipe.hot_rows_from_batch(batches[0][0], batches[0][1], 300)       # more than the library keeps
+    junk = {}
+    for t in range(w.T):
+        for d in (range(w.P) if w.part_kind == 1 else [w.table_owner[t]]):
+            lo, n = ctx.bls_shard_range(t, d)
+            if n and rng.random() < 0.7:                                          # some shards get no list
+                r = rng.integers(0, n, int(rng.integers(1, 40))).tolist()
+                junk[(t, d)] = r + r[:3]                                          # with repeats
+    for lists in (true_hot, junk):
+        pipe.set_hot_rows(lists)
+        for ix, off in batches:
+            nnz = int(off[-1])
+            ref = oracle.pipeline(c, tabs_np, ix.numpy(), off.numpy())
+            out = pipe.new_out()
+            it, slot = pipe.issue(ix.to(dev), off.to(dev), nnz)
+            assert np.array_equal(bits(pipe.pooled.cpu().numpy()), bits(ref["Y"]))
+            pipe.complete(it, out)
+            assert np.array_equal(bits(out.cpu().numpy()), bits(ref["Out"]))
+            it, slot = pipe.issue_fused(ix.to(dev), off.to(dev), nnz)
+            assert np.array_equal(bits(pipe.slot_view(slot).cpu().numpy()), bits(ref["R"]))
+            pipe.complete(it, out)
+        ix, off = batches[1]
+        nnz = int(off[-1])
+        wts = torch.from_numpy(rng.uniform(-2.0, 2.0, size=nnz).astype(np.float32))
+        ref = oracle.pipeline(c, tabs_np, ix.numpy(), off.numpy(), weights=wts.numpy())
+        out = pipe.new_out()
+        it, _ = pipe.issue_weighted(ix.to(dev), off.to(dev), wts.to(dev), nnz)
+        pipe.complete(it, out)
+        assert np.array_equal(bits(out.cpu().numpy()), bits(ref["Out"]))
+        ctx.bls_check()
+    import paper_2512_19342_amd as B
+    with pytest.raises(B.BlsError) as e:                                          # a row outside the shard
+        t0 = 0
+        d0 = 0 if w.part_kind == 1 else w.table_owner[0]
+        ctx.bls_set_hot_rows(t0, d0, [ctx.bls_shard_range(t0, d0)[1]])
+    assert e.value.code == B.BLS_EINVAL
+
+
 FUSED = [synth.workload(1), synth.workload(2), synth.workload(3, "small"), synth.workload(4, "small"),
          synth.workload(5, "small")] + [
     synth.custom("edge", k=2, values="gauss", table_dtype=dt, seed=29, index_dist=("zipf", 1.1), **EDGE[i])
