@@ -565,6 +565,27 @@ def main() -> int:
         c.bls_check()
         note(f"{args.steps} steps with up to {c.K} iterations in flight: {dtr / args.steps * 1e3:.3f} ms per step")
 
+    # table-wise partitions: the whole iteration in one launch (bls_step_tablewise); beside `value`, never in it
+    one = None
+    if w.part_kind == 0 and not args.timed_only:
+        try:
+            for i in range(args.warmup):
+                pipe.step_one_launch(*batches[i % len(batches)], nnzs[i % len(batches)], out)
+            torch.cuda.synchronize()
+            t1 = time.perf_counter()
+            done = 0
+            for i in range(args.steps):
+                k = (args.warmup + i) % len(batches)
+                pipe.step_one_launch(*batches[k], nnzs[k], out)
+                done += nnzs[k]
+            torch.cuda.synchronize()
+            d1 = time.perf_counter() - t1
+            c.bls_check()
+            one = {"entry_point": "bls_step_tablewise", "ms_per_step": d1 / args.steps * 1e3, "lookups_per_s": done / d1}
+            note(f"{args.steps} one-launch steps: {one['ms_per_step']:.4f} ms per step")
+        except Exception as e:                              # a shape the one-launch kernel does not take
+            one = {"entry_point": "bls_step_tablewise", "refused": str(e)}
+
     dlrm = None
     if not args.timed_only or args.dense:
         dlrm = dense_section(args, w, pipe, batches, nnzs, note)
@@ -629,6 +650,7 @@ def main() -> int:
         "fused_owner_side": None if dtf is None else {
             "entry_point": "bls_plan + bls_embbag_pool_put + bls_unpack", "ms_per_step": dtf / args.steps * 1e3,
             "lookups_per_s": fused_lookups / dtf},
+        "one_launch_step": one,
         "ring_in_flight": None if dtr is None else {
             "K": c.K, "ms_per_step": dtr / args.steps * 1e3,
             "note": "staged path, completion deferred K-1 iterations on a second stream"},

@@ -241,6 +241,25 @@ int bls_embbag_pool_weighted(bls_ctx *ctx, const int64_t *d_ridx, const float *d
 int bls_embbag_pool_put_weighted(bls_ctx *ctx, const int64_t *d_ridx, const float *d_rweights,
                                  const int64_t *d_segoff, int64_t nnz, int32_t slot, void *hip_stream);
 
+/*
+ * A whole synchronous iteration of a TABLE-WISE partition in one launch: bls_plan, bls_embbag_pool,
+ * bls_pack, bls_ring_advance, bls_alltoallv_local and bls_unpack in that order with no other
+ * iteration in flight (the k = 0 case of section "A zero-bound parameter": issue and completion
+ * back to back).  Small batches are bound by the hand-over between the staged calls' kernels, not by
+ * the kernels; with whole tables per rank every output has a closed-form place given the lengths
+ * of the (table, mini-batch) runs, so one kernel writes them all.  Every output - counts and
+ * displacements, d_ridx, d_segoff, d_perm (or NULL), d_pooled, d_send, the receive regions of ring
+ * slot (iteration mod K) and d_out - is bit for bit what the staged calls leave.  Counts as one
+ * iteration of the ring (*iter_out, may be NULL, receives its number).  BLS_EORDER while iterations
+ * are in flight; BLS_EINVAL for a row-wise partition, for rows that are not a multiple of 16 bytes
+ * or longer than 1 KB, and for more than 2048 (table, rank) runs: use the staged calls there.
+ * Unweighted sum pooling only.  No workspace is needed.
+ */
+int bls_step_tablewise(bls_ctx *ctx, const int64_t *d_indices, const int64_t *d_offsets, int64_t nnz,
+                       int64_t *d_sendcounts, int64_t *d_sdispls, int64_t *d_recvcounts, int64_t *d_rdispls,
+                       int64_t *d_ridx, int64_t *d_segoff, int64_t *d_perm, float *d_pooled, float *d_send,
+                       float *d_out, int64_t *iter_out, void *hip_stream);
+
 /* Alltoallv completion for iteration `iter`, which must be the oldest in flight
  * (wait() completes the tail request and pops it): copy the receive regions of its
  * slot to d_out[B][T][D] fp32 and free the slot.  Table-wise: a copy.  Row-wise: the P

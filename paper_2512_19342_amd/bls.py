@@ -20,7 +20,7 @@ BLS_ACT_NONE, BLS_ACT_RELU, BLS_ACT_SIGMOID = 0, 1, 2
 BLS_TABLE_WISE, BLS_ROW_WISE = 0, 1
 
 EXPORTS = [
-    "bls_create", "bls_destroy", "bls_set_shard", "bls_shard_range", "bls_desc_bytes", "bls_commit", "bls_set_hot_rows", "bls_set_pool_tuning", "bls_sizes", "bls_pooled_counts", "bls_plan", "bls_plan_noalloc", "bls_plan_weighted",
+    "bls_create", "bls_destroy", "bls_set_shard", "bls_shard_range", "bls_desc_bytes", "bls_commit", "bls_set_hot_rows", "bls_set_pool_tuning", "bls_sizes", "bls_pooled_counts", "bls_plan", "bls_plan_noalloc", "bls_plan_weighted", "bls_step_tablewise",
     "bls_embbag_pool", "bls_embbag_pool_weighted", "bls_embbag_pool_put", "bls_embbag_pool_put_weighted", "bls_pack",
     "bls_set_ring", "bls_ring_advance", "bls_alltoallv_local", "bls_unpack", "bls_unpack_mean", "bls_ring_state",
     "bls_rank_put", "bls_rank_complete", "bls_rank_delay", "bls_mlp_layer", "bls_interact", "bls_unpack_interact", "bls_check", "bls_last_error",
@@ -62,6 +62,8 @@ def lib() -> C.CDLL:
         L.bls_pooled_counts.argtypes = [vp] + [C.POINTER(C.c_int64)] * 4
         L.bls_plan.argtypes = [vp, i64p, i64p, C.c_int64, i64p, i64p, i64p, i64p, i64p, i64p, i64p, vp, C.c_size_t, vp]
         L.bls_plan_noalloc.argtypes = [vp, i64p, i64p, C.c_int64, i64p, i64p, i64p, i64p, i64p, i64p, i64p, vp]
+        L.bls_step_tablewise.argtypes = [vp, i64p, i64p, C.c_int64, i64p, i64p, i64p, i64p, i64p, i64p, i64p, vp, vp, vp,
+                                         C.POINTER(C.c_int64), vp]
         L.bls_plan_weighted.argtypes = [vp, i64p, i64p, vp, C.c_int64, i64p, i64p, i64p, i64p, i64p, vp, i64p, i64p, vp,
                                         C.c_size_t, vp]
         L.bls_embbag_pool.argtypes = [vp, i64p, i64p, C.c_int64, vp, vp]
@@ -201,6 +203,14 @@ class Context:
     def bls_plan_noalloc(self, indices, offsets, nnz, sendcounts, sdispls, recvcounts, rdispls, ridx, segoff, perm, stream=None):
         self._call("bls_plan_noalloc", _ptr(indices), _ptr(offsets), int(nnz), _ptr(sendcounts), _ptr(sdispls),
                    _ptr(recvcounts), _ptr(rdispls), _ptr(ridx), _ptr(segoff), _ptr(perm), _stream(stream))
+
+    def bls_step_tablewise(self, indices, offsets, nnz, sendcounts, sdispls, recvcounts, rdispls, ridx, segoff, perm,
+                           pooled, send, out, stream=None) -> int:
+        it = C.c_int64()
+        self._call("bls_step_tablewise", _ptr(indices), _ptr(offsets), int(nnz), _ptr(sendcounts), _ptr(sdispls),
+                   _ptr(recvcounts), _ptr(rdispls), _ptr(ridx), _ptr(segoff), _ptr(perm), _ptr(pooled), _ptr(send), _ptr(out),
+                   C.byref(it), _stream(stream))
+        return it.value
 
     def bls_plan_weighted(self, indices, offsets, weights, nnz, sendcounts, sdispls, recvcounts, rdispls, ridx, rweights,
                           segoff, perm, ws, stream=None):

@@ -607,6 +607,48 @@ extern "C" int bls_unpack_mean(bls_ctx *ctx, int64_t iter, const int64_t *d_offs
     return unpack_common(ctx, iter, d_offsets, d_out, hip_stream);
 }
 
+// ---- a whole synchronous iteration in one launch (table-wise partitions) ------------------------
+
+extern "C" int bls_step_tablewise(bls_ctx *ctx, const int64_t *d_indices, const int64_t *d_offsets, int64_t nnz,
+                                  int64_t *d_sendcounts, int64_t *d_sdispls, int64_t *d_recvcounts, int64_t *d_rdispls,
+                                  int64_t *d_ridx, int64_t *d_segoff, int64_t *d_perm, float *d_pooled, float *d_send,
+                                  float *d_out, int64_t *iter_out, void *hip_stream)
+{
+    if (!ctx) return BLS_EINVAL;
+    if (nnz < 0 || !d_offsets || !d_sendcounts || !d_sdispls || !d_recvcounts || !d_rdispls || !d_segoff || !d_pooled ||
+        !d_send || !d_out || (nnz > 0 && (!d_indices || !d_ridx)))
+        return bls_fail(ctx, BLS_EINVAL, "bls_step_tablewise: NULL argument or negative nnz");
+    if ((((uintptr_t)d_pooled | (uintptr_t)d_send | (uintptr_t)d_out) & 15u) != 0)
+        return bls_fail(ctx, BLS_EINVAL, "bls_step_tablewise: vector buffers must be 16-byte aligned");
+    if (d_pooled == d_send || d_pooled == d_out || d_send == d_out) return bls_fail(ctx, BLS_EINVAL, "bls_step_tablewise: aliased buffers");
+    if (!ctx->slots) return bls_fail(ctx, BLS_EINVAL, "bls_step_tablewise: no ring (bls_set_ring)");
+    if (ctx->head != ctx->tail) return bls_fail(ctx, BLS_EORDER, "bls_step_tablewise: iterations in flight");
+    for (int r = 0; r < (int)ctx->rr.put_next.size(); ++r)
+        if (ctx->rr.put_next[r] != ctx->rr.done_next[r] || ctx->rr.put_next[r] != ctx->rr.put_next[0])
+            return bls_fail(ctx, BLS_EORDER, "bls_step_tablewise: per-rank iterations are in flight on this context");
+    int rc = bls_ready(ctx);
+    if (rc) return rc;
+    const int64_t j = ctx->head;
+    const int slot = (int)(j % ctx->K);
+    RingSlot &r = ctx->ring[slot];
+    rc = ensure_events(ctx, r);
+    if (rc) return rc;
+    hipStream_t st = (hipStream_t)hip_stream;
+    if (r.has_released && r.released_on != st) BLS_HIP(ctx, hipStreamWaitEvent(st, r.released, 0));
+    rc = bls_launch_step_tablewise(ctx, d_indices, d_offsets, nnz, d_sendcounts, d_sdispls, d_recvcounts, d_rdispls, d_ridx,
+                                   d_segoff, d_perm, d_pooled, d_send, (float *)(ctx->slots + (size_t)slot * ctx->slot_bytes),
+                                   d_out, st);
+    if (rc) return rc;
+    BLS_HIP(ctx, hipEventRecord(r.released, st));             // the slot is free again once this launch has run
+    r.released_on = st;
+    r.has_released = true;
+    r.state = 0;
+    r.iter = j;
+    ctx->head = ctx->tail = j + 1;
+    if (iter_out) *iter_out = j;
+    return BLS_OK;
+}
+
 // ---- per-rank issue and completion -----------------------------------------------------------
 
 static int rank_ring_init(bls_ctx *ctx)

@@ -114,6 +114,9 @@ size_t bls_plan_ws_bytes(const bls_ctx *ctx);
 // rw: weight of every lookup in ridx order, or NULL; (owner, table) pairs q0 .. q0+qn-1 only
 int bls_launch_pool(bls_ctx *ctx, const int64_t *ridx, const float *rw, const int64_t *segoff, int64_t nnz, float *Y,
                     int to_slot, int q0, int qn, hipStream_t st);
+int bls_launch_step_tablewise(bls_ctx *ctx, const int64_t *idx, const int64_t *off, int64_t nnz, int64_t *sendcounts,
+                              int64_t *sdispls, int64_t *recvcounts, int64_t *rdispls, int64_t *ridx, int64_t *segoff,
+                              int64_t *perm, float *Y, float *S, float *R, float *out, hipStream_t st);
 int bls_launch_pack(bls_ctx *ctx, const float *Y, float *S, hipStream_t st);
 int bls_launch_exchange(bls_ctx *ctx, const float *S, float *R, hipStream_t st);
 // mean_off: the batch's offsets for mean pooling (divide by the bag length), or NULL; samples b0 .. b0+bn-1 only

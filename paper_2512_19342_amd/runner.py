@@ -142,6 +142,13 @@ class Pipeline:
         it, _ = self.issue(indices, offsets, nnz, stream)
         self.complete(it, out, stream)
 
+    def step_one_launch(self, indices, offsets, nnz, out, stream=None) -> int:
+        """The whole iteration in one launch (table-wise partitions, nothing in flight): bls_step_tablewise.
+        Returns the iteration number; its receive regions are in slot ``iteration % K``."""
+        assert nnz <= self.max_nnz
+        return self.ctx.bls_step_tablewise(indices, offsets, nnz, self.sendcounts, self.sdispls, self.recvcounts, self.rdispls,
+                                           self.ridx, self.segoff, self.perm, self.pooled, self.send, out, stream)
+
     def slot_view(self, slot: int) -> torch.Tensor:
         return self.slots[slot * self.n_floats:(slot + 1) * self.n_floats]
 

@@ -46,7 +46,7 @@ def bag_sum32(w, t, idx):
     return oracle.bag_sum(synth.table_rows(w, t, ids).numpy().reshape(-1, w.D))[0]
 
 
-@pytest.mark.parametrize("cfg,storage", [(3, None), (4, None), (5, None), (4, "u8rq"), (4, "f8rq")])
+@pytest.mark.parametrize("cfg,storage", [(3, None), (4, None), (5, None), (4, "u8rq"), (4, "f8rq"), (6, None)])
 def test_full_size(cfg, storage):
     from paper_2512_19342_amd.runner import Pipeline
     w = synth.workload(cfg, "full")

@@ -459,6 +459,118 @@ def test_pool_put_equals_staged_path(w):
     pipe.ctx.bls_check()
 
 
+ONE_LAUNCH = [synth.workload(1), synth.workload(2), synth.workload(4, "small"), synth.workload(6, "small")] + [
+    synth.custom("edge", k=k, values="gauss", table_dtype=dt, seed=41, index_dist=("zipf", 1.1), **EDGE[i])
+    for i, k in ((0, 0), (1, 1), (2, 3), (7, 2), (11, 1), (13, 2)) for dt in ("fp32", "fp16", "u8rq")
+    if (EDGE[i]["D"] * {"fp32": 4, "fp16": 2, "u8rq": 1}[dt]) % 16 == 0]
+
+
+@pytest.mark.parametrize("w", ONE_LAUNCH, ids=lambda w: f"{w.name}-{w.table_dtype}-D{w.D}-P{w.P}-B{w.B}-k{w.k}")
+def test_one_launch_step_equals_staged_path(w):
+    """bls_step_tablewise writes every output of the staged calls in one launch: counts, displacements,
+    ridx, segoff, perm, the pooled, send and receive buffers and the output, all equal to the oracle's,
+    iteration after iteration (the ring slot rotates), and mixes with the staged calls on one context."""
+    from paper_2512_19342_amd.runner import Pipeline
+    if w.name in ("cfg4s", "cfg6s"):
+        w.values = "gauss"
+    dev = torch.device("cuda:0")
+    tabs_cpu = [synth.make_table(w, t) for t in range(w.T)]
+    pipe = Pipeline(w, [t.to(dev) for t in tabs_cpu], 1 << 21, want_perm=True)
+    c = case_of(w)
+    tabs_np = [t.numpy() for t in tabs_cpu]
+    for it in range(4):
+        ix, off = synth.make_batch(w, it)
+        nnz = int(off[-1])
+        ref = oracle.pipeline(c, tabs_np, ix.numpy(), off.numpy())
+        out = pipe.new_out().fill_(float("nan"))
+        for buf in (pipe.ridx, pipe.perm, pipe.segoff, pipe.sendcounts, pipe.sdispls, pipe.recvcounts, pipe.rdispls):
+            buf.fill_(-7)
+        if it == 2:                                               # a staged iteration in between
+            pipe.step(ix.to(dev), off.to(dev), nnz, out)
+            j = it
+        else:
+            j = pipe.step_one_launch(ix.to(dev), off.to(dev), nnz, out)
+        assert j == it
+        pipe.ctx.bls_check()
+        for k in ("sendcounts", "sdispls", "recvcounts", "rdispls", "segoff"):
+            assert np.array_equal(getattr(pipe, k).cpu().numpy(), ref[k]), (k, it)
+        assert np.array_equal(pipe.ridx[:nnz].cpu().numpy(), ref["ridx"]), it
+        assert np.array_equal(pipe.perm[:nnz].cpu().numpy(), ref["perm"]), it
+        for k, buf in (("Y", pipe.pooled), ("S", pipe.send), ("R", pipe.slot_view(j % pipe.ctx.K)), ("Out", out)):
+            assert np.array_equal(bits(buf.cpu().numpy().reshape(-1)), bits(ref[k].reshape(-1))), (k, it)
+    head, tail, _ = pipe.ctx.bls_ring_state()
+    assert head == tail == 4
+
+
+def test_one_launch_step_flags_bad_inputs():
+    """Bad indices and offsets through the one-launch step: flagged, never a fault; a bad index adds
+    nothing to its bag, as in the staged calls."""
+    import paper_2512_19342_amd as B
+    from paper_2512_19342_amd.runner import Pipeline
+    w = synth.workload(4, "small")
+    dev = torch.device("cuda:0")
+    tabs = [synth.make_table(w, t).to(dev) for t in range(w.T)]
+    ix, off = synth.make_batch(w, 0)
+    nnz = int(off[-1])
+    pipe = Pipeline(w, tabs, nnz, want_perm=True)
+    for how in ("index_high", "index_negative", "offsets_decrease", "offsets_past_end", "run_edge_negative"):
+        bix, boff = ix.clone(), off.clone()
+        if how == "index_high":
+            bix[nnz // 2] = 10 ** 12
+        elif how == "index_negative":
+            bix[5] = -3
+        elif how == "offsets_decrease":
+            boff[10] = boff[12] + 5
+        elif how == "offsets_past_end":
+            boff[-1] = nnz + 1000
+        else:
+            boff[w.B] = -4                                         # the first bag of the second table
+        out = pipe.new_out()
+        pipe.step_one_launch(bix.to(dev), boff.to(dev), nnz, out)
+        with pytest.raises(B.BlsError) as e:
+            pipe.ctx.bls_check()
+        assert e.value.code == B.BLS_ERANGE, how
+        if how.startswith("index"):
+            at = nnz // 2 if how == "index_high" else 5
+            goff = off.numpy().copy()
+            goff[goff > at] -= 1
+            want = oracle.pipeline(case_of(w), [t.cpu().numpy() for t in tabs], np.delete(ix.numpy(), at), goff)["Out"]
+            assert np.array_equal(bits(out.cpu().numpy()), bits(want)), how
+    out = pipe.new_out()
+    pipe.step_one_launch(ix.to(dev), off.to(dev), nnz, out)
+    pipe.ctx.bls_check()
+    ref = oracle.pipeline(case_of(w), [t.cpu().numpy() for t in tabs], ix.numpy(), off.numpy())["Out"]
+    assert np.array_equal(bits(out.cpu().numpy()), bits(ref))
+
+
+def test_one_launch_step_refusals():
+    import paper_2512_19342_amd as B
+    from paper_2512_19342_amd.runner import Pipeline
+    dev = torch.device("cuda:0")
+    w = synth.workload(3, "small")                                # row-wise
+    pipe = Pipeline(w, [synth.make_table(w, t).to(dev) for t in range(w.T)], 1 << 20)
+    ix, off = synth.make_batch(w, 0)
+    with pytest.raises(B.BlsError) as e:
+        pipe.step_one_launch(ix.to(dev), off.to(dev), int(off[-1]), pipe.new_out())
+    assert e.value.code == B.BLS_EINVAL and "row-wise" in pipe.ctx.bls_last_error()
+    w = synth.custom("odd", P=2, T=2, D=7, k=2, B=8, rows=[9, 9], part_kind=0)   # 28-byte rows
+    pipe = Pipeline(w, [synth.make_table(w, t).to(dev) for t in range(w.T)], 1 << 10)
+    ix, off = synth.make_batch(w, 0)
+    with pytest.raises(B.BlsError) as e:
+        pipe.step_one_launch(ix.to(dev), off.to(dev), int(off[-1]), pipe.new_out())
+    assert e.value.code == B.BLS_EINVAL
+    w = synth.workload(4, "small")
+    pipe = Pipeline(w, [synth.make_table(w, t).to(dev) for t in range(w.T)], 1 << 21)
+    ix, off = synth.make_batch(w, 0)
+    j, _ = pipe.issue(ix.to(dev), off.to(dev), int(off[-1]))      # an iteration in flight
+    with pytest.raises(B.BlsError) as e:
+        pipe.step_one_launch(ix.to(dev), off.to(dev), int(off[-1]), pipe.new_out())
+    assert e.value.code == B.BLS_EORDER
+    pipe.complete(j, pipe.new_out())
+    pipe.step_one_launch(ix.to(dev), off.to(dev), int(off[-1]), pipe.new_out())
+    pipe.ctx.bls_check()
+
+
 def test_pool_put_needs_the_current_slot():
     import paper_2512_19342_amd as B
     from paper_2512_19342_amd.runner import Pipeline
