@@ -363,6 +363,8 @@ def main() -> int:
     ap.add_argument("--size", default="full", choices=["full", "small"])
     ap.add_argument("--batches", type=int, default=16, help="distinct pre-generated batches, rotated")
     ap.add_argument("--no-uniform-control", action="store_true", help="skip the uniform-index control run")
+    ap.add_argument("--flat-control", action=argparse.BooleanOptionalAction, default=True,
+                    help="with the uniform-index control: also the run with equal-size tables (regenerates the tables)")
     ap.add_argument("--hot-rows", type=int, default=0,
                     help="name this many popular rows per shard (counted on a batch that is not among the timed ones): "
                          "the pooling kernels keep them in LDS (bls_set_hot_rows)")
@@ -444,9 +446,11 @@ def main() -> int:
     c = pipe.ctx
     names = ["plan", "pool", "pack", "exchange", "unpack"]
 
-    def timed_run(bts, nz, steps: int, warmup: int) -> dict:
+    def timed_run(bts, nz, steps: int, warmup: int, pipe=pipe, out=out) -> dict:
         """`warmup` untimed and `steps` timed staged steps over the batches `bts`; HIP events on the
         launch stream around every stage of every timed step."""
+        c = pipe.ctx
+
         def one_step(i: int, ev=None):
             ix, off = bts[i % len(bts)]
             nnz = nz[i % len(bts)]
@@ -621,6 +625,28 @@ def main() -> int:
         note(f"uniform-index control: {control['ms_per_step']:.3f} ms per step, pool {ums['pool']:.3f} ms = "
              f"{control['roofline']['achieved']:.0f} GB/s of algorithmic bytes")
         del ub
+        # the same again with every table the same size (same total): under uniform indices no table is
+        # then small enough for L2 or the memory-side cache to hold, every row comes from HBM
+        if args.flat_control and plain and len(set(w.rows)) > 1:
+            wf = synth.workload(args.config, args.size)
+            wf.rows, wf.index_dist = [sum(w.rows) // w.T] * w.T, ("uniform",)
+            ftabs = [synth.make_table(wf, t, dev) for t in range(wf.T)]
+            fb = [synth.make_batch(wf, it, dev) for it in range(min(args.batches, 8))]
+            fn = [int(off[-1].item()) for _, off in fb]
+            fpipe = Pipeline(wf, ftabs, max(fn))
+            frun = timed_run(fb, fn, args.steps, args.warmup, fpipe, fpipe.new_out())
+            fsb = stage_bytes(wf, int(frun["lookups"] / args.steps))
+            fms = frun["stage_ms"]
+            control["equal_tables"] = {
+                "what": f"{wf.T} tables of {wf.rows[0]} rows each ({wf.table_bytes() / 1e9:.1f} GB), uniform indices: every row from HBM",
+                "ms_per_step": frun["dt"] / args.steps * 1e3, "stage_ms": fms,
+                "roofline": pool_roofline(fsb["pool"], frun["stage_ms_stats"]["pool"], None),
+                "pool_plus_pack_gbps": (fsb["pool"] + fsb["pack"]) / ((fms["pool"] + fms["pack"]) * 1e-3) / 1e9,
+            }
+            control["equal_tables"]["pool_plus_pack_frac_of_hbm_peak"] = control["equal_tables"]["pool_plus_pack_gbps"] / PEAK_HBM_GBPS
+            note(f"equal-size tables, uniform indices: pool {fms['pool']:.3f} ms = "
+                 f"{control['equal_tables']['roofline']['achieved']:.0f} GB/s of algorithmic bytes")
+            del fpipe, ftabs, fb
 
     res = {
         "metric": "embedding lookups/sec + achieved HBM GB/s (bucket+pool+pack), 1 MI355X",
