@@ -90,6 +90,46 @@ def test_ring_bookkeeping_without_gpu(B):
             c1.bls_ring_advance(0)
 
 
+def test_partition_rule_hot_rows_and_tuning_without_gpu(B):
+    """Host-side calls that touch no GPU: the row-wise partition rule as the library states it, the checks on
+    hot-row lists and on the pool's tuning knobs, the size of the descriptor buffer, and the refusal of the
+    plan without a workspace when the problem is too large for its static array."""
+    c = B.Context(P=3, T=2, D=8, k=1, B=6, rows=[10, 4], table_owner=[0, 0], part_kind=B.BLS_ROW_WISE)
+    # blocks of ceil(rows / P) rows; trailing shards short or empty
+    assert [c.bls_shard_range(0, d) for d in range(3)] == [(0, 4), (4, 4), (8, 2)]
+    assert [c.bls_shard_range(1, d) for d in range(3)] == [(0, 2), (2, 2), (4, 0)]
+    for t, rows in ((0, 10), (1, 4)):                      # the blocks tile the table exactly
+        spans = [c.bls_shard_range(t, d) for d in range(3)]
+        assert sum(n for _, n in spans) == rows and all(spans[d][0] == min(d * -(-rows // 3), rows) for d in range(3))
+    tw = B.Context(P=2, T=2, D=8, k=1, B=4, rows=[5, 6], table_owner=[1, 0])
+    assert tw.bls_shard_range(0, 1) == (0, 5) and tw.bls_shard_range(0, 0) == (0, 0)
+    with pytest.raises(B.BlsError):
+        c.bls_shard_range(2, 0)
+    base = c.bls_desc_bytes()
+    assert 0 < base < 4096
+    c.bls_set_hot_rows(0, 1, [3, 1, 3, 0])                 # a repeat is dropped
+    assert c.bls_desc_bytes() >= base and c.bls_desc_bytes() <= base + 16
+    with pytest.raises(B.BlsError) as e:
+        c.bls_set_hot_rows(0, 2, [2])                      # shard (0, 2) has rows 0 and 1 only
+    assert e.value.code == B.BLS_EINVAL
+    with pytest.raises(B.BlsError):
+        c.bls_set_hot_rows(1, 2, [0])                      # an empty shard
+    with pytest.raises(B.BlsError):
+        tw.bls_set_hot_rows(0, 0, [0])                     # not the table's owner
+    c.bls_set_hot_rows(0, 1, [])                           # cleared
+    assert c.bls_desc_bytes() == base
+    c.bls_set_pool_tuning(lane_bytes=8, segments_per_group=3, xcd_map=0, wide_positions=1)
+    for bad in (dict(lane_bytes=5), dict(segments_per_group=64), dict(xcd_map=2), dict(wide_positions=-2)):
+        with pytest.raises(B.BlsError) as e:
+            c.bls_set_pool_tuning(**bad)
+        assert e.value.code == B.BLS_EINVAL
+    big = B.Context(P=8, T=4096, D=4, k=1, B=1 << 15, rows=[8] * 4096, table_owner=[0] * 4096, part_kind=B.BLS_ROW_WISE)
+    assert big.bls_sizes(0)["plan_ws_bytes"] > (1 << 20)
+    with pytest.raises(B.BlsError) as e:                   # refused before anything touches a GPU
+        big.bls_plan_noalloc(None, None, 0, None, None, None, None, None, None, None, 0)
+    assert e.value.code == B.BLS_ENOSPC
+
+
 def test_bench_refuses_more_than_one_gpu():
     r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
     assert r.returncode != 0 and "one GPU" in r.stderr
