@@ -20,7 +20,7 @@ BLS_ACT_NONE, BLS_ACT_RELU, BLS_ACT_SIGMOID = 0, 1, 2
 BLS_TABLE_WISE, BLS_ROW_WISE = 0, 1
 
 EXPORTS = [
-    "bls_create", "bls_destroy", "bls_set_shard", "bls_shard_range", "bls_desc_bytes", "bls_commit", "bls_set_hot_rows", "bls_set_pool_tuning", "bls_sizes", "bls_pooled_counts", "bls_plan", "bls_plan_noalloc", "bls_plan_weighted", "bls_step_tablewise",
+    "bls_create", "bls_destroy", "bls_set_shard", "bls_shard_range", "bls_desc_bytes", "bls_commit", "bls_set_hot_rows", "bls_set_pool_tuning", "bls_set_plan_tuning", "bls_sizes", "bls_pooled_counts", "bls_plan", "bls_plan_noalloc", "bls_plan_weighted", "bls_step_tablewise",
     "bls_embbag_pool", "bls_embbag_pool_weighted", "bls_embbag_pool_put", "bls_embbag_pool_put_weighted", "bls_pack",
     "bls_set_ring", "bls_ring_advance", "bls_alltoallv_local", "bls_unpack", "bls_unpack_mean", "bls_ring_state",
     "bls_rank_put", "bls_rank_complete", "bls_rank_delay", "bls_mlp_layer", "bls_interact", "bls_unpack_interact", "bls_check", "bls_last_error",
@@ -58,6 +58,7 @@ def lib() -> C.CDLL:
         L.bls_commit.argtypes = [vp, vp, C.c_size_t, vp]
         L.bls_set_hot_rows.argtypes = [vp, C.c_int32, C.c_int32, C.POINTER(C.c_int64), C.c_int32]
         L.bls_set_pool_tuning.argtypes = [vp, C.c_int32, C.c_int32, C.c_int32, C.c_int32]
+        L.bls_set_plan_tuning.argtypes = [vp, C.c_int32]
         L.bls_sizes.argtypes = [vp, C.c_int64] + [C.POINTER(C.c_size_t)] * 4
         L.bls_pooled_counts.argtypes = [vp] + [C.POINTER(C.c_int64)] * 4
         L.bls_plan.argtypes = [vp, i64p, i64p, C.c_int64, i64p, i64p, i64p, i64p, i64p, i64p, i64p, vp, C.c_size_t, vp]
@@ -175,6 +176,9 @@ class Context:
     def bls_set_hot_rows(self, t: int, rank: int, rows: Sequence[int]):
         a = (C.c_int64 * max(len(rows), 1))(*[int(x) for x in rows])
         self._call("bls_set_hot_rows", int(t), int(rank), a, len(rows))
+
+    def bls_set_plan_tuning(self, scan_while_placing=-1):
+        self._call("bls_set_plan_tuning", int(scan_while_placing))
 
     def bls_set_pool_tuning(self, lane_bytes=0, segments_per_group=0, xcd_map=-1, wide_positions=-1):
         self._call("bls_set_pool_tuning", int(lane_bytes), int(segments_per_group), int(xcd_map), int(wide_positions))

@@ -183,6 +183,14 @@ extern "C" int bls_set_pool_tuning(bls_ctx *ctx, int32_t lane_bytes, int32_t seg
     return BLS_OK;
 }
 
+extern "C" int bls_set_plan_tuning(bls_ctx *ctx, int32_t scan_while_placing)
+{
+    if (!ctx) return BLS_EINVAL;
+    if (scan_while_placing < -1 || scan_while_placing > 1) return bls_fail(ctx, BLS_EINVAL, "bls_set_plan_tuning: value out of range");
+    ctx->tune_plan_scan = scan_while_placing;
+    return BLS_OK;
+}
+
 extern "C" int bls_sizes(const bls_ctx *ctx, int64_t max_nnz, size_t *plan_ws_bytes, size_t *pooled_bytes,
                          size_t *send_bytes, size_t *slot_bytes)
 {

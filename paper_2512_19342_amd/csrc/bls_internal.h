@@ -82,6 +82,7 @@ struct bls_ctx {
 
     // pool launch shape overrides (bls_set_pool_tuning); 0 / -1 = the library's choice
     int tune_lane_bytes = 0, tune_segs = 0, tune_xcd = -1, tune_wide = -1, tune_hot = -1;
+    int tune_plan_scan = -1;      // row-wise plan: 0 = always a scan launch, otherwise the placing workgroups scan where they can
 
     // ring
     char *slots = nullptr;

@@ -16,6 +16,8 @@
 //                packed per-owner counters over the workgroup (running counts carried from chunk
 //                to chunk) and writes ridx, perm and the weights; the segment starts fall out of
 //                the same running counts.
+// Row-wise with at most eight ranks there is no scan launch: the tiles are fewer and larger, and
+// every placing workgroup adds the count array up for itself (plan_place_tiles_scan).
 #include <algorithm>
 
 #include "bls_internal.h"
@@ -511,38 +513,35 @@ __device__ __forceinline__ uint32_t field16(unsigned long long w0, unsigned long
 // the chunk's lookups of the same owner.  The ranks return through LDS to the threads that hold
 // the rows; running totals carry the rank from chunk to chunk.  The start of segment (d, bag) is
 // the same count taken at the bag's first lookup.
-template <bool PERM, bool WGT>
-__global__ __launch_bounds__(kThreads) void plan_place_tiles(DevDesc dd, Tiles tg, const int64_t *__restrict__ idx,
-                                                             const int64_t *__restrict__ off, int64_t nnz,
-                                                             const int64_t *__restrict__ X, int64_t *__restrict__ segoff,
-                                                             int64_t *__restrict__ ridx, int64_t *__restrict__ perm,
-                                                             const int64_t *__restrict__ sabs,
-                                                             const int64_t *__restrict__ rabs,
-                                                             const float *__restrict__ w_in, float *__restrict__ w_out)
-{
-    __shared__ unsigned long long ownb[kThreads];             // owners of the chunk's lookups, a byte each (0xff: none)
-    __shared__ unsigned long long excl[kThreads][2];          // per thread: same-owner lookups before its first one
-    __shared__ __attribute__((aligned(16))) unsigned short rk[kStream];   // rank of every lookup among its owner's
-    __shared__ unsigned long long wtot[kWaves][2];            // per wavefront: its lookups per owner
-    __shared__ int64_t start[64];                             // owner's next free place: tile start + running count
-    __shared__ int64_t shift[64];                             // owner-side place -> requester-side place
+// LDS of one placing workgroup.
+struct PlaceLds {
+    unsigned long long ownb[kThreads];             // owners of the chunk's lookups, a byte each (0xff: none)
+    unsigned long long excl[kThreads][2];          // per thread: same-owner lookups before its first one
+    __attribute__((aligned(16))) unsigned short rk[kStream];   // rank of every lookup among its owner's
+    unsigned long long wtot[kWaves][2];            // per wavefront: its lookups per owner
+    int64_t start[64];                             // owner's next free place: tile start + running count
+    int64_t shift[64];                             // owner-side place -> requester-side place
+};
 
-    const int t = blockIdx.y / dd.P, s = blockIdx.y - t * dd.P;
-    const uint32_t c = blockIdx.x;
-    const int64_t f = bls_first(dd, s), n = bls_first(dd, s + 1) - f;
-    const int64_t b0 = (int64_t)c * tg.cb;
-    if (b0 >= n) return;                                      // uniform over the workgroup: no bags in this tile
+// Places the lookups [lo, lo + len) of a tile of run (t, s): the nb bags from bag b0 of the run's n.
+// L.start and L.shift are set by the caller (threads below P) before the call; no barrier is needed
+// in between.
+template <bool PERM, bool WGT>
+__device__ __forceinline__ void place_tile(const DevDesc &dd, PlaceLds &L, const int64_t *__restrict__ idx,
+                                           const int64_t *__restrict__ off, int64_t nnz, int64_t *__restrict__ segoff,
+                                           int64_t *__restrict__ ridx, int64_t *__restrict__ perm,
+                                           const float *__restrict__ w_in, float *__restrict__ w_out, int t, int s,
+                                           int64_t n, int64_t b0, uint32_t nb, int64_t lo, int64_t len)
+{
+    auto &ownb = L.ownb;
+    auto &excl = L.excl;
+    auto &rk = L.rk;
+    auto &wtot = L.wtot;
+    auto &start = L.start;
+    auto &shift = L.shift;
     const int64_t rows = dd.rows[t], rps = dd.rps[t];
-    const uint32_t nb = (uint32_t)(n - b0 < tg.cb ? n - b0 : tg.cb);
-    const int64_t g0 = (int64_t)t * dd.B + f + b0;
-    int64_t lo, hi;
-    tile_range(dd, off, g0, nb, nnz, lo, hi);
-    const int64_t len = hi - lo;
+    const int64_t g0 = (int64_t)t * dd.B + bls_first(dd, s) + b0;
     const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
-    if (threadIdx.x < dd.P) {
-        start[threadIdx.x] = X[tile_entry(dd, tg, threadIdx.x, s, t, c)];
-        shift[threadIdx.x] = PERM ? sabs[s * dd.P + threadIdx.x] - rabs[threadIdx.x * dd.P + s] : 0;
-    }
     const float inv = 1.f / (float)rps;
     const int passes = (dd.P + kOwnersPerPass - 1) / kOwnersPerPass;
 
@@ -672,6 +671,143 @@ __global__ __launch_bounds__(kThreads) void plan_place_tiles(DevDesc dd, Tiles t
     }
 }
 
+template <bool PERM, bool WGT>
+__global__ __launch_bounds__(kThreads) void plan_place_tiles(DevDesc dd, Tiles tg, const int64_t *__restrict__ idx,
+                                                             const int64_t *__restrict__ off, int64_t nnz,
+                                                             const int64_t *__restrict__ X, int64_t *__restrict__ segoff,
+                                                             int64_t *__restrict__ ridx, int64_t *__restrict__ perm,
+                                                             const int64_t *__restrict__ sabs,
+                                                             const int64_t *__restrict__ rabs,
+                                                             const float *__restrict__ w_in, float *__restrict__ w_out)
+{
+    __shared__ PlaceLds L;
+    const int t = blockIdx.y / dd.P, s = blockIdx.y - t * dd.P;
+    const uint32_t c = blockIdx.x;
+    const int64_t f = bls_first(dd, s), n = bls_first(dd, s + 1) - f;
+    const int64_t b0 = (int64_t)c * tg.cb;
+    if (b0 >= n) return;                                      // uniform over the workgroup: no bags in this tile
+    const uint32_t nb = (uint32_t)(n - b0 < tg.cb ? n - b0 : tg.cb);
+    int64_t lo, hi;
+    tile_range(dd, off, (int64_t)t * dd.B + f + b0, nb, nnz, lo, hi);
+    if (threadIdx.x < dd.P) {
+        L.start[threadIdx.x] = X[tile_entry(dd, tg, threadIdx.x, s, t, c)];
+        L.shift[threadIdx.x] = PERM ? sabs[s * dd.P + threadIdx.x] - rabs[threadIdx.x * dd.P + s] : 0;
+    }
+    place_tile<PERM, WGT>(dd, L, idx, off, nnz, segoff, ridx, perm, w_in, w_out, t, s, n, b0, nb, lo, hi - lo);
+}
+
+// Row-wise with at most eight ranks: placing without a scan launch.  A tile's start for owner d is the
+// sum of all counts before entry (d, s, t, c) in owner order; an owner's entries are a row of P*T*tiles
+// counts, so the eight starts are the totals of the earlier rows plus a prefix of the own row.  Every
+// workgroup adds the count array up for itself (it is small and sits in L2): 32 threads per owner,
+// keeping apart what lies before this tile, what belongs to earlier requesters and to this requester
+// (the last two place the buckets in requester order, for perm).  The first workgroup also derives
+// the alltoallv counts and displacements.  Sums are kept in 32 bits: for batches below 2^32 lookups.
+template <bool PERM, bool WGT>
+__global__ __launch_bounds__(kThreads) void plan_place_tiles_scan(DevDesc dd, Tiles tg, const int64_t *__restrict__ idx,
+                                                                  const int64_t *__restrict__ off, int64_t nnz,
+                                                                  const int64_t *__restrict__ C,
+                                                                  int64_t *__restrict__ sendcounts, int64_t *__restrict__ sdispls,
+                                                                  int64_t *__restrict__ recvcounts, int64_t *__restrict__ rdispls,
+                                                                  int64_t *__restrict__ segoff, int64_t *__restrict__ ridx,
+                                                                  int64_t *__restrict__ perm, const float *__restrict__ w_in,
+                                                                  float *__restrict__ w_out)
+{
+    __shared__ PlaceLds L;
+    __shared__ uint32_t part[8][4];                   // per owner: total, earlier requesters, this requester, before this tile
+    __shared__ int64_t blk[64], rowtot[8];            // the first workgroup: lookups per (owner, requester) block
+
+    const int P = dd.P;
+    const int t = blockIdx.y / P, s = blockIdx.y - t * P;
+    const uint32_t c = blockIdx.x;
+    const int64_t f = bls_first(dd, s), n = bls_first(dd, s + 1) - f;
+    const int64_t b0 = (int64_t)c * tg.cb;
+    const bool first_wg = blockIdx.x == 0 && blockIdx.y == 0;
+    if (b0 >= n && !first_wg) return;                 // uniform over the workgroup: no bags in this tile
+
+    const uint32_t per_req = (uint32_t)dd.T * tg.tiles, rowlen = (uint32_t)P * per_req;
+    {
+        const int d = threadIdx.x >> 5, l = threadIdx.x & 31;
+        const uint32_t a0 = (uint32_t)s * per_req, a1 = a0 + per_req, at = a0 + (uint32_t)t * tg.tiles + c;
+        uint32_t tot = 0, early = 0, same = 0, before = 0;
+        if (d < P) {
+            const int64_t *row = C + (int64_t)d * rowlen;
+            constexpr int kAhead = 8;                 // independent loads in flight
+            for (uint32_t j0 = l; j0 < rowlen; j0 += 32 * kAhead) {
+                uint32_t x[kAhead];
+#pragma unroll
+                for (int k = 0; k < kAhead; ++k) x[k] = j0 + 32 * k < rowlen ? (uint32_t)row[j0 + 32 * k] : 0u;
+#pragma unroll
+                for (int k = 0; k < kAhead; ++k) {
+                    const uint32_t j = j0 + 32 * k;
+                    tot += x[k];
+                    if (j < a0) early += x[k];
+                    else if (j < a1) same += x[k];
+                    if (j < at) before += x[k];
+                }
+            }
+        }
+#pragma unroll
+        for (int sh = 16; sh >= 1; sh >>= 1) {
+            tot += __shfl_xor(tot, sh, 64);
+            early += __shfl_xor(early, sh, 64);
+            same += __shfl_xor(same, sh, 64);
+            before += __shfl_xor(before, sh, 64);
+        }
+        if (l == 0) { part[d][0] = tot; part[d][1] = early; part[d][2] = same; part[d][3] = before; }
+    }
+    __syncthreads();
+    if (threadIdx.x < P) {
+        const int d = threadIdx.x;
+        int64_t owners_before = 0, early_all = 0, same_before = 0;
+        for (int o = 0; o < P; ++o) {
+            if (o < d) { owners_before += part[o][0]; same_before += part[o][2]; }
+            early_all += part[o][1];
+        }
+        L.start[d] = owners_before + part[d][3];
+        // bucket (s, d) starts at early_all + same_before in requester order, at owners_before + early(d) in owner order
+        L.shift[d] = PERM ? (early_all + same_before) - (owners_before + (int64_t)part[d][1]) : 0;
+    }
+
+    if (first_wg) {
+        const int e = threadIdx.x >> 2, l = threadIdx.x & 3;  // block e = d * P + s', four threads each
+        uint32_t sum = 0;
+        if (e < P * P)
+            for (uint32_t j = l; j < per_req; j += 4) sum += (uint32_t)C[(int64_t)e * per_req + j];
+        sum += __shfl_xor(sum, 1, 64);
+        sum += __shfl_xor(sum, 2, 64);
+        if (l == 0 && e < P * P) blk[e] = sum;
+        __syncthreads();
+        if (threadIdx.x < P) {                            // lookups per requester
+            int64_t run = 0;
+            for (int d = 0; d < P; ++d) run += blk[d * P + threadIdx.x];
+            rowtot[threadIdx.x] = run;
+        }
+        __syncthreads();
+        if (threadIdx.x < P * P) {
+            const int d = threadIdx.x / P, sp = threadIdx.x - d * P;
+            int64_t rd = 0, sd = 0;
+            for (int r = 0; r < sp; ++r) rd += blk[d * P + r];
+            for (int o = 0; o < d; ++o) sd += blk[o * P + sp];
+            recvcounts[d * P + sp] = blk[d * P + sp];
+            rdispls[d * P + sp] = rd;
+            sendcounts[sp * P + d] = blk[d * P + sp];
+            sdispls[sp * P + d] = sd;
+        }
+        if (threadIdx.x == 0) {
+            int64_t all = 0;
+            for (int r = 0; r < P; ++r) all += rowtot[r];
+            segoff[dd.nseg] = all;
+        }
+        if (b0 >= n) return;
+    }
+
+    const uint32_t nb = (uint32_t)(n - b0 < tg.cb ? n - b0 : tg.cb);
+    int64_t lo, hi;
+    tile_range(dd, off, (int64_t)t * dd.B + f + b0, nb, nnz, lo, hi);
+    place_tile<PERM, WGT>(dd, L, idx, off, nnz, segoff, ridx, perm, w_in, w_out, t, s, n, b0, nb, lo, hi - lo);
+}
+
 int64_t scan_blocks(int64_t n) { return (n + kChunk - 1) / kChunk; }
 
 uint32_t pow2_at_least(int64_t x)
@@ -683,11 +819,11 @@ uint32_t pow2_at_least(int64_t x)
 
 // Row-wise tiles: about kTilesWanted tiles in all, none below `min_bags` bags.
 constexpr int64_t kTilesWanted = 2048;
-uint32_t bags_per_tile(const bls_ctx *ctx, int64_t min_bags)
+uint32_t bags_per_tile(const bls_ctx *ctx, int64_t min_bags, int64_t tiles_wanted = kTilesWanted)
 {
     const int64_t n_max = ctx->B / ctx->P + (ctx->B % ctx->P ? 1 : 0);
     const int64_t runs = (int64_t)ctx->T * ctx->P;
-    const int64_t for_count = (n_max * runs + kTilesWanted - 1) / kTilesWanted;
+    const int64_t for_count = (n_max * runs + tiles_wanted - 1) / tiles_wanted;
     return pow2_at_least(std::max<int64_t>({for_count, min_bags, 32}));
 }
 
@@ -719,8 +855,10 @@ int bls_launch_plan(bls_ctx *ctx, const int64_t *idx, const int64_t *off, int64_
     // tiles of about a thousand lookups or more, going by the batch's mean bag length
     const int64_t mean = nnz / std::max<int64_t>(1, (int64_t)ctx->T * ctx->B) + 1;
     const int64_t n_max = ctx->B / ctx->P + (ctx->B % ctx->P ? 1 : 0);
+    // row-wise with few ranks: the placing workgroups add the counts up themselves, no scan launch
+    const bool own_scan = rowwise && ctx->P <= 8 && nnz < ((int64_t)1 << 32) && ctx->tune_plan_scan != 0;
     Tiles tg;
-    tg.cb = rowwise ? bags_per_tile(ctx, 1024 / mean) : 1u;
+    tg.cb = rowwise ? bags_per_tile(ctx, 1024 / mean, own_scan ? 1024 : kTilesWanted) : 1u;
     tg.tiles = rowwise ? (uint32_t)((n_max + tg.cb - 1) / tg.cb) : 1u;
     const int64_t n = count_entries(ctx, tg.cb), nblk = scan_blocks(n);
     int64_t *C = (int64_t *)ws;                       // n counts
@@ -732,7 +870,9 @@ int bls_launch_plan(bls_ctx *ctx, const int64_t *idx, const int64_t *off, int64_
 
     if (rowwise) plan_count_tiles<<<tgrid, kThreads, 0, st>>>(dd, tg, idx, off, nnz, C);
     else plan_count_runs<<<dim3((unsigned)((n + kThreads - 1) / kThreads)), kThreads, 0, st>>>(dd, off, nnz, C);
-    if (rowwise && (int64_t)ctx->P * ctx->P * n <= (int64_t)1 << 22) {
+    if (own_scan) {
+        // no launch
+    } else if (rowwise && (int64_t)ctx->P * ctx->P * n <= (int64_t)1 << 22) {
         plan_scan_blocks<<<dim3((unsigned)(ctx->P * ctx->P)), kWideThreads, 0, st>>>(dd, tg.tiles, C, X, n, sendcounts, sdispls, recvcounts, rdispls, sabs, rabs, segoff_end);
     } else if (nblk <= kSmallScanTiles) {
         plan_scan_small<<<1, kThreads, 0, st>>>(dd, tg.tiles, C, X, n, sendcounts, sdispls, recvcounts, rdispls, sabs, rabs, segoff_end);
@@ -742,7 +882,14 @@ int bls_launch_plan(bls_ctx *ctx, const int64_t *idx, const int64_t *off, int64_
         scan_apply<<<dim3((unsigned)nblk), kThreads, 0, st>>>(C, X + 1, n, sums, X);
         plan_finish<<<1, kThreads, 0, st>>>(dd, tg.tiles, X, sendcounts, sdispls, recvcounts, rdispls, sabs, rabs, segoff_end);
     }
-    if (rowwise) {
+    if (own_scan) {
+#define BLS_PLACE_SCAN(PERM, WGT) plan_place_tiles_scan<PERM, WGT><<<tgrid, kThreads, 0, st>>>(dd, tg, idx, off, nnz, C, sendcounts, sdispls, recvcounts, rdispls, segoff, ridx, perm, w_in, w_out)
+        if (perm && w_in) BLS_PLACE_SCAN(true, true);
+        else if (perm) BLS_PLACE_SCAN(true, false);
+        else if (w_in) BLS_PLACE_SCAN(false, true);
+        else BLS_PLACE_SCAN(false, false);
+#undef BLS_PLACE_SCAN
+    } else if (rowwise) {
         if (perm && w_in) plan_place_tiles<true, true><<<tgrid, kThreads, 0, st>>>(dd, tg, idx, off, nnz, X, segoff, ridx, perm, sabs, rabs, w_in, w_out);
         else if (perm) plan_place_tiles<true, false><<<tgrid, kThreads, 0, st>>>(dd, tg, idx, off, nnz, X, segoff, ridx, perm, sabs, rabs, w_in, w_out);
         else if (w_in) plan_place_tiles<false, true><<<tgrid, kThreads, 0, st>>>(dd, tg, idx, off, nnz, X, segoff, ridx, perm, sabs, rabs, w_in, w_out);

@@ -28,7 +28,7 @@ def bits(a):
     return a.view(np.uint32) if a.dtype == np.float32 else a
 
 
-def run_gpu(w, tabs_cpu, batches, want_perm=True, tuning=None):
+def run_gpu(w, tabs_cpu, batches, want_perm=True, tuning=None, plan_scan=None):
     from paper_2512_19342_amd.runner import Pipeline
     dev = torch.device("cuda:0")
     tabs = [t.to(dev) for t in tabs_cpu]
@@ -36,6 +36,8 @@ def run_gpu(w, tabs_cpu, batches, want_perm=True, tuning=None):
     pipe = Pipeline(w, tabs, max_nnz, want_perm=want_perm)
     if tuning:
         pipe.ctx.bls_set_pool_tuning(**tuning)
+    if plan_scan is not None:
+        pipe.ctx.bls_set_plan_tuning(plan_scan)
     res = []
     for ix, off in batches:
         nnz = int(off[-1])
@@ -189,6 +191,38 @@ def test_rowwise_plan_chunk_edges():
     tabs = [synth.make_table(w, t) for t in range(T)]
     batches = [(torch.from_numpy(ix), torch.from_numpy(off))]
     got, _ = run_gpu(w, tabs, batches)
+    check_against_oracle(w, tabs, batches, got)
+
+
+ROWWISE_EDGE = [spec for spec in EDGE if spec["part_kind"] == 1]
+
+
+@pytest.mark.parametrize("spec", ROWWISE_EDGE, ids=lambda s: f"P{s['P']}-T{s['T']}-B{s['B']}")
+@pytest.mark.parametrize("want_perm", [True, False])
+def test_rowwise_plan_in_three_launches(spec, want_perm):
+    """bls_plan leaves the scan to the placing workgroups for a row-wise partition where it can (the
+    default, which every other test runs); the three-launch form (count, scan, place) must give the
+    same plan."""
+    w = synth.custom("edge3", k=1, values="grid", seed=29, index_dist=("zipf", 1.1), **spec)
+    tabs = [synth.make_table(w, t) for t in range(w.T)]
+    batches = [synth.make_batch(w, it) for it in range(2)]
+    got, _ = run_gpu(w, tabs, batches, want_perm=want_perm, plan_scan=0)
+    c = case_of(w)
+    tabs_np = [t.numpy() for t in tabs]
+    for (ix, off), g in zip(batches, got):
+        ref = oracle.pipeline(c, tabs_np, ix.numpy(), off.numpy())
+        for k in ("sendcounts", "sdispls", "recvcounts", "rdispls", "ridx", "segoff") + (("perm",) if want_perm else ()):
+            assert np.array_equal(g[k], ref[k]), k
+        assert np.array_equal(bits(g["Out"]), bits(ref["Out"]))
+
+
+@pytest.mark.parametrize("cfg", [3, 5])
+@pytest.mark.parametrize("scan_while_placing", [0, 1])
+def test_rowwise_workloads_in_either_plan_form(cfg, scan_while_placing):
+    w = synth.workload(cfg, "small")
+    tabs = [synth.make_table(w, t) for t in range(w.T)]
+    batches = [synth.make_batch(w, it) for it in range(3)]
+    got, _ = run_gpu(w, tabs, batches, plan_scan=scan_while_placing)
     check_against_oracle(w, tabs, batches, got)
 
 
