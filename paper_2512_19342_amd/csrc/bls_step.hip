@@ -21,7 +21,7 @@ constexpr int kThreads = 256;
 constexpr int kWaves = kThreads / 64;
 constexpr int kMaxRuns = 2048;                 // runs (q, s) whose starts one workgroup scans in LDS
 constexpr int kPerThread = kMaxRuns / kThreads;
-constexpr int kU = 4;                          // independent row loads per lane before the first add
+constexpr int kU = 8;                          // independent row loads per lane before the first add
 
 __device__ __forceinline__ void flag_error(const DevDesc &dd) { atomicOr(dd.err, 1); }
 
@@ -167,12 +167,15 @@ __global__ __launch_bounds__(kThreads) void step_tablewise(DevDesc dd, const int
 
     A acc;
     acc.zero();
+    int64_t ahead = li < len ? idx[beg + li] : -1;            // a block's row numbers are asked for one block early
     for (int64_t c0 = 0; __any(c0 < len); c0 += G) {
         const int64_t left = len - c0;
         const int rem = left < 0 ? 0 : (left > G ? G : (int)left);
         int64_t mine = -1;
+        const int64_t got = ahead;
+        ahead = c0 + G + li < len ? idx[beg + c0 + G + li] : -1;
         if (li < rem) {
-            mine = idx[beg + c0 + li];
+            mine = got;
             if (mine < 0 || mine >= rows) { flag_error(dd); mine = -1; }       // adds nothing to the bag
             ridx[place + c0 + li] = mine;
             if (perm) perm[beg + c0 + li] = place + c0 + li + to_send;
