@@ -193,3 +193,74 @@ def test_full_size_weighted(cfg):
             want, _ = oracle.bag_sum(parts)
         assert np.array_equal(out[b, t].cpu().numpy().view(np.uint32), want.view(np.uint32)), (t, b)
     print(f"  {n_samples} sampled weighted bags match", flush=True)
+
+
+@pytest.mark.parametrize("part_kind,L", [(0, 600), (1, 1100), (1, 2100)], ids=["tablewise-2.5e9", "rowwise-2.3e9", "rowwise-4.4e9"])
+def test_more_than_two_to_the_31_lookups(part_kind, L):
+    """A batch of 2.3e9 to 4.4e9 lookups (the last one beyond 2^32, where the row-wise plan scans in 64 bits): positions, counts and displacements beyond 32 bits.  The expected values
+    are worked out with torch on the device from the definitions: owner-side order is (owner, requester,
+    table, sample, position), which for these two shapes is the input order (table-wise, one table per
+    rank) or the input order filtered by owner (row-wise, one table); table values are small integers, so
+    every bag sum is exact in fp32 whatever the order."""
+    from paper_2512_19342_amd.runner import Pipeline
+    dev = torch.device("cuda:0")
+    B, D = 1 << 21, 4
+    if part_kind == 0:
+        P, T, rows = 2, 2, [1000, 777]
+    else:
+        P, T, rows = 4, 1, [100003]
+    nnz = T * B * L
+    assert nnz > 1 << 31
+    w = synth.custom("huge", P=P, T=T, D=D, B=B, k=1, part_kind=part_kind, rows=rows, bag=("fixed", L))
+    print(f"large batch, part_kind {part_kind}: {nnz} lookups", flush=True)
+    g = torch.Generator(device=dev)
+    g.manual_seed(20250 + L)
+    ix = torch.cat([torch.randint(0, rows[t], (B * L,), generator=g, device=dev, dtype=torch.int64) for t in range(T)])
+    off = torch.arange(T * B + 1, device=dev, dtype=torch.int64) * L
+    tabs = [((torch.arange(r, device=dev) % 7).to(torch.float32)[:, None] + torch.arange(D, device=dev, dtype=torch.float32)[None, :]).contiguous()
+            for r in rows]
+    pipe = Pipeline(w, tabs, nnz)
+    out = pipe.new_out()
+    it, slot = pipe.issue(ix, off, nnz)
+    pipe.complete(it, out)
+    pipe.ctx.bls_check()
+    torch.cuda.synchronize()
+
+    rps = [(r + P - 1) // P for r in rows]
+    if part_kind == 0:
+        assert torch.equal(pipe.ridx[:nnz], ix)
+        assert torch.equal(pipe.segoff, off)
+        sc = pipe.sendcounts.view(P, P).cpu().numpy()
+        first = [s * (B // P) + min(s, B % P) for s in range(P + 1)]
+        for s in range(P):
+            for d in range(P):
+                assert sc[s, d] == (first[s + 1] - first[s]) * L      # rank d owns table d
+    else:
+        owner = torch.div(ix, rps[0], rounding_mode="floor").to(torch.int8)
+        per_bag = [(owner == d).view(B, L).sum(1) for d in range(P)]
+        totals = [int(c.sum()) for c in per_bag]
+        assert sum(totals) == nnz
+        at = [sum(totals[:d]) for d in range(P)]                      # start of owner d's block; then the next free place
+        step = 1 << 28                                                # masked selection in pieces torch can index
+        for c0 in range(0, nnz, step):
+            ixc, ownc = ix[c0:c0 + step], owner[c0:c0 + step]
+            for d in range(P):
+                want = ixc[ownc == d] - d * rps[0]
+                assert torch.equal(pipe.ridx[at[d]:at[d] + want.numel()], want), f"ridx of owner {d}, lookups from {c0}"
+                at[d] += want.numel()
+        assert at == [sum(totals[:d + 1]) for d in range(P)]
+        counts = torch.stack(per_bag).reshape(-1)                     # (owner, bag): segment lengths in segment order
+        want_seg = torch.zeros(P * B + 1, dtype=torch.int64, device=dev)
+        torch.cumsum(counts, 0, out=want_seg[1:])
+        assert torch.equal(pipe.segoff, want_seg)
+        rc = pipe.recvcounts.view(P, P)
+        first = [s * (B // P) + min(s, B % P) for s in range(P + 1)]
+        for d in range(P):
+            for s in range(P):
+                assert int(rc[d, s]) == int(per_bag[d][first[s]:first[s + 1]].sum())
+        del owner
+    # bag sums: exact integers
+    for t in range(T):
+        vals = (ix[t * B * L:(t + 1) * B * L] % rows[t] % 7).to(torch.float32).view(B, L).sum(1)   # row value is row % 7 (+ column)
+        want = vals[:, None] + L * torch.arange(D, device=dev, dtype=torch.float32)[None, :]
+        assert torch.equal(out[:, t, :], want), f"table {t}"
