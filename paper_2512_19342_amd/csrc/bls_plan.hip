@@ -855,10 +855,17 @@ int bls_launch_plan(bls_ctx *ctx, const int64_t *idx, const int64_t *off, int64_
     // tiles of about a thousand lookups or more, going by the batch's mean bag length
     const int64_t mean = nnz / std::max<int64_t>(1, (int64_t)ctx->T * ctx->B) + 1;
     const int64_t n_max = ctx->B / ctx->P + (ctx->B % ctx->P ? 1 : 0);
-    // row-wise with few ranks: the placing workgroups add the counts up themselves, no scan launch
-    const bool own_scan = rowwise && ctx->P <= 8 && nnz < ((int64_t)1 << 32) && ctx->tune_plan_scan != 0;
+    // row-wise with few ranks and a count array small enough for every workgroup to read (with many
+    // tables the runs alone outnumber that): the placing workgroups add the counts up themselves, on
+    // fewer and larger tiles, and there is no scan launch
+    constexpr int64_t kOwnScanEntries = 16384;
+    bool own_scan = rowwise && ctx->P <= 8 && nnz < ((int64_t)1 << 32) && ctx->tune_plan_scan != 0;
     Tiles tg;
     tg.cb = rowwise ? bags_per_tile(ctx, 1024 / mean, own_scan ? 1024 : kTilesWanted) : 1u;
+    if (own_scan && count_entries(ctx, tg.cb) > kOwnScanEntries) {
+        own_scan = false;
+        tg.cb = bags_per_tile(ctx, 1024 / mean);
+    }
     tg.tiles = rowwise ? (uint32_t)((n_max + tg.cb - 1) / tg.cb) : 1u;
     const int64_t n = count_entries(ctx, tg.cb), nblk = scan_blocks(n);
     int64_t *C = (int64_t *)ws;                       // n counts

@@ -111,6 +111,7 @@ EDGE = [
     dict(P=3, T=2, D=4, B=600, part_kind=1, rows=[5000, 77], bag=("uniform", 0, 200)),       # tiles of several chunks, several tiles per run
     dict(P=2, T=1, D=4, B=128, part_kind=1, rows=[1000], bag=("fixed", 64)),                 # tiles of exactly one full chunk
     dict(P=9, T=3, D=4, B=400, part_kind=1, rows=[900, 10, 4000], bag=("uniform", 0, 30)),   # more than eight owners: two ranking passes
+    dict(P=8, T=300, D=4, B=64, part_kind=1, rows=[40] * 300, bag=("uniform", 0, 3)),        # 19200 tile counts over eight owners: too many for every workgroup to add up
 ]
 
 
