@@ -648,6 +648,29 @@ def main() -> int:
                  f"{control['equal_tables']['roofline']['achieved']:.0f} GB/s of algorithmic bytes")
             del fpipe, ftabs, fb
 
+    # the other end: the same bags over tables of sixteen rows each, which every compute unit's L1 holds whole.
+    # What the pooling kernel reaches there is the rate of the vector memory path for its load shape, measured:
+    # the ceiling that applies when popular rows are served by the caches.
+    if w.index_dist[0] == "zipf" and not args.timed_only and not args.no_uniform_control and plain:
+        wl = synth.workload(args.config, args.size)
+        wl.rows = [16] * w.T
+        ltabs = [synth.make_table(wl, t, dev) for t in range(wl.T)]
+        lb = [synth.make_batch(wl, it, dev) for it in range(min(args.batches, 8))]
+        ln = [int(off[-1].item()) for _, off in lb]
+        lpipe = Pipeline(wl, ltabs, max(ln))
+        lrun = timed_run(lb, ln, args.steps, args.warmup, lpipe, lpipe.new_out())
+        lsb = stage_bytes(wl, int(lrun["lookups"] / args.steps))
+        lms = lrun["stage_ms_stats"]["pool"]
+        roofline["l1_resident_control"] = {
+            "what": f"the same bags over {wl.T} tables of 16 rows: every row in every compute unit's L1",
+            "pool_ms": lms["mean"], "pool_ms_median": lms["median"], "pool_ms_min": lms["min"],
+            "achieved": lsb["pool"] / (lms["mean"] * 1e-3) / 1e9, "unit": "GB/s",
+        }
+        roofline["frac_of_l1_resident_rate"] = roofline["achieved"] / roofline["l1_resident_control"]["achieved"]
+        note(f"L1-resident control: pool {lms['mean']:.3f} ms = {roofline['l1_resident_control']['achieved']:.0f} GB/s of algorithmic bytes; "
+             f"the workload's pool runs at {roofline['frac_of_l1_resident_rate']:.2f} of that")
+        del lpipe, ltabs, lb
+
     res = {
         "metric": "embedding lookups/sec + achieved HBM GB/s (bucket+pool+pack), 1 MI355X",
         "value": lookups / dt, "unit": "lookups/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
