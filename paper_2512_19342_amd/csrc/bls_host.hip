@@ -237,7 +237,7 @@ namespace {
 constexpr size_t kFlagBytes = 16;
 
 struct BlobLayout {
-    size_t first, n_loc, nsum, rows, rps, t_q, q_t, q_d, q_base, q_rows, hot_n, hot_off, hot_rows, total;
+    size_t first, n_loc, nsum, rows, rps, t_q, q_t, q_d, q_base, q_rows, q_deal, hot_n, hot_off, hot_rows, total;
 };
 
 size_t put(size_t &at, size_t bytes)
@@ -262,6 +262,7 @@ BlobLayout blob_layout(const bls_ctx *c)
     L.q_d = put(at, Q * sizeof(int32_t));
     L.q_base = put(at, Q * sizeof(void *));
     L.q_rows = put(at, Q * sizeof(int64_t));
+    L.q_deal = put(at, Q * sizeof(int32_t));
     size_t hot = 0;
     for (const auto &h : c->q_hot) hot += h.size();
     L.hot_n = put(at, Q * sizeof(int32_t));
@@ -310,6 +311,19 @@ extern "C" int bls_commit(bls_ctx *ctx, void *d_desc, size_t bytes, void *hip_st
     fill(h, L.rows, ctx->rows); fill(h, L.rps, ctx->rps); fill(h, L.t_q, ctx->t_q);
     fill(h, L.q_t, ctx->q_t); fill(h, L.q_d, ctx->q_d); fill(h, L.q_base, ctx->q_base); fill(h, L.q_rows, ctx->q_rows);
     {
+        // The order in which a pooling launch over all shards deals them to the XCDs (position i goes to XCD
+        // i % 8 in round i / 8): by size, largest first, every other round backwards, so that no XCD collects
+        // the largest shard of every round - the large ones are those whose rows miss the caches.
+        std::vector<int32_t> by_size(ctx->Q), deal(ctx->Q);
+        for (int q = 0; q < ctx->Q; ++q) by_size[q] = q;
+        std::stable_sort(by_size.begin(), by_size.end(), [&](int32_t a, int32_t b) { return ctx->q_rows[a] > ctx->q_rows[b]; });
+        for (int i = 0; i < ctx->Q; ++i) {
+            const int round = i / 8, j = i % 8, in_round = std::min(8, ctx->Q - round * 8);
+            deal[round * 8 + (round % 2 ? in_round - 1 - j : j)] = by_size[i];
+        }
+        fill(h, L.q_deal, deal);
+    }
+    {
         std::vector<int32_t> hn(ctx->Q, 0), ho(ctx->Q, 0);
         size_t at = 0;
         for (int q = 0; q < ctx->Q; ++q) {
@@ -337,6 +351,7 @@ extern "C" int bls_commit(bls_ctx *ctx, void *d_desc, size_t bytes, void *hip_st
     d.rows = (const int64_t *)(b + L.rows); d.rps = (const int64_t *)(b + L.rps); d.t_q = (const int32_t *)(b + L.t_q);
     d.q_t = (const int32_t *)(b + L.q_t); d.q_d = (const int32_t *)(b + L.q_d);
     d.q_base = (const void *const *)(b + L.q_base); d.q_rows = (const int64_t *)(b + L.q_rows);
+    d.q_deal = (const int32_t *)(b + L.q_deal);
     d.hot_n = (const int32_t *)(b + L.hot_n); d.hot_off = (const int32_t *)(b + L.hot_off);
     d.hot_rows = (const uint32_t *)(b + L.hot_rows);
     ctx->dirty = false;

@@ -34,6 +34,7 @@ struct DevDesc {
     const int32_t *q_d;          // [Q]
     const void *const *q_base;   // [Q] shard storage
     const int64_t *q_rows;       // [Q] rows in the shard
+    const int32_t *q_deal;       // [Q] the shards in the order a pooling launch over all of them deals them to the XCDs
     const int32_t *hot_n;        // [Q] popular rows named for the shard (bls_set_hot_rows), 0 if none
     const int32_t *hot_off;      // [Q] where the shard's list starts in hot_rows
     const uint32_t *hot_rows;    // the lists, local row numbers, most popular first

@@ -309,14 +309,16 @@ __global__ __launch_bounds__(kThreads) void pool_stream(DevDesc dd, const int64_
 {
     // wgx = 0: grid y = q.  Otherwise a flat grid dealt out so that the workgroups an XCD receives
     // (every eighth one) all belong to the same few tables: q = 8 * (round of tables) + XCD.
-    // Only the (owner, table) pairs q0 .. q0+qn-1 are worked on (all of them, or one owner's).
+    // Only the (owner, table) pairs q0 .. q0+qn-1 are worked on (all of them, or one owner's); all of them
+    // are taken in the order dd.q_deal, which spreads the large shards evenly over the XCDs.
     uint32_t bx = blockIdx.x;
     int q = q0 + blockIdx.y;
     if (wgx) {
         const uint32_t xcd = blockIdx.x & 7u, r = blockIdx.x >> 3;
-        q = q0 + (int)((r / wgx) * 8u + xcd);
+        const int pos = (int)((r / wgx) * 8u + xcd);
         bx = r % wgx;
-        if (q >= q0 + qn) return;
+        if (pos >= qn) return;
+        q = qn == dd.Q ? dd.q_deal[pos] : q0 + pos;           // all shards: in the balanced order
     }
     const HotRows none{nullptr, nullptr, nullptr, 0};
     stream_group<G, DT, VB, U, WIDE, WGT, false>(dd, q, bx * (kThreads / G) + threadIdx.x / G, ridx, rw, segoff, nnz, Y, to_slot,
