@@ -312,14 +312,20 @@ extern "C" int bls_commit(bls_ctx *ctx, void *d_desc, size_t bytes, void *hip_st
     fill(h, L.q_t, ctx->q_t); fill(h, L.q_d, ctx->q_d); fill(h, L.q_base, ctx->q_base); fill(h, L.q_rows, ctx->q_rows);
     {
         // The order in which a pooling launch over all shards deals them to the XCDs (position i goes to XCD
-        // i % 8 in round i / 8): by size, largest first, every other round backwards, so that no XCD collects
-        // the largest shard of every round - the large ones are those whose rows miss the caches.
+        // i % 8 in round i / 8).  By size, largest first, every other round backwards, so that no XCD collects
+        // the largest shard of every round (the large ones are those whose rows miss the caches); and every XCD
+        // starts at another place of its list, so that the XCDs are not all at their largest shard at once.
         std::vector<int32_t> by_size(ctx->Q), deal(ctx->Q);
         for (int q = 0; q < ctx->Q; ++q) by_size[q] = q;
         std::stable_sort(by_size.begin(), by_size.end(), [&](int32_t a, int32_t b) { return ctx->q_rows[a] > ctx->q_rows[b]; });
+        std::vector<std::vector<int32_t>> mine(8);
         for (int i = 0; i < ctx->Q; ++i) {
             const int round = i / 8, j = i % 8, in_round = std::min(8, ctx->Q - round * 8);
-            deal[round * 8 + (round % 2 ? in_round - 1 - j : j)] = by_size[i];
+            mine[round % 2 ? in_round - 1 - j : j].push_back(by_size[i]);
+        }
+        for (int x = 0; x < 8; ++x) {
+            const int n = (int)mine[x].size();
+            for (int k = 0; k < n; ++k) deal[k * 8 + x] = mine[x][(k + x) % n];
         }
         fill(h, L.q_deal, deal);
     }
