@@ -135,11 +135,12 @@ int bls_set_hot_rows(bls_ctx *ctx, int32_t t, int32_t rank, const int64_t *rows,
 int bls_set_pool_tuning(bls_ctx *ctx, int32_t lane_bytes, int32_t segments_per_group, int32_t xcd_map,
                         int32_t wide_positions);
 
-/* Form of bls_plan under a row-wise partition, for tests and experiments; results are the same
- * bit for bit.  scan_while_placing = 0: always three launches (count, scan, place).  -1 or 1: two
- * launches where the problem allows it (at most eight ranks, batches below 2^32 lookups): every
- * placing workgroup adds the tile counts up for itself instead of reading a scanned array.  A
- * table-wise partition always takes the three launches. */
+/* Form of bls_plan, for tests and experiments; results are the same bit for bit.
+ * scan_while_placing = 0: always three launches (count, scan, place).  -1 or 1: fewer where the
+ * problem allows it.  Table-wise with at most 2048 runs (pairs of an (owner, table) and a
+ * requester) and at most 2^22 lookups: one launch, every workgroup works the run starts out for
+ * itself from the offsets at the run edges.  Row-wise with at most eight ranks and batches below 2^32 lookups: two launches,
+ * every placing workgroup adds the tile counts up for itself instead of reading a scanned array. */
 int bls_set_plan_tuning(bls_ctx *ctx, int32_t scan_while_placing);
 
 /* Buffer sizes in bytes for a batch of at most max_nnz lookups: plan workspace, the

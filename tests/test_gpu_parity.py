@@ -217,9 +217,33 @@ def test_rowwise_plan_in_three_launches(spec, want_perm):
         assert np.array_equal(bits(g["Out"]), bits(ref["Out"]))
 
 
-@pytest.mark.parametrize("cfg", [3, 5])
+TABLEWISE_EDGE = [spec for spec in EDGE if spec["part_kind"] == 0]
+
+
+@pytest.mark.parametrize("spec", TABLEWISE_EDGE, ids=lambda s: f"P{s['P']}-T{s['T']}-B{s['B']}")
+def test_tablewise_plan_in_three_launches(spec):
+    """bls_plan takes one launch for a small table-wise batch (up to 2048 runs and 2^22 lookups: the default,
+    which every other test here runs); the three-launch form (count, scan, place) must give the same plan."""
+    w = synth.custom("edge3t", k=1, values="grid", seed=31, index_dist=("zipf", 1.1), **spec)
+    tabs = [synth.make_table(w, t) for t in range(w.T)]
+    batches = [synth.make_batch(w, it) for it in range(2)]
+    got, _ = run_gpu(w, tabs, batches, plan_scan=0)
+    check_against_oracle(w, tabs, batches, got)
+
+
+def test_tablewise_plan_with_more_runs_than_one_launch_takes():
+    """P * Q = 2112 runs: beyond what the one-launch form scans in LDS, so the three launches serve."""
+    w = synth.custom("manyruns", P=64, T=33, D=4, B=128, k=1, part_kind=0, rows=[50 + 3 * t for t in range(33)],
+                     values="grid", bag=("uniform", 0, 4), seed=41)
+    tabs = [synth.make_table(w, t) for t in range(w.T)]
+    batches = [synth.make_batch(w, it) for it in range(2)]
+    got, _ = run_gpu(w, tabs, batches)
+    check_against_oracle(w, tabs, batches, got)
+
+
+@pytest.mark.parametrize("cfg", [3, 4, 5, 6])
 @pytest.mark.parametrize("scan_while_placing", [0, 1])
-def test_rowwise_workloads_in_either_plan_form(cfg, scan_while_placing):
+def test_workloads_in_either_plan_form(cfg, scan_while_placing):
     w = synth.workload(cfg, "small")
     tabs = [synth.make_table(w, t) for t in range(w.T)]
     batches = [synth.make_batch(w, it) for it in range(3)]
