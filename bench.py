@@ -357,8 +357,8 @@ def lag_demo(args) -> int:
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--config", type=int, default=4, help="benchmark workload 1..6 (default 4, the target)")
     ap.add_argument("--size", default="full", choices=["full", "small"])
     ap.add_argument("--batches", type=int, default=16, help="distinct pre-generated batches, rotated")
@@ -602,6 +602,17 @@ def main() -> int:
     plain = args.size == "full" and not args.table_dtype and not args.bag_fixed and not args.rows_cap and not args.flat_rows and not args.hot_rows
     roofline = pool_roofline(sb["pool"], run["stage_ms_stats"]["pool"],
                              recorded_traffic(args.config, uniform=bool(args.index_dist)) if plain else None)
+
+    # the rows one batch touches at least once: what an infinite cache would still have to fetch
+    if not args.timed_only:
+        ix0, off0 = batches[0]
+        distinct = 0
+        for t in range(w.T):
+            distinct += int(torch.unique(ix0[int(off0[t * w.B]):int(off0[(t + 1) * w.B])]).numel())
+        row_bytes = w.row_bytes
+        roofline["distinct_rows_per_batch"] = distinct
+        roofline["compulsory_row_bytes"] = distinct * row_bytes
+        roofline["compulsory_over_row_bytes"] = distinct / max(1, nnzs[0])
 
     # cache-defeating control: the same tables and bag lengths with uniform indices, the same staged step
     control = None
