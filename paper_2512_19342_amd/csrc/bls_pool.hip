@@ -430,10 +430,12 @@ void launch_rows(const bls_ctx *ctx, const int64_t *ridx, const float *rw, const
     constexpr int UU = U < G ? U : G;
     const uint32_t per_block = kThreads / G;
     if constexpr (G >= 4) {
-        // segments per group: aim at a stream of about a hundred rows
+        // segments per group: aim at a stream of two to three hundred rows (the lane groups of a wavefront finish
+        // at different times, and the longer the streams the smaller the share of loads only one of them uses;
+        // much longer streams lose again)
         const int64_t mean = nnz / std::max<int64_t>(1, ctx->nseg) + 1;
         int nb = 1;
-        while (nb * 2 < G && nb * 2 <= 16 && nb * mean < 96) nb *= 2;
+        while (nb * 2 < G && nb * 2 <= 16 && nb * mean < 192) nb *= 2;
         if (ctx->tune_segs > 0) nb = ctx->tune_segs;
         nb = std::max(1, std::min(nb, G - 1));
         const int64_t n_max = ctx->B / ctx->P + (ctx->B % ctx->P ? 1 : 0);
