@@ -436,6 +436,10 @@ void launch_rows(const bls_ctx *ctx, const int64_t *ridx, const float *rw, const
         const int64_t mean = nnz / std::max<int64_t>(1, ctx->nseg) + 1;
         int nb = 1;
         while (nb * 2 < G && nb * 2 <= 16 && nb * mean < 192) nb *= 2;
+        // ... but a small batch takes shorter streams (down to some sixty rows) rather than fewer than two
+        // workgroups per compute unit
+        const int64_t room = 2 * (int64_t)std::max(ctx->compute_units, 1);
+        while (nb > 1 && nb * mean >= 64 && (int64_t)qn * ((ctx->B + nb - 1) / nb) < room * per_block) nb /= 2;
         if (ctx->tune_segs > 0) nb = ctx->tune_segs;
         nb = std::max(1, std::min(nb, G - 1));
         const int64_t n_max = ctx->B / ctx->P + (ctx->B % ctx->P ? 1 : 0);
