@@ -123,6 +123,12 @@ def test_partition_rule_hot_rows_and_tuning_without_gpu(B):
         with pytest.raises(B.BlsError) as e:
             c.bls_set_pool_tuning(**bad)
         assert e.value.code == B.BLS_EINVAL
+    for ok in (-1, 0, 1):
+        c.bls_set_plan_tuning(ok)
+    for bad in (-2, 2):
+        with pytest.raises(B.BlsError) as e:
+            c.bls_set_plan_tuning(bad)
+        assert e.value.code == B.BLS_EINVAL
     big = B.Context(P=8, T=4096, D=4, k=1, B=1 << 15, rows=[8] * 4096, table_owner=[0] * 4096, part_kind=B.BLS_ROW_WISE)
     assert big.bls_sizes(0)["plan_ws_bytes"] > (1 << 20)
     with pytest.raises(B.BlsError) as e:                   # refused before anything touches a GPU
