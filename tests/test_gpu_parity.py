@@ -807,12 +807,14 @@ def test_per_rank_weighted_and_mean(part_kind):
             assert np.array_equal(bits(out.cpu().numpy()), bits(ref)), (mean, it)
 
 
-def test_step_can_be_captured_in_a_graph_and_replayed():
+@pytest.mark.parametrize("cfg,size", [(2, "full"), (5, "small")], ids=["tablewise", "rowwise"])
+def test_step_can_be_captured_in_a_graph_and_replayed(cfg, size):
     """The whole staged step recorded once into a HIP graph (the calls allocate nothing and clear
     nothing with memsets) and replayed on new batches written into the same input buffers, with
-    eager work and synchronisations between the replays: every replay equals the oracle."""
+    eager work and synchronisations between the replays: every replay equals the oracle.  Both
+    partitions: the plan has a form of its own for each."""
     from paper_2512_19342_amd.runner import Pipeline
-    w = synth.workload(2)                                       # one index per bag: every batch has T*B lookups
+    w = synth.workload(cfg, size)                               # bags of a fixed length: every batch has the same number of lookups
     dev = torch.device("cuda:0")
     tabs_cpu = [synth.make_table(w, t) for t in range(w.T)]
     batches = [synth.make_batch(w, it) for it in range(4)]
